@@ -1,0 +1,223 @@
+"""CPU oracle for the quantized DiT linear layer (DiffPro, arXiv 2511.11446).
+
+TEST INFRASTRUCTURE ONLY.  The arithmetic lives in ``diffpro_oracle.c`` (plain
+scalar C); this module compiles it with gcc and exposes it on numpy arrays.
+Nothing here imports, links or calls the HIP library, and the HIP library never
+calls this.  Allowed callers: the test-suite, the smoke check, and the
+benchmark's ``cpu_baseline`` leg.
+
+Operations and the passages they follow:
+  daq               Step 3, eq. (4) with tau = block absmax (percentile -> 100)
+  gemm_i8           INT8 x INT8 -> INT32 GEMM (Step 3, Step 5, Section 6)
+  gemm_w4g128       the same GEMM on 4-bit group-128 weights (Step 2)
+  epilogue_w8/_w4   dequantization with per-channel / per-group weight scales
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "diffpro_oracle.c")
+_LIB = os.path.join(_HERE, "libdiffpro_oracle.so")
+CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-shared", "-fPIC", "-std=c11"]
+
+_lib = None
+
+
+def build(force=False):
+    """Compile the oracle with gcc (a second or two)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(["gcc", *CFLAGS, _SRC, "-o", tmp, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        L.orc_half_to_float.restype = ctypes.c_float
+        L.orc_half_to_float.argtypes = [ctypes.c_uint16]
+        L.orc_float_to_half.restype = ctypes.c_uint16
+        L.orc_float_to_half.argtypes = [ctypes.c_float]
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.dtype(dtype):
+        raise TypeError("expected %s, got %s" % (np.dtype(dtype), a.dtype))
+    return a
+
+
+def _f16bits(a):
+    """Accept float16 or uint16 arrays; hand the raw 16-bit patterns to C."""
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.float16:
+        return a.view(np.uint16)
+    return _c(a, np.uint16)
+
+
+def max_threads():
+    return int(lib().orc_max_threads())
+
+
+def half_to_float(bits):
+    bits = _c(bits, np.uint16)
+    out = np.empty(bits.shape, np.float32)
+    lib().orc_half_to_float_array(_p(bits), _p(out), ctypes.c_int64(bits.size))
+    return out
+
+
+def float_to_half(f):
+    f = _c(f, np.float32)
+    out = np.empty(f.shape, np.uint16)
+    lib().orc_float_to_half_array(_p(f), _p(out), ctypes.c_int64(f.size))
+    return out
+
+
+def daq(x, R, nthreads=1):
+    """x [M,K] float16 -> (codes int8 [M,K], alpha float32 [M/R])."""
+    xb = _f16bits(x)
+    M, K = xb.shape
+    q = np.empty((M, K), np.int8)
+    s = np.empty((M // R if R > 0 else 0,), np.float32)
+    rc = lib().orc_daq(_p(xb), ctypes.c_int64(M), ctypes.c_int64(K), ctypes.c_int64(R), _p(q), _p(s),
+                       ctypes.c_int(nthreads))
+    if rc:
+        raise ValueError("orc_daq rc=%d" % rc)
+    return q, s
+
+
+def gemm_i8(q, w, nthreads=1):
+    """q [M,K] int8, w [N,K] int8 -> acc int32 [M,N]."""
+    q = _c(q, np.int8)
+    w = _c(w, np.int8)
+    M, K = q.shape
+    N, K2 = w.shape
+    assert K == K2
+    acc = np.empty((M, N), np.int32)
+    rc = lib().orc_gemm_i8(_p(q), _p(w), ctypes.c_int64(M), ctypes.c_int64(N), ctypes.c_int64(K), _p(acc),
+                           ctypes.c_int(nthreads))
+    if rc:
+        raise ValueError("orc_gemm_i8 rc=%d" % rc)
+    return acc
+
+
+def pack_w4(w):
+    """w [N,K] int8 codes in [-8,7] -> packed uint8 [N,K/2]."""
+    w = _c(w, np.int8)
+    N, K = w.shape
+    out = np.empty((N, K // 2), np.uint8)
+    rc = lib().orc_pack_w4(_p(w), ctypes.c_int64(N), ctypes.c_int64(K), _p(out))
+    if rc:
+        raise ValueError("orc_pack_w4 rc=%d" % rc)
+    return out
+
+
+def unpack_w4(packed, K):
+    packed = _c(packed, np.uint8)
+    N = packed.shape[0]
+    assert packed.shape[1] * 2 == K
+    out = np.empty((N, K), np.int8)
+    rc = lib().orc_unpack_w4(_p(packed), ctypes.c_int64(N), ctypes.c_int64(K), _p(out))
+    if rc:
+        raise ValueError("orc_unpack_w4 rc=%d" % rc)
+    return out
+
+
+def gemm_w4g128(q, w4, nthreads=1):
+    """q [M,K] int8, w4 packed [N,K/2] -> partials int32 [M,K/128,N]."""
+    q = _c(q, np.int8)
+    w4 = _c(w4, np.uint8)
+    M, K = q.shape
+    N = w4.shape[0]
+    assert w4.shape[1] * 2 == K
+    P = np.empty((M, K // 128, N), np.int32)
+    rc = lib().orc_gemm_w4g128(_p(q), _p(w4), ctypes.c_int64(M), ctypes.c_int64(N), ctypes.c_int64(K), _p(P),
+                               ctypes.c_int(nthreads))
+    if rc:
+        raise ValueError("orc_gemm_w4g128 rc=%d" % rc)
+    return P
+
+
+def epilogue_w8(acc, s_a, R, s_w, bias):
+    """-> y float16 [M,N]."""
+    acc = _c(acc, np.int32)
+    s_a = _c(s_a, np.float32)
+    s_w = _c(s_w, np.float32)
+    M, N = acc.shape
+    assert s_a.size == M // R and s_w.size == N
+    b = None if bias is None else _f16bits(bias)
+    y = np.empty((M, N), np.uint16)
+    rc = lib().orc_epilogue_w8(_p(acc), _p(s_a), ctypes.c_int64(R), _p(s_w), _p(b), ctypes.c_int64(M),
+                               ctypes.c_int64(N), _p(y))
+    if rc:
+        raise ValueError("orc_epilogue_w8 rc=%d" % rc)
+    return y.view(np.float16)
+
+
+def epilogue_w4(P, s_a, R, s_w, bias):
+    """P [M,G,N] int32, s_w float16 [N,G] -> y float16 [M,N]."""
+    P = _c(P, np.int32)
+    s_a = _c(s_a, np.float32)
+    sw = _f16bits(s_w)
+    M, G, N = P.shape
+    assert sw.shape == (N, G) and s_a.size == M // R
+    b = None if bias is None else _f16bits(bias)
+    y = np.empty((M, N), np.uint16)
+    rc = lib().orc_epilogue_w4(_p(P), _p(s_a), ctypes.c_int64(R), _p(sw), _p(b), ctypes.c_int64(M),
+                               ctypes.c_int64(N), ctypes.c_int64(G), _p(y))
+    if rc:
+        raise ValueError("orc_epilogue_w4 rc=%d" % rc)
+    return y.view(np.float16)
+
+
+def qlinear_w8a8(x, R, w, s_w, bias, nthreads=1, want_debug=True):
+    """Whole layer.  Returns dict(y, q, s_a, acc)."""
+    xb = _f16bits(x)
+    w = _c(w, np.int8)
+    s_w = _c(s_w, np.float32)
+    M, K = xb.shape
+    N = w.shape[0]
+    assert w.shape[1] == K and s_w.size == N
+    b = None if bias is None else _f16bits(bias)
+    y = np.empty((M, N), np.uint16)
+    q = np.empty((M, K), np.int8) if want_debug else None
+    s_a = np.empty((M // R,), np.float32) if want_debug else None
+    acc = np.empty((M, N), np.int32) if want_debug else None
+    rc = lib().orc_qlinear_w8a8(_p(xb), ctypes.c_int64(M), ctypes.c_int64(K), ctypes.c_int64(R), _p(w), _p(s_w),
+                                _p(b), ctypes.c_int64(N), _p(y), _p(q), _p(s_a), _p(acc), ctypes.c_int(nthreads))
+    if rc:
+        raise ValueError("orc_qlinear_w8a8 rc=%d" % rc)
+    return dict(y=y.view(np.float16), q=q, s_a=s_a, acc=acc)
+
+
+def qlinear_w4a8(x, R, w4, s_w, bias, nthreads=1, want_debug=True):
+    """Whole layer on 4-bit group-128 weights.  Returns dict(y, q, s_a, P)."""
+    xb = _f16bits(x)
+    w4 = _c(w4, np.uint8)
+    sw = _f16bits(s_w)
+    M, K = xb.shape
+    N = w4.shape[0]
+    G = K // 128
+    assert w4.shape[1] * 2 == K and sw.shape == (N, G)
+    b = None if bias is None else _f16bits(bias)
+    y = np.empty((M, N), np.uint16)
+    q = np.empty((M, K), np.int8) if want_debug else None
+    s_a = np.empty((M // R,), np.float32) if want_debug else None
+    P = np.empty((M, G, N), np.int32) if want_debug else None
+    rc = lib().orc_qlinear_w4a8(_p(xb), ctypes.c_int64(M), ctypes.c_int64(K), ctypes.c_int64(R), _p(w4), _p(sw),
+                                _p(b), ctypes.c_int64(N), _p(y), _p(q), _p(s_a), _p(P), ctypes.c_int(nthreads))
+    if rc:
+        raise ValueError("orc_qlinear_w4a8 rc=%d" % rc)
+    return dict(y=y.view(np.float16), q=q, s_a=s_a, P=P)
