@@ -1,0 +1,197 @@
+/*
+ * diffpro_qlinear.h - C ABI of the MI355X (gfx950) quantized DiT linear layer
+ * of DiffPro (arXiv 2511.11446): dynamic activation quantization (DAQ) ->
+ * INT8 x INT8 -> INT32 GEMM -> dequantization + bias, and a runner that walks
+ * a per-layer {4,8}-bit weight plan.
+ *
+ * General rules
+ *   - Every pointer marked (device) is GPU memory owned by the caller; the
+ *     library reads inputs, writes outputs, never frees or keeps them past the
+ *     call (a plan keeps the weight/scale/bias pointers it was created with).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work on it and return without synchronizing.  Calls on
+ *     different streams may run concurrently if their buffers are disjoint.
+ *   - No call allocates device memory.  Scratch comes from the caller through
+ *     (workspace, workspace_bytes); the matching *_workspace_bytes() gives the
+ *     size.  workspace must be 256-byte aligned.
+ *   - Every call returns a ql_status.  All argument checks happen before the
+ *     first HIP call, so they behave the same on a machine without a GPU.
+ *   - Inputs are assumed finite; NaN/Inf activations give unspecified codes.
+ *   - Matrices are row-major and dense (row pitch = number of columns).
+ *   - Limits: 1 <= M, N, K; M*K, M*N and N*K below 2^31; K <= 133143
+ *     (so that K * 127 * 127 fits an int32); M % R == 0.
+ *     The fast (MFMA) kernels need K % 16 == 0 and 16-byte aligned x, q, w;
+ *     other shapes or alignments are served by slower generic kernels with the
+ *     same results.  4-bit weights need K % 128 == 0.
+ */
+#ifndef DIFFPRO_QLINEAR_H
+#define DIFFPRO_QLINEAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ql_status {
+    QL_OK = 0,
+    QL_ERR_NULL = 1,        /* a required pointer is NULL */
+    QL_ERR_SHAPE = 2,       /* a size is out of the limits above */
+    QL_ERR_ALIGN = 3,       /* workspace not 256-byte aligned, or a 2/4-byte typed pointer misaligned */
+    QL_ERR_UNSUPPORTED = 4, /* w_bits not in {4,8} or group not in {0,128} */
+    QL_ERR_WORKSPACE = 5,   /* workspace missing or too small */
+    QL_ERR_DEVICE = 6       /* a HIP call failed; see ql_last_device_error() */
+} ql_status;
+
+/* Human-readable name of a status code (static storage, host). */
+const char *ql_status_string(int status);
+
+/* The hipError_t of the most recent failed HIP call on this thread (0 if none). */
+int ql_last_device_error(void);
+
+/* Library version: major * 1000 + minor. */
+int ql_version(void);
+
+/* ------------------------------------------------------------------------
+ * DAQ: Step 3, eq. (4) with tau = the absolute maximum of the scale block
+ * (percentile p -> 100; the "per sample per timestep min max scales" of
+ * Section 2.3), b = 8, zero-point 0.
+ *   alpha_r = amax_r / 127            (1 if the block is all zero)
+ *   q[m,k]  = clamp(round_half_even(x[m,k] / alpha_r), -127, 127)
+ * A scale block r is R consecutive rows: R = 1 per token, R = tokens per image
+ * per sample, R = M per tensor.
+ *   x       (device) [M,K] fp16, in
+ *   q       (device) [M,K] int8, out
+ *   scales  (device) [M/R] fp32 alpha, out
+ *   workspace: needed only when R > 1 (daq_workspace_bytes)
+ * ---------------------------------------------------------------------- */
+size_t daq_workspace_bytes(int64_t M, int64_t K, int64_t R);
+
+int daq_quantize(const void *x, int64_t M, int64_t K, int64_t R,
+                 void *q, void *scales,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------
+ * Optional exports of the integer intermediates, for verification.  Any
+ * member may be NULL; the struct pointer itself may be NULL.  They are written
+ * by the same kernels that produce y.
+ *   q         (device) [M,K] int8 activation codes
+ *   a_scales  (device) [M/R] fp32 activation scales alpha
+ *   acc       (device) int32: [M,N] accumulators for 8-bit weights;
+ *             [M, K/128, N] per-group partial sums for 4-bit weights
+ * ---------------------------------------------------------------------- */
+typedef struct ql_debug {
+    void *q;
+    void *a_scales;
+    void *acc;
+} ql_debug;
+
+/* Scratch for one quantized linear on M rows of K inputs (codes + scales + block maxima). */
+size_t qlinear_workspace_bytes(int64_t M, int64_t K, int64_t R);
+
+/* ------------------------------------------------------------------------
+ * Quantized linear with 8-bit weights (Step 3 and Step 5: "every linear layer
+ * uses an INT8 x INT8 -> INT32 kernel with per-output-channel weight scales";
+ * Section 6 counts DAQ, requantization and dequantization in the latency):
+ *   q, alpha = DAQ(x, R)
+ *   acc[m,n] = sum_k q[m,k] * w[n,k]                       (int32)
+ *   y[m,n]   = fp16( float(acc) * alpha[m/R] * w_scale[n] + bias[n] )
+ * evaluated in fp32, left to right, round-to-nearest-even into fp16.
+ *   x        (device) [M,K] fp16
+ *   w        (device) [N,K] int8 codes in [-127,127], K contiguous
+ *   w_scale  (device) [N] fp32
+ *   bias     (device) [N] fp16, or NULL
+ *   y        (device) [M,N] fp16, out
+ * ---------------------------------------------------------------------- */
+int qlinear_w8a8(const void *x, int64_t M, int64_t K, int64_t R,
+                 const void *w, const void *w_scale, const void *bias, int64_t N,
+                 void *y, const ql_debug *dbg,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------
+ * Quantized linear with 4-bit group-128 weights (Step 2: integer weights with
+ * per-group scales; symmetric, zero-point 0, as in the ablation section):
+ *   P[m,g,n] = sum_{k in group g} q[m,k] * w4[n,k]          (int32, g = k/128)
+ *   f        = sum_g float(P[m,g,n]) * w_scale[n,g]         (fp32, g ascending)
+ *   y[m,n]   = fp16( f * alpha[m/R] + bias[n] )
+ *   w4       (device) [N, K/2] bytes, two's-complement nibbles in [-8,7].
+ *            Storage order: inside every run of 8 consecutive k (4 bytes),
+ *            byte j (0..3) holds k = 8b+j in its low nibble and k = 8b+4+j in
+ *            its high nibble.  ql_pack_w4_host() produces it.
+ *   w_scale  (device) [N, K/128] fp16
+ * ---------------------------------------------------------------------- */
+int qlinear_w4a8(const void *x, int64_t M, int64_t K, int64_t R,
+                 const void *w4, const void *w_scale, const void *bias, int64_t N,
+                 void *y, const ql_debug *dbg,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------
+ * The GEMM + dequantization stage alone, on codes a previous daq_quantize()
+ * produced (used to time the two stages separately).  Same formulas as above.
+ *   q         (device) [M,K] int8
+ *   a_scales  (device) [M/R] fp32
+ *   acc       (device) optional int32 export as in ql_debug, or NULL
+ * ---------------------------------------------------------------------- */
+int qgemm_w8a8(const void *q, const void *a_scales, int64_t M, int64_t K, int64_t R,
+               const void *w, const void *w_scale, const void *bias, int64_t N,
+               void *y, void *acc, void *stream);
+
+int qgemm_w4a8(const void *q, const void *a_scales, int64_t M, int64_t K, int64_t R,
+               const void *w4, const void *w_scale, const void *bias, int64_t N,
+               void *y, void *acc, void *stream);
+
+/* Host helper: pack int8 codes in [-8,7], [N,K] row-major (host), into the
+ * 4-bit storage order described at qlinear_w4a8 ([N,K/2] bytes, host).
+ * K % 8 == 0.  Returns QL_ERR_SHAPE for a code outside [-8,7]. */
+int ql_pack_w4_host(const int8_t *codes, int64_t N, int64_t K, uint8_t *packed);
+
+/* ------------------------------------------------------------------------
+ * Plan runner: Algorithm 2, Phase B ("wrap layers per the bit plan ... forward
+ * with quantized weights and activations") and Step 6, restricted to the
+ * quantized linears.  A plan is a list of layers, each with its own weight
+ * width; qlinear_plan_run enqueues DAQ + GEMM + epilogue for every layer in
+ * order on one stream.
+ * ---------------------------------------------------------------------- */
+typedef struct ql_layer_desc {
+    int64_t K;            /* input features */
+    int64_t N;            /* output features */
+    int32_t w_bits;       /* 8 or 4 */
+    int32_t group;        /* 0 = one scale per output channel (8-bit); 128 (4-bit) */
+    const void *w;        /* (device) int8 [N,K] or packed 4-bit [N,K/2] */
+    const void *w_scale;  /* (device) fp32 [N] (8-bit) or fp16 [N,K/128] (4-bit) */
+    const void *bias;     /* (device) fp16 [N] or NULL */
+} ql_layer_desc;
+
+typedef struct ql_plan ql_plan; /* opaque, host object owned by the library */
+
+/* Validates and copies the descriptors (host memory only; no device call).
+ * M_max bounds the rows of later runs. */
+int ql_plan_create(const ql_layer_desc *layers, int32_t n_layers, int64_t M_max, ql_plan **plan_out);
+void ql_plan_destroy(ql_plan *plan);
+int32_t ql_plan_num_layers(const ql_plan *plan);
+
+/* Scratch for a run on M rows (sized for the widest layer input). */
+size_t ql_plan_workspace_bytes(const ql_plan *plan, int64_t M, int64_t R);
+
+/* x_in[l] (device) [M, K_l] fp16 and y_out[l] (device) [M, N_l] fp16 for every
+ * layer l; the two pointer arrays themselves are host memory.  Layers run in
+ * order on `stream`, so y_out[l] may alias x_in[l+1]. */
+int qlinear_plan_run(const ql_plan *plan, const void *const *x_in, void *const *y_out,
+                     int64_t M, int64_t R,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------
+ * Tuning hooks (benchmark sweeps).  ql_set_gemm_variant(v) forces GEMM tile
+ * variant v for later calls from this process (-1 = choose by shape);
+ * ql_num_gemm_variants() gives the valid range; ql_gemm_variant_name(v) a
+ * short description.  Results do not depend on the variant.
+ * ---------------------------------------------------------------------- */
+int ql_set_gemm_variant(int variant);
+int ql_num_gemm_variants(void);
+const char *ql_gemm_variant_name(int variant);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DIFFPRO_QLINEAR_H */

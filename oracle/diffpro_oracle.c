@@ -22,7 +22,8 @@
  *   round = round-half-to-even; an all-zero block gets scale 1; the quotient
  *   v / alpha is one correctly rounded binary32 division; codes are clamped
  *   to [-127, 127]; the epilogue is evaluated in binary32 in the order
- *   written below, without fused multiply-add.
+ *   written below, where fmaf(a, b, c) is a*b+c with a single rounding and
+ *   every other operation rounds once.
  *
  * Build: gcc -O2 -ffp-contract=off -fno-fast-math -fopenmp -shared -fPIC.
  * Rows are independent, so the only parallelism is an OpenMP loop over rows
@@ -221,10 +222,11 @@ int orc_gemm_w4g128(const int8_t *q, const uint8_t *w4, int64_t M, int64_t N, in
 /* ------------------------------------------------------------------ */
 /* Dequantization epilogues (Section 6: "dequantization"; Step 5:      */
 /* per-output-channel weight scales).  binary32, one rounding per      */
-/* operation, in the order written.                                    */
-/*   W8:  y = f16( ((float(acc) * s_a[m/R]) * s_w[n]) + bias[n] )       */
-/*   W4:  f = 0; for g ascending: f = f + float(P[g]) * s_w[n,g]        */
-/*        y = f16( (f * s_a[m/R]) + bias[n] )                           */
+/* operation, in the order written; fma = fused multiply-add.          */
+/*   W8:  t = float(acc) * s_a[m/R]                                     */
+/*        y = f16( fma(t, s_w[n], bias[n]) )      [t * s_w[n] if no bias] */
+/*   W4:  f = 0; for g ascending: f = fma(float(P[g]), s_w[n,g], f)      */
+/*        y = f16( fma(f, s_a[m/R], bias[n]) )    [f * s_a if no bias]   */
 /*   bias == NULL means no bias term.                                  */
 /* ------------------------------------------------------------------ */
 int orc_epilogue_w8(const int32_t *acc, const float *s_a, int64_t R, const float *s_w,
@@ -233,10 +235,8 @@ int orc_epilogue_w8(const int32_t *acc, const float *s_a, int64_t R, const float
     if (M < 0 || N < 0 || R <= 0 || (M % R) != 0) return 1;
     for (int64_t m = 0; m < M; ++m)
         for (int64_t n = 0; n < N; ++n) {
-            float u = (float)acc[m * N + n];
-            u = u * s_a[m / R];
-            u = u * s_w[n];
-            if (bias) u = u + orc_half_to_float(bias[n]);
+            float t = (float)acc[m * N + n] * s_a[m / R];
+            float u = bias ? fmaf(t, s_w[n], orc_half_to_float(bias[n])) : t * s_w[n];
             y[m * N + n] = orc_float_to_half(u);
         }
     return 0;
@@ -249,12 +249,9 @@ int orc_epilogue_w4(const int32_t *P, const float *s_a, int64_t R, const uint16_
     for (int64_t m = 0; m < M; ++m)
         for (int64_t n = 0; n < N; ++n) {
             float f = 0.0f;
-            for (int64_t g = 0; g < G; ++g) {
-                float term = (float)P[(m * G + g) * N + n] * orc_half_to_float(s_w[n * G + g]);
-                f = f + term;
-            }
-            float u = f * s_a[m / R];
-            if (bias) u = u + orc_half_to_float(bias[n]);
+            for (int64_t g = 0; g < G; ++g)
+                f = fmaf((float)P[(m * G + g) * N + n], orc_half_to_float(s_w[n * G + g]), f);
+            float u = bias ? fmaf(f, s_a[m / R], orc_half_to_float(bias[n])) : f * s_a[m / R];
             y[m * N + n] = orc_float_to_half(u);
         }
     return 0;

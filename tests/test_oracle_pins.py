@@ -297,17 +297,21 @@ def test_epilogue_w8_scales_rows_columns_bias(orc):
     y = orc.epilogue_w8(acc, s_a, R, s_w, b)
     exact = acc.astype(np.float64) * np.repeat(s_a, R).astype(np.float64)[:, None] * s_w.astype(np.float64)[None, :] \
         + b.astype(np.float64)[None, :]
-    # three binary32 roundings then one binary16 rounding: within 2^-11 (1 + small) relative
+    # two binary32 roundings then one binary16 rounding: within 2^-11 (1 + small) relative
     assert np.all(np.abs(y.astype(np.float64) - exact) <= np.abs(exact) * (2.0 ** -11 + 2.0 ** -21) + 1e-12)
     # zero accumulators give exactly the bias; no bias gives exactly zero
     z = np.zeros((M, N), np.int32)
     assert np.array_equal(orc.epilogue_w8(z, s_a, R, s_w, b), np.repeat(b[None, :], M, 0))
     assert not orc.epilogue_w8(z, s_a, R, s_w, None).view(np.uint16).any()
-    # the same expression evaluated by numpy's binary32 arithmetic
+    # without a bias the expression is two binary32 products: numpy's binary32 arithmetic agrees bit for bit
     u = acc.astype(np.float32) * np.repeat(s_a, R)[:, None]
     u = u * s_w[None, :]
-    u = u + b.astype(np.float32)[None, :]
-    assert np.array_equal(y, u.astype(np.float16))
+    assert np.array_equal(orc.epilogue_w8(acc, s_a, R, s_w, None), u.astype(np.float16))
+    # with a bias the last step is one fused multiply-add: t*s_w is exact in binary64, so the binary64
+    # sum differs from the exact one by at most 2^-53 relative; allow the rare double-rounding flip
+    t = (acc.astype(np.float32) * np.repeat(s_a, R)[:, None]).astype(np.float64)
+    v = (t * s_w.astype(np.float64)[None, :] + b.astype(np.float64)[None, :]).astype(np.float32)
+    assert (y != v.astype(np.float16)).sum() <= 1
 
 
 def test_epilogue_w4_equal_power_of_two_groups_reduce_to_w8(orc):
