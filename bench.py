@@ -1,0 +1,248 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized DiT linear path (DAQ -> INT8 GEMM -> dequantization) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+One "step" = one pass of the whole hot path over one batch of synthetic input: every
+layer of the workload runs DAQ + GEMM + epilogue (fp16 in HBM -> fp16 in HBM) through
+qlinear_plan_run.  Prints ONE JSON line: effective INT8 TOPS (sum of 2*M*N*K over the
+layers / time), the roofline of the dominant kernel measured with events around its own
+launches, and the CPU oracle timed on the host cores on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workload  # noqa: E402
+
+INT8_PEAK_TOPS = 5033.0   # MI355X dense INT8 matrix peak (256 CUs x 2.4 GHz x 8192 op/clk)
+HBM_PEAK_GBS = 8000.0
+DEFAULT_WORKLOAD = "c2_block_w8a8_m2048"
+POOL = 4                  # distinct activation sets rotated over the steps (different drift sigma each)
+
+
+def build_layers(ql, torch, wl_name):
+    wl = workload.WORKLOADS[wl_name]
+    if wl["layers"] == "bit_plan":
+        descs = [(p["name"], p["K"], p["N"], p["bits"], p["block"]) for p in workload.bit_plan()]
+    else:
+        descs = [(n, k, o, b, 0) for (n, k, o, b) in wl["layers"]]
+    layers = []
+    for name, K, N, bits, blk in descs:
+        lw = workload.layer_weights(name, K, N, bits, wl_name, blk)
+        w = lw["w"] if bits == 8 else ql.ql_pack_w4_host(lw["w"])
+        layers.append(dict(name=name, K=K, N=N, bits=bits, w=torch.from_numpy(w).cuda(),
+                           w_scale=torch.from_numpy(lw["s_w"]).cuda(), bias=torch.from_numpy(lw["bias"]).cuda(),
+                           host=lw))
+    return wl, layers
+
+
+def build_inputs(ql, torch, wl_name, wl, layers):
+    """Per layer type one fp16 activation buffer per pool slot, drift sigma taken from the workload's schedule.
+    The MLP output layer (fc2) gets the GELU of the GPU's own fc1 output of the same slot."""
+    M, R = wl["M"], wl["R"]
+    steps = wl["steps"]
+    sig = workload.sigma_schedule(steps) if steps > 1 else np.array([1.0])
+    slots = [int(round(i * (len(sig) - 1) / max(POOL - 1, 1))) for i in range(POOL)] if steps > 1 else [0]
+    types = {}
+    for l in layers:
+        types.setdefault(l["name"], (l["K"], l["N"]))
+    pool = []
+    for s in slots:
+        x = {}
+        for name, (K, N) in types.items():
+            if name == "fc2" and "fc1" in types:
+                continue
+            x[name] = torch.from_numpy(workload.activations(M, K, wl_name, name, s, sigma=float(sig[s]))).cuda()
+        if "fc2" in types and "fc1" in types:
+            fc1 = next(l for l in layers if l["name"] == "fc1")
+            if fc1["bits"] == 8:
+                y1 = ql.qlinear_w8a8(x["fc1"], R, fc1["w"], fc1["w_scale"], fc1["bias"])
+            else:
+                y1 = ql.qlinear_w4a8(x["fc1"], R, fc1["w"], fc1["w_scale"], fc1["bias"])
+            x["fc2"] = torch.nn.functional.gelu(y1.float(), approximate="tanh").half()   # input preparation only
+            del y1
+        elif "fc2" in types:
+            K = types["fc2"][0]
+            x["fc2"] = torch.from_numpy(workload.gelu_tanh_f16(
+                workload.activations(M, K, wl_name, "fc2", s, sigma=float(sig[s])))).cuda()
+        pool.append(x)
+    return pool, [float(sig[s]) for s in slots]
+
+
+def cpu_baseline(wl_name, wl, layers, budget_rows=2048):
+    """The oracle as it stands, row-parallel over the host cores, on the first rows of the workload."""
+    import oracle
+    oracle.build()
+    M, R = wl["M"], wl["R"]
+    uniq = {}
+    for l in layers:
+        uniq.setdefault((l["name"], l["bits"]), l)
+    rows = min(M, budget_rows)
+    Rs = R if (R <= rows and rows % R == 0) else rows   # a scale block larger than the sample becomes the sample
+    threads = oracle.max_threads()
+    t_total, macs = 0.0, 0
+    for l in uniq.values():
+        x = workload.activations(rows, l["K"], wl_name, l["name"], "cpu")
+        lw = l["host"]
+        t0 = time.perf_counter()
+        if l["bits"] == 8:
+            oracle.qlinear_w8a8(x, Rs, lw["w"], lw["s_w"], lw["bias"], nthreads=threads, want_debug=False)
+        else:
+            oracle.qlinear_w4a8(x, Rs, oracle.pack_w4(lw["w"]), lw["s_w"], lw["bias"], nthreads=threads,
+                                want_debug=False)
+        t_total += time.perf_counter() - t0
+        macs += rows * l["K"] * l["N"]
+    return {"value": 2.0 * macs / t_total / 1e12, "unit": "TOPS", "cores": threads, "kind": "oracle",
+            "sample": "first %d of %d rows through %d distinct layers (%s), one pass, %.1f s" %
+                      (rows, M, len(uniq), ",".join("%s/w%d" % k for k in uniq), t_total),
+            "seconds": t_total}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(workload.WORKLOADS))
+    ap.add_argument("--variant", type=int, default=-1, help="force a GEMM tile variant (sweeps)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-breakdown", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (every GPU box here has one); --gpus %d is not supported. "
+              "The path shards by rows with no exchange; see DESIGN.md." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2511_11446_amd as ql
+    ql.lib()   # raises if the HIP library is not built: there is no fallback
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    ql.set_gemm_variant(args.variant)
+
+    wl, layers = build_layers(ql, torch, args.workload)
+    M, R = wl["M"], wl["R"]
+    big = M >= 8192
+    steps = args.steps if args.steps is not None else (wl["steps"] if wl["steps"] > 1 else (100 if not big else 20))
+    warmup = args.warmup if args.warmup is not None else (10 if not big else 3)
+    pool, sigmas = build_inputs(ql, torch, args.workload, wl, layers)
+    plan = ql.Plan([dict(K=l["K"], N=l["N"], bits=l["bits"], w=l["w"], w_scale=l["w_scale"], bias=l["bias"])
+                    for l in layers], M_max=M)
+    ws = ql.workspace(plan.workspace_bytes(M, R))
+    y_by_type = {}
+    for l in layers:
+        if l["name"] not in y_by_type:
+            y_by_type[l["name"]] = torch.empty((M, l["N"]), dtype=torch.float16, device="cuda")
+    import ctypes
+    L = len(layers)
+    xs_pool = [(ctypes.c_void_p * L)(*[slot[l["name"]].data_ptr() for l in layers]) for slot in pool]
+    ys = (ctypes.c_void_p * L)(*[y_by_type[l["name"]].data_ptr() for l in layers])
+    stream = torch.cuda.current_stream()
+    sptr = ctypes.c_void_p(stream.cuda_stream)
+    ops_per_step = sum(2.0 * M * l["N"] * l["K"] for l in layers)
+
+    for i in range(warmup):
+        plan.run_ptrs(xs_pool[i % len(pool)], ys, M, R, ws, sptr)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_wall0 = time.perf_counter()
+    e0.record(stream)
+    for i in range(steps):
+        plan.run_ptrs(xs_pool[i % len(pool)], ys, M, R, ws, sptr)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    t_wall = time.perf_counter() - t_wall0
+    ms = e0.elapsed_time(e1)
+    ms_per_step = ms / steps
+    tops = ops_per_step / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-kernel breakdown: the same layers, DAQ and GEMM launched separately with events around each
+    roofline = None
+    breakdown = {}
+    if not args.no_breakdown:
+        reps = max(3, min(steps, 20))
+        uniq = {}
+        for l in layers:
+            uniq.setdefault((l["name"], l["bits"]), l)
+        counts = {}
+        for l in layers:
+            counts[(l["name"], l["bits"])] = counts.get((l["name"], l["bits"]), 0) + 1
+        gemm_time, gemm_ops, gemm_n, daq_time, daq_bytes, daq_n = 0.0, 0.0, 0, 0.0, 0.0, 0
+        for key, l in uniq.items():
+            x = pool[0][l["name"]]
+            q = torch.empty((M, l["K"]), dtype=torch.int8, device="cuda")
+            sa = torch.empty((M // R,), dtype=torch.float32, device="cuda")
+            dws = ql.workspace(ql.daq_workspace_bytes(M, l["K"], R))
+            y = y_by_type[l["name"]]
+            gfn = ql.qgemm_w8a8 if l["bits"] == 8 else ql.qgemm_w4a8
+            evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(reps)]
+            for _ in range(2):
+                ql.daq_quantize(x, R, q, sa, dws)
+                gfn(q, sa, R, l["w"], l["w_scale"], l["bias"], y=y)
+            torch.cuda.synchronize()
+            for r in range(reps):
+                evs[r][0].record(stream)
+                ql.daq_quantize(x, R, q, sa, dws)
+                evs[r][1].record(stream)
+                gfn(q, sa, R, l["w"], l["w_scale"], l["bias"], y=y)
+                evs[r][2].record(stream)
+            torch.cuda.synchronize()
+            td = float(np.mean([evs[r][0].elapsed_time(evs[r][1]) for r in range(reps)])) * 1e-3
+            tg = float(np.mean([evs[r][1].elapsed_time(evs[r][2]) for r in range(reps)])) * 1e-3
+            ops = 2.0 * M * l["N"] * l["K"]
+            dbytes = 3.0 * M * l["K"] + 4.0 * (M // R)
+            breakdown["%s/w%d" % key] = {"daq_us": td * 1e6, "gemm_us": tg * 1e6, "gemm_tops": ops / tg / 1e12,
+                                          "daq_gbs": dbytes / td / 1e9, "launches_per_step": counts[key]}
+            gemm_time += tg * counts[key]
+            gemm_ops += ops * counts[key]
+            gemm_n += counts[key]
+            daq_time += td * counts[key]
+            daq_bytes += dbytes * counts[key]
+            daq_n += counts[key]
+        if gemm_time >= daq_time:
+            ach = gemm_ops / gemm_time / 1e12
+            roofline = {"bound": "mfma", "kernel": "qgemm_mfma (INT8 GEMM + dequantization), all layers of a step",
+                        "achieved": ach, "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": ach / INT8_PEAK_TOPS,
+                        "avg_launch_us": gemm_time / gemm_n * 1e6, "ops_per_launch": gemm_ops / gemm_n,
+                        "traffic": None}
+        else:
+            ach = daq_bytes / daq_time / 1e9
+            roofline = {"bound": "hbm", "kernel": "daq_rows (DAQ pass), all layers of a step", "achieved": ach,
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                        "avg_launch_us": daq_time / daq_n * 1e6, "bytes_per_launch": daq_bytes / daq_n,
+                        "traffic": None}
+        roofline["daq_hbm_gbs"] = daq_bytes / daq_time / 1e9
+        roofline["gemm_only_tops"] = gemm_ops / gemm_time / 1e12
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(args.workload, wl, layers)
+
+    out = {
+        "metric": "effective INT8 TOPS for DAQ+qlinear on DiT-XL/2 shapes (sum 2MNK / time, fp16 in -> fp16 out)",
+        "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "pct_int8_mfma_peak": 100.0 * tops / INT8_PEAK_TOPS,
+        "config": {"workload": args.workload, "M": M, "rows_per_scale": R, "layers": L,
+                   "w4_layers": sum(l["bits"] == 4 for l in layers), "activation_sets_rotated": len(pool),
+                   "sigmas": sigmas, "gemm_variant": args.variant},
+        "host_wall_ms_per_step": t_wall / steps * 1e3,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "breakdown": breakdown,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,270 @@
+"""Python binding of the MI355X quantized DiT linear layer (DiffPro, arXiv 2511.11446).
+
+Argument marshalling only: every step (DAQ, INT8 GEMM, dequantization, plan walk)
+runs inside ``libdiffpro_qlinear.so`` (hand-written HIP for gfx950) through the C
+ABI of ``include/diffpro_qlinear.h``.  PyTorch supplies device memory and the
+current stream, nothing else.  There is no CPU or PyTorch fallback: if the
+library is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdiffpro_qlinear.so")
+
+QL_OK = 0
+STATUS_NAMES = {0: "QL_OK", 1: "QL_ERR_NULL", 2: "QL_ERR_SHAPE", 3: "QL_ERR_ALIGN", 4: "QL_ERR_UNSUPPORTED",
+                5: "QL_ERR_WORKSPACE", 6: "QL_ERR_DEVICE"}
+
+# every symbol include/diffpro_qlinear.h declares
+EXPORTS = ("ql_status_string", "ql_last_device_error", "ql_version", "daq_workspace_bytes", "daq_quantize",
+           "qlinear_workspace_bytes", "qlinear_w8a8", "qlinear_w4a8", "qgemm_w8a8", "qgemm_w4a8",
+           "ql_pack_w4_host", "ql_plan_create", "ql_plan_destroy", "ql_plan_num_layers",
+           "ql_plan_workspace_bytes", "qlinear_plan_run", "ql_set_gemm_variant", "ql_num_gemm_variants",
+           "ql_gemm_variant_name")
+
+
+class QlError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        extra = ""
+        if status == 6:
+            extra = " (hipError %d)" % lib().ql_last_device_error()
+        super().__init__("%s failed: %s%s" % (where, STATUS_NAMES.get(status, status), extra))
+
+
+class ql_debug(ctypes.Structure):
+    _fields_ = [("q", ctypes.c_void_p), ("a_scales", ctypes.c_void_p), ("acc", ctypes.c_void_p)]
+
+
+class ql_layer_desc(ctypes.Structure):
+    _fields_ = [("K", ctypes.c_int64), ("N", ctypes.c_int64), ("w_bits", ctypes.c_int32), ("group", ctypes.c_int32),
+                ("w", ctypes.c_void_p), ("w_scale", ctypes.c_void_p), ("bias", ctypes.c_void_p)]
+
+
+_lib = None
+_i64, _vp, _sz, _int = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+
+
+def lib():
+    """Load the HIP library (built in-tree by ``python -m paper_2511_11446_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("%s is missing: build it with `python -m paper_2511_11446_amd.build` "
+                          "(there is no fallback path)" % LIB_PATH)
+    L = ctypes.CDLL(LIB_PATH)
+    L.ql_status_string.restype = ctypes.c_char_p
+    L.ql_status_string.argtypes = [_int]
+    L.ql_gemm_variant_name.restype = ctypes.c_char_p
+    L.ql_gemm_variant_name.argtypes = [_int]
+    L.daq_workspace_bytes.restype = _sz
+    L.daq_workspace_bytes.argtypes = [_i64, _i64, _i64]
+    L.qlinear_workspace_bytes.restype = _sz
+    L.qlinear_workspace_bytes.argtypes = [_i64, _i64, _i64]
+    L.daq_quantize.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _sz, _vp]
+    lin = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _i64, _vp, ctypes.POINTER(ql_debug), _vp, _sz, _vp]
+    L.qlinear_w8a8.argtypes = lin
+    L.qlinear_w4a8.argtypes = lin
+    gem = [_vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _vp]
+    L.qgemm_w8a8.argtypes = gem
+    L.qgemm_w4a8.argtypes = gem
+    L.ql_pack_w4_host.argtypes = [_vp, _i64, _i64, _vp]
+    L.ql_plan_create.argtypes = [ctypes.POINTER(ql_layer_desc), ctypes.c_int32, _i64, ctypes.POINTER(_vp)]
+    L.ql_plan_destroy.argtypes = [_vp]
+    L.ql_plan_destroy.restype = None
+    L.ql_plan_num_layers.argtypes = [_vp]
+    L.ql_plan_num_layers.restype = ctypes.c_int32
+    L.ql_plan_workspace_bytes.argtypes = [_vp, _i64, _i64]
+    L.ql_plan_workspace_bytes.restype = _sz
+    L.qlinear_plan_run.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _i64, _i64, _vp, _sz, _vp]
+    L.ql_set_gemm_variant.argtypes = [_int]
+    _lib = L
+    return L
+
+
+def _check(status, where):
+    if status != QL_OK:
+        raise QlError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _need(t, dtype, shape=None, name="tensor"):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or not t.is_contiguous() or t.dtype != dtype:
+        raise TypeError("%s must be a contiguous CUDA tensor of %s" % (name, dtype))
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s has shape %s, expected %s" % (name, tuple(t.shape), tuple(shape)))
+    return t
+
+
+def workspace(nbytes, device="cuda"):
+    """A 256-byte aligned scratch tensor of at least nbytes."""
+    import torch
+    return torch.empty((max(int(nbytes), 256),), dtype=torch.uint8, device=device)
+
+
+def daq_workspace_bytes(M, K, R):
+    return int(lib().daq_workspace_bytes(M, K, R))
+
+
+def qlinear_workspace_bytes(M, K, R):
+    return int(lib().qlinear_workspace_bytes(M, K, R))
+
+
+def daq_quantize(x, R, q=None, scales=None, ws=None, stream=None):
+    """x fp16 [M,K] -> (q int8 [M,K], scales fp32 [M/R])."""
+    import torch
+    _need(x, torch.float16, name="x")
+    M, K = x.shape
+    if q is None:
+        q = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    if scales is None:
+        scales = torch.empty((max(M // max(R, 1), 1),), dtype=torch.float32, device=x.device)
+    if ws is None and R > 1:
+        ws = workspace(daq_workspace_bytes(M, K, R), x.device)
+    rc = lib().daq_quantize(_ptr(x), M, K, R, _ptr(q), _ptr(scales), _ptr(ws), 0 if ws is None else ws.numel(),
+                            _stream(stream))
+    _check(rc, "daq_quantize")
+    return q, scales
+
+
+def _qlinear(fn_name, x, R, w, w_scale, bias, N, y, debug, ws, stream):
+    import torch
+    _need(x, torch.float16, name="x")
+    M, K = x.shape
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    if ws is None:
+        ws = workspace(qlinear_workspace_bytes(M, K, R), x.device)
+    dbg = None
+    out = {"y": y}
+    if debug:
+        G = K // 128
+        out["q"] = torch.empty((M, K), dtype=torch.int8, device=x.device)
+        out["s_a"] = torch.empty((M // R,), dtype=torch.float32, device=x.device)
+        shape = (M, N) if fn_name == "qlinear_w8a8" else (M, G, N)
+        out["acc" if fn_name == "qlinear_w8a8" else "P"] = acc = torch.empty(shape, dtype=torch.int32, device=x.device)
+        dbg = ctypes.pointer(ql_debug(out["q"].data_ptr(), out["s_a"].data_ptr(), acc.data_ptr()))
+    rc = getattr(lib(), fn_name)(_ptr(x), M, K, R, _ptr(w), _ptr(w_scale), _ptr(bias), N, _ptr(y), dbg, _ptr(ws),
+                                 ws.numel(), _stream(stream))
+    _check(rc, fn_name)
+    return out if debug else y
+
+
+def qlinear_w8a8(x, R, w, w_scale, bias=None, y=None, debug=False, ws=None, stream=None):
+    """DAQ + INT8 GEMM + dequantization.  w int8 [N,K], w_scale fp32 [N], bias fp16 [N] or None."""
+    import torch
+    _need(w, torch.int8, name="w")
+    _need(w_scale, torch.float32, (w.shape[0],), "w_scale")
+    if bias is not None:
+        _need(bias, torch.float16, (w.shape[0],), "bias")
+    if w.shape[1] != x.shape[1]:
+        raise ValueError("w must be [N,K]")
+    return _qlinear("qlinear_w8a8", x, R, w, w_scale, bias, w.shape[0], y, debug, ws, stream)
+
+
+def qlinear_w4a8(x, R, w4, w_scale, bias=None, y=None, debug=False, ws=None, stream=None):
+    """Same with packed 4-bit weights: w4 uint8 [N,K/2], w_scale fp16 [N,K/128]."""
+    import torch
+    _need(w4, torch.uint8, name="w4")
+    K = x.shape[1]
+    if w4.shape[1] * 2 != K:
+        raise ValueError("w4 must be [N,K/2]")
+    _need(w_scale, torch.float16, (w4.shape[0], K // 128), "w_scale")
+    if bias is not None:
+        _need(bias, torch.float16, (w4.shape[0],), "bias")
+    return _qlinear("qlinear_w4a8", x, R, w4, w_scale, bias, w4.shape[0], y, debug, ws, stream)
+
+
+def _qgemm(fn_name, q, a_scales, R, w, w_scale, bias, N, y, acc, stream):
+    import torch
+    _need(q, torch.int8, name="q")
+    _need(a_scales, torch.float32, name="a_scales")
+    M, K = q.shape
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=q.device)
+    rc = getattr(lib(), fn_name)(_ptr(q), _ptr(a_scales), M, K, R, _ptr(w), _ptr(w_scale), _ptr(bias), N, _ptr(y),
+                                 _ptr(acc), _stream(stream))
+    _check(rc, fn_name)
+    return y
+
+
+def qgemm_w8a8(q, a_scales, R, w, w_scale, bias=None, y=None, acc=None, stream=None):
+    return _qgemm("qgemm_w8a8", q, a_scales, R, w, w_scale, bias, w.shape[0], y, acc, stream)
+
+
+def qgemm_w4a8(q, a_scales, R, w4, w_scale, bias=None, y=None, acc=None, stream=None):
+    return _qgemm("qgemm_w4a8", q, a_scales, R, w4, w_scale, bias, w4.shape[0], y, acc, stream)
+
+
+def ql_pack_w4_host(codes):
+    """numpy int8 [N,K] in [-8,7] -> numpy uint8 [N,K/2] in the library's 4-bit storage order."""
+    import numpy as np
+    codes = np.ascontiguousarray(codes, dtype=np.int8)
+    N, K = codes.shape
+    out = np.empty((N, K // 2), np.uint8)
+    rc = lib().ql_pack_w4_host(codes.ctypes.data_as(_vp), N, K, out.ctypes.data_as(_vp))
+    _check(rc, "ql_pack_w4_host")
+    return out
+
+
+class Plan:
+    """A per-layer weight-bit plan (Algorithm 2, Phase B): list of dicts(K, N, bits, w, w_scale, bias) of CUDA tensors."""
+
+    def __init__(self, layers, M_max):
+        self._keep = layers  # the plan stores raw pointers: keep the tensors alive
+        arr = (ql_layer_desc * len(layers))()
+        for i, l in enumerate(layers):
+            arr[i] = ql_layer_desc(l["K"], l["N"], l["bits"], 128 if l["bits"] == 4 else 0, l["w"].data_ptr(),
+                                   l["w_scale"].data_ptr(), 0 if l.get("bias") is None else l["bias"].data_ptr())
+        h = _vp()
+        _check(lib().ql_plan_create(arr, len(layers), M_max, ctypes.byref(h)), "ql_plan_create")
+        self.handle = h
+        self.L = len(layers)
+        self.M_max = M_max
+
+    def workspace_bytes(self, M, R):
+        return int(lib().ql_plan_workspace_bytes(self.handle, M, R))
+
+    def run(self, x_in, y_out, M, R, ws, stream=None):
+        """x_in / y_out: lists of L CUDA tensors ([M,K_l] fp16 / [M,N_l] fp16)."""
+        xs = (_vp * self.L)(*[t.data_ptr() for t in x_in])
+        ys = (_vp * self.L)(*[t.data_ptr() for t in y_out])
+        _check(lib().qlinear_plan_run(self.handle, xs, ys, M, R, _ptr(ws), ws.numel(), _stream(stream)),
+               "qlinear_plan_run")
+
+    def run_ptrs(self, xs, ys, M, R, ws, stream_ptr):
+        """Same with pre-marshalled pointer arrays (keeps Python out of a timed loop)."""
+        _check(lib().qlinear_plan_run(self.handle, xs, ys, M, R, _ptr(ws), ws.numel(), stream_ptr), "qlinear_plan_run")
+
+    def close(self):
+        if self.handle:
+            lib().ql_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def set_gemm_variant(v):
+    _check(lib().ql_set_gemm_variant(v), "ql_set_gemm_variant")
+
+
+def gemm_variants():
+    L = lib()
+    return [L.ql_gemm_variant_name(i).decode() for i in range(L.ql_num_gemm_variants())]

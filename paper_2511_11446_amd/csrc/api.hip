@@ -1,0 +1,317 @@
+// Host side of the C ABI declared in include/diffpro_qlinear.h: argument
+// validation (always before the first HIP call), workspace carving, kernel
+// dispatch, and the plan runner (Algorithm 2, Phase B restricted to the
+// quantized linears).
+#include "../../include/diffpro_qlinear.h"
+#include "ql_internal.h"
+
+#include <atomic>
+#include <new>
+#include <vector>
+
+namespace {
+
+thread_local int g_last_device_error = 0;
+std::atomic<int> g_gemm_variant{-1};
+
+constexpr int64_t K_MAX = 133143;          // 133143 * 127 * 127 < 2^31
+constexpr int64_t ELEMS_MAX = 2147483647;  // int32 indexing inside the kernels
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int device_status(hipError_t e)
+{
+    if (e == hipSuccess) return QL_OK;
+    g_last_device_error = (int)e;
+    return QL_ERR_DEVICE;
+}
+
+int check_shape(int64_t M, int64_t K, int64_t R, int64_t N)
+{
+    if (M < 1 || K < 1 || N < 1 || R < 1) return QL_ERR_SHAPE;
+    if (K > K_MAX || M % R != 0) return QL_ERR_SHAPE;
+    if (M > ELEMS_MAX / K || M > ELEMS_MAX / N || N > ELEMS_MAX / K) return QL_ERR_SHAPE;
+    return QL_OK;
+}
+
+inline bool misaligned(const void *p, size_t a) { return p && ((uintptr_t)p % a) != 0; }
+
+// workspace layout of one layer: [codes M*K][scales M/R][block maxima M/R (R > 1)]
+struct LayerWs {
+    size_t q_off, s_off, bm_off, total;
+};
+
+LayerWs layer_ws(int64_t M, int64_t K, int64_t R)
+{
+    LayerWs w;
+    w.q_off = 0;
+    w.s_off = align_up((size_t)(M * K), 256);
+    w.bm_off = w.s_off + align_up((size_t)(M / R) * 4, 256);
+    w.total = w.bm_off + (R > 1 ? align_up((size_t)(M / R) * 4, 256) : 0);
+    return w;
+}
+
+int check_workspace(void *ws, size_t have, size_t need)
+{
+    if (need == 0) return QL_OK;
+    if (!ws || have < need) return QL_ERR_WORKSPACE;
+    if ((uintptr_t)ws % 256 != 0) return QL_ERR_ALIGN;
+    return QL_OK;
+}
+
+// DAQ then GEMM for one layer; all arguments already validated
+int run_layer(const void *x, int64_t M, int64_t K, int64_t R, int w_bits, const void *w, const void *w_scale,
+              const void *bias, int64_t N, void *y, const ql_debug *dbg, void *workspace, hipStream_t stream)
+{
+    const LayerWs lw = layer_ws(M, K, R);
+    unsigned char *base = static_cast<unsigned char *>(workspace);
+    ql::DaqArgs d;
+    d.x = x;
+    d.q = (dbg && dbg->q) ? static_cast<int8_t *>(dbg->q) : reinterpret_cast<int8_t *>(base + lw.q_off);
+    d.scales = (dbg && dbg->a_scales) ? static_cast<float *>(dbg->a_scales) : reinterpret_cast<float *>(base + lw.s_off);
+    d.blockmax = R > 1 ? reinterpret_cast<unsigned *>(base + lw.bm_off) : nullptr;
+    d.M = (int)M;
+    d.K = (int)K;
+    d.R = (int)R;
+    int rc = device_status(ql::launch_daq(d, stream));
+    if (rc) return rc;
+    ql::GemmArgs g;
+    g.q = d.q;
+    g.s_a = d.scales;
+    g.w = w;
+    g.s_w = w_scale;
+    g.bias = bias;
+    g.y = y;
+    g.acc_out = dbg ? static_cast<int32_t *>(dbg->acc) : nullptr;
+    g.M = (int)M;
+    g.N = (int)N;
+    g.K = (int)K;
+    g.R = (int)R;
+    g.w_bits = w_bits;
+    return device_status(ql::launch_qgemm(g, g_gemm_variant.load(), stream));
+}
+
+int check_layer_ptrs(const void *x, const void *w, const void *w_scale, const void *bias, const void *y,
+                     const ql_debug *dbg, int w_bits)
+{
+    if (!x || !w || !w_scale || !y) return QL_ERR_NULL;
+    if (misaligned(x, 2) || misaligned(y, 2) || misaligned(bias, 2)) return QL_ERR_ALIGN;
+    if (misaligned(w_scale, w_bits == 8 ? 4 : 2)) return QL_ERR_ALIGN;
+    if (dbg && (misaligned(dbg->a_scales, 4) || misaligned(dbg->acc, 4))) return QL_ERR_ALIGN;
+    return QL_OK;
+}
+
+int qlinear_any(int w_bits, const void *x, int64_t M, int64_t K, int64_t R, const void *w, const void *w_scale,
+                const void *bias, int64_t N, void *y, const ql_debug *dbg, void *workspace, size_t workspace_bytes,
+                void *stream)
+{
+    int rc = check_layer_ptrs(x, w, w_scale, bias, y, dbg, w_bits);
+    if (rc) return rc;
+    rc = check_shape(M, K, R, N);
+    if (rc) return rc;
+    if (w_bits == 4 && K % 128 != 0) return QL_ERR_SHAPE;
+    if (w_bits == 4 && M > ELEMS_MAX / N / (K / 128) && dbg && dbg->acc) return QL_ERR_SHAPE;
+    rc = check_workspace(workspace, workspace_bytes, layer_ws(M, K, R).total);
+    if (rc) return rc;
+    return run_layer(x, M, K, R, w_bits, w, w_scale, bias, N, y, dbg, workspace, static_cast<hipStream_t>(stream));
+}
+
+int qgemm_any(int w_bits, const void *q, const void *a_scales, int64_t M, int64_t K, int64_t R, const void *w,
+              const void *w_scale, const void *bias, int64_t N, void *y, void *acc, void *stream)
+{
+    if (!q || !a_scales || !w || !w_scale || !y) return QL_ERR_NULL;
+    if (misaligned(a_scales, 4) || misaligned(y, 2) || misaligned(bias, 2) || misaligned(acc, 4) ||
+        misaligned(w_scale, w_bits == 8 ? 4 : 2))
+        return QL_ERR_ALIGN;
+    int rc = check_shape(M, K, R, N);
+    if (rc) return rc;
+    if (w_bits == 4 && K % 128 != 0) return QL_ERR_SHAPE;
+    if (w_bits == 4 && acc && M > ELEMS_MAX / N / (K / 128)) return QL_ERR_SHAPE;
+    ql::GemmArgs g;
+    g.q = static_cast<const int8_t *>(q);
+    g.s_a = static_cast<const float *>(a_scales);
+    g.w = w;
+    g.s_w = w_scale;
+    g.bias = bias;
+    g.y = y;
+    g.acc_out = static_cast<int32_t *>(acc);
+    g.M = (int)M;
+    g.N = (int)N;
+    g.K = (int)K;
+    g.R = (int)R;
+    g.w_bits = w_bits;
+    return device_status(ql::launch_qgemm(g, g_gemm_variant.load(), static_cast<hipStream_t>(stream)));
+}
+
+}  // namespace
+
+struct ql_plan {
+    std::vector<ql_layer_desc> layers;
+    int64_t M_max;
+    int64_t K_widest;
+};
+
+extern "C" {
+
+const char *ql_status_string(int status)
+{
+    switch (status) {
+        case QL_OK: return "QL_OK";
+        case QL_ERR_NULL: return "QL_ERR_NULL";
+        case QL_ERR_SHAPE: return "QL_ERR_SHAPE";
+        case QL_ERR_ALIGN: return "QL_ERR_ALIGN";
+        case QL_ERR_UNSUPPORTED: return "QL_ERR_UNSUPPORTED";
+        case QL_ERR_WORKSPACE: return "QL_ERR_WORKSPACE";
+        case QL_ERR_DEVICE: return "QL_ERR_DEVICE";
+        default: return "QL_ERR_?";
+    }
+}
+
+int ql_last_device_error(void) { return g_last_device_error; }
+
+int ql_version(void) { return 1000; }
+
+size_t daq_workspace_bytes(int64_t M, int64_t K, int64_t R)
+{
+    (void)K;
+    if (M < 1 || R <= 1 || M % R != 0) return 0;
+    return align_up((size_t)(M / R) * 4, 256);
+}
+
+int daq_quantize(const void *x, int64_t M, int64_t K, int64_t R, void *q, void *scales, void *workspace,
+                 size_t workspace_bytes, void *stream)
+{
+    if (!x || !q || !scales) return QL_ERR_NULL;
+    if (misaligned(x, 2) || misaligned(scales, 4)) return QL_ERR_ALIGN;
+    int rc = check_shape(M, K, R, 1);
+    if (rc) return rc;
+    rc = check_workspace(workspace, workspace_bytes, daq_workspace_bytes(M, K, R));
+    if (rc) return rc;
+    ql::DaqArgs d;
+    d.x = x;
+    d.q = static_cast<int8_t *>(q);
+    d.scales = static_cast<float *>(scales);
+    d.blockmax = R > 1 ? static_cast<unsigned *>(workspace) : nullptr;
+    d.M = (int)M;
+    d.K = (int)K;
+    d.R = (int)R;
+    return device_status(ql::launch_daq(d, static_cast<hipStream_t>(stream)));
+}
+
+size_t qlinear_workspace_bytes(int64_t M, int64_t K, int64_t R)
+{
+    if (M < 1 || K < 1 || R < 1 || M % R != 0) return 0;
+    return layer_ws(M, K, R).total;
+}
+
+int qlinear_w8a8(const void *x, int64_t M, int64_t K, int64_t R, const void *w, const void *w_scale,
+                 const void *bias, int64_t N, void *y, const ql_debug *dbg, void *workspace, size_t workspace_bytes,
+                 void *stream)
+{
+    return qlinear_any(8, x, M, K, R, w, w_scale, bias, N, y, dbg, workspace, workspace_bytes, stream);
+}
+
+int qlinear_w4a8(const void *x, int64_t M, int64_t K, int64_t R, const void *w4, const void *w_scale,
+                 const void *bias, int64_t N, void *y, const ql_debug *dbg, void *workspace, size_t workspace_bytes,
+                 void *stream)
+{
+    return qlinear_any(4, x, M, K, R, w4, w_scale, bias, N, y, dbg, workspace, workspace_bytes, stream);
+}
+
+int qgemm_w8a8(const void *q, const void *a_scales, int64_t M, int64_t K, int64_t R, const void *w,
+               const void *w_scale, const void *bias, int64_t N, void *y, void *acc, void *stream)
+{
+    return qgemm_any(8, q, a_scales, M, K, R, w, w_scale, bias, N, y, acc, stream);
+}
+
+int qgemm_w4a8(const void *q, const void *a_scales, int64_t M, int64_t K, int64_t R, const void *w4,
+               const void *w_scale, const void *bias, int64_t N, void *y, void *acc, void *stream)
+{
+    return qgemm_any(4, q, a_scales, M, K, R, w4, w_scale, bias, N, y, acc, stream);
+}
+
+int ql_pack_w4_host(const int8_t *codes, int64_t N, int64_t K, uint8_t *packed)
+{
+    if (!codes || !packed) return QL_ERR_NULL;
+    if (N < 1 || K < 1 || K % 8 != 0) return QL_ERR_SHAPE;
+    for (int64_t n = 0; n < N; ++n) {
+        const int8_t *src = codes + n * K;
+        uint8_t *dst = packed + n * (K / 2);
+        for (int64_t blk = 0; blk < K / 8; ++blk)
+            for (int j = 0; j < 4; ++j) {
+                const int lo = src[8 * blk + j], hi = src[8 * blk + 4 + j];
+                if (lo < -8 || lo > 7 || hi < -8 || hi > 7) return QL_ERR_SHAPE;
+                dst[4 * blk + j] = (uint8_t)((lo & 0xf) | ((hi & 0xf) << 4));
+            }
+    }
+    return QL_OK;
+}
+
+int ql_plan_create(const ql_layer_desc *layers, int32_t n_layers, int64_t M_max, ql_plan **plan_out)
+{
+    if (!layers || !plan_out) return QL_ERR_NULL;
+    *plan_out = nullptr;
+    if (n_layers < 1 || M_max < 1) return QL_ERR_SHAPE;
+    int64_t widest = 0;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const ql_layer_desc &d = layers[l];
+        if (d.w_bits != 8 && d.w_bits != 4) return QL_ERR_UNSUPPORTED;
+        if ((d.w_bits == 8 && d.group != 0) || (d.w_bits == 4 && d.group != 128)) return QL_ERR_UNSUPPORTED;
+        if (!d.w || !d.w_scale) return QL_ERR_NULL;
+        int rc = check_shape(M_max, d.K, 1, d.N);
+        if (rc) return rc;
+        if (d.w_bits == 4 && d.K % 128 != 0) return QL_ERR_SHAPE;
+        if (misaligned(d.w_scale, d.w_bits == 8 ? 4 : 2) || misaligned(d.bias, 2)) return QL_ERR_ALIGN;
+        widest = d.K > widest ? d.K : widest;
+    }
+    ql_plan *p = new (std::nothrow) ql_plan;
+    if (!p) return QL_ERR_WORKSPACE;
+    p->layers.assign(layers, layers + n_layers);
+    p->M_max = M_max;
+    p->K_widest = widest;
+    *plan_out = p;
+    return QL_OK;
+}
+
+void ql_plan_destroy(ql_plan *plan) { delete plan; }
+
+int32_t ql_plan_num_layers(const ql_plan *plan) { return plan ? (int32_t)plan->layers.size() : 0; }
+
+size_t ql_plan_workspace_bytes(const ql_plan *plan, int64_t M, int64_t R)
+{
+    if (!plan || M < 1 || R < 1 || M % R != 0 || M > plan->M_max) return 0;
+    return layer_ws(M, plan->K_widest, R).total;
+}
+
+int qlinear_plan_run(const ql_plan *plan, const void *const *x_in, void *const *y_out, int64_t M, int64_t R,
+                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!plan || !x_in || !y_out) return QL_ERR_NULL;
+    if (M < 1 || R < 1 || M % R != 0 || M > plan->M_max) return QL_ERR_SHAPE;
+    for (size_t l = 0; l < plan->layers.size(); ++l) {
+        if (!x_in[l] || !y_out[l]) return QL_ERR_NULL;
+        if (misaligned(x_in[l], 2) || misaligned(y_out[l], 2)) return QL_ERR_ALIGN;
+    }
+    int rc = check_workspace(workspace, workspace_bytes, ql_plan_workspace_bytes(plan, M, R));
+    if (rc) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (size_t l = 0; l < plan->layers.size(); ++l) {
+        const ql_layer_desc &d = plan->layers[l];
+        rc = run_layer(x_in[l], M, d.K, R, d.w_bits, d.w, d.w_scale, d.bias, d.N, y_out[l], nullptr, workspace, s);
+        if (rc) return rc;
+    }
+    return QL_OK;
+}
+
+int ql_set_gemm_variant(int variant)
+{
+    if (variant < -1 || variant > ql::num_gemm_variants()) return QL_ERR_UNSUPPORTED;
+    g_gemm_variant.store(variant);
+    return QL_OK;
+}
+
+int ql_num_gemm_variants(void) { return ql::num_gemm_variants(); }
+
+const char *ql_gemm_variant_name(int variant) { return ql::gemm_variant_name(variant); }
+
+}  // extern "C"

@@ -1,0 +1,361 @@
+// INT8 x INT8 -> INT32 GEMM with fused dequantization for gfx950 (CDNA4).
+//
+// The paper's linears are "INT8 x INT8 -> INT32 GEMMs" with per-output-channel
+// weight scales (Step 3, Step 5, Section 6) or per-group scales (Step 2).
+// Here: acc[m,n] = sum_k q[m,k] * w[n,k] on v_mfma_i32_32x32x32_i8, both
+// operands K-contiguous, tiles staged through LDS with a two-stage pipeline,
+// and the dequantization + bias + fp16 conversion applied to the accumulators
+// in registers.  4-bit weights are unpacked from nibbles to int8 (times 16) in
+// registers and every group of 128 k is folded into an fp32 sum with its scale.
+#include "ql_internal.h"
+
+#include <type_traits>
+
+namespace ql {
+
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int XCDS = 8;    // L2 domains of the chip; consecutive workgroup ids go round-robin over them
+constexpr int GROUP_M = 4; // tile rows walked together so that one L2 sees few distinct A and W panels
+
+__device__ __forceinline__ float half_to_float_dev(unsigned short h)
+{
+    return (float)__builtin_bit_cast(_Float16, h);
+}
+
+// Tile shape: a workgroup of WGM x WGN wavefronts, each owning TM x TN MFMA
+// tiles of 32x32, walks K in steps of BK int8.
+// WPS = wavefronts per SIMD the register budget must allow (512 / WPS registers per lane).
+template <int TM_, int TN_, int WGM_, int WGN_, int BK_, bool W4_, int WPS_>
+struct Tile {
+    static constexpr int TM = TM_, TN = TN_, WGM = WGM_, WGN = WGN_, BK = BK_, WPS = WPS_;
+    static constexpr bool W4 = W4_;
+    static constexpr int NT = WGM * WGN * 64;
+    static constexpr int BM = WGM * TM * 32;
+    static constexpr int BN = WGN * TN * 32;
+    static constexpr int BKB = W4 ? BK / 2 : BK;  // bytes of one B row per K step
+    static constexpr int LDA = BK + 16;            // LDS row pitch, padded against bank conflicts
+    static constexpr int LDB = BKB + 16;
+    static constexpr int A_ITERS = BM * BK / 16 / NT;
+    static constexpr int B_ITERS = BN * BKB / 16 / NT;
+    static constexpr int A_BYTES = BM * LDA;
+    static constexpr int B_BYTES = BN * LDB;
+    static constexpr int S_BYTES = W4 ? 2 * BN * 4 : 0;
+    static constexpr int LDS_BYTES = 2 * A_BYTES + 2 * B_BYTES + S_BYTES;
+    static_assert(BM * BK / 16 % NT == 0 && BN * BKB / 16 % NT == 0, "tile loads must divide over the threads");
+    static_assert(!W4 || BK == 128, "one K step is one 128-wide weight group");
+    static_assert(BM * 4 <= 2 * A_BYTES, "row-scale staging reuses the A buffers");
+};
+
+template <class T>
+__global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tiles_m, int tiles_n, int nblk_padded)
+{
+    constexpr int TM = T::TM, TN = T::TN, BK = T::BK, BM = T::BM, BN = T::BN, NT = T::NT;
+    constexpr int LDA = T::LDA, LDB = T::LDB, BKB = T::BKB;
+    constexpr bool W4 = T::W4;
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char *sA = smem;
+    unsigned char *sB = smem + 2 * T::A_BYTES;
+    float *sS = reinterpret_cast<float *>(sB + 2 * T::B_BYTES);
+
+    // ---- which tile: spread consecutive logical tiles inside one XCD, walk GROUP_M tile rows at a time
+    const int per_xcd = nblk_padded / XCDS;
+    const int logical = (blockIdx.x % XCDS) * per_xcd + blockIdx.x / XCDS;
+    if (logical >= tiles_m * tiles_n) return;
+    const int group_sz = GROUP_M * tiles_n;
+    const int first_m = (logical / group_sz) * GROUP_M;
+    const int gm = min(tiles_m - first_m, GROUP_M);
+    const int tile_m = first_m + (logical % group_sz) % gm;
+    const int tile_n = (logical % group_sz) / gm;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / T::WGN, wn = wave % T::WGN;
+    const int M = a.M, N = a.N, K = a.K;
+    const int KB = W4 ? K / 2 : K;  // bytes per weight row
+    const int G = K / 128;
+    const int nk = K / BK;  // the dispatcher only sends K % BK == 0 here
+
+    // ---- global -> register staging of one K step
+    v4i ga[T::A_ITERS], gb[T::B_ITERS];
+    float gs = 0.0f;
+    auto load_tile = [&](int kt) {
+        const int k0 = kt * BK;
+#pragma unroll
+        for (int i = 0; i < T::A_ITERS; ++i) {
+            const int c = tid + i * NT;
+            const int row = c / (BK / 16), cc = c % (BK / 16);
+            const int gr = min(m0 + row, M - 1);
+            ga[i] = *reinterpret_cast<const v4i *>(a.q + (size_t)gr * K + (k0 + cc * 16));
+        }
+        const int kb0 = W4 ? k0 / 2 : k0;
+#pragma unroll
+        for (int i = 0; i < T::B_ITERS; ++i) {
+            const int c = tid + i * NT;
+            const int row = c / (BKB / 16), cc = c % (BKB / 16);
+            const int gr = min(n0 + row, N - 1);
+            gb[i] = *reinterpret_cast<const v4i *>(static_cast<const unsigned char *>(a.w) + (size_t)gr * KB + (kb0 + cc * 16));
+        }
+        if (W4 && (k0 % 128) == 0 && tid < BN) {
+            const int gr = min(n0 + tid, N - 1);
+            // the nibbles are used as value*16, so the group scale carries the 1/16 (exact: a power of two)
+            gs = half_to_float_dev(static_cast<const unsigned short *>(a.s_w)[(size_t)gr * G + k0 / 128]) * 0.0625f;
+        }
+    };
+    auto store_tile = [&](int kt) {
+        unsigned char *dA = sA + (kt & 1) * T::A_BYTES;
+        unsigned char *dB = sB + (kt & 1) * T::B_BYTES;
+#pragma unroll
+        for (int i = 0; i < T::A_ITERS; ++i) {
+            const int c = tid + i * NT;
+            *reinterpret_cast<v4i *>(dA + (c / (BK / 16)) * LDA + (c % (BK / 16)) * 16) = ga[i];
+        }
+#pragma unroll
+        for (int i = 0; i < T::B_ITERS; ++i) {
+            const int c = tid + i * NT;
+            *reinterpret_cast<v4i *>(dB + (c / (BKB / 16)) * LDB + (c % (BKB / 16)) * 16) = gb[i];
+        }
+        if (W4 && ((kt * BK) % 128) == 0 && tid < BN) sS[(((kt * BK) / 128) & 1) * BN + tid] = gs;
+    };
+
+    v16i acc[TM][TN];
+    float fsum[W4 ? TM : 1][W4 ? TN : 1][16];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+            if (W4) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) fsum[i][j][r] = 0.0f;
+            }
+        }
+
+    // lane -> fragment: row (lane & 31) of a 32-row tile, k offset 16 * (lane >> 5) inside a 32-wide K slice
+    const int frag_row = lane & 31, frag_half = lane >> 5;
+    const int a_off = (wm * TM * 32 + frag_row) * LDA + frag_half * 16;
+    const int b_off = (wn * TN * 32 + frag_row) * LDB + frag_half * (W4 ? 8 : 16);
+
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+
+    for (int kt = 0; kt < nk; ++kt) {
+        if (kt + 1 < nk) load_tile(kt + 1);
+        const unsigned char *pa = sA + (kt & 1) * T::A_BYTES + a_off;
+        const unsigned char *pb = sB + (kt & 1) * T::B_BYTES + b_off;
+#pragma unroll
+        for (int ks = 0; ks < BK / 32; ++ks) {
+            v4i af[TM], bf[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const v4i *>(pa + i * 32 * LDA + ks * 32);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                if (W4) {
+                    const v2i p = *reinterpret_cast<const v2i *>(pb + j * 32 * LDB + ks * 16);
+                    // byte b of a packed word: low nibble = k b, high nibble = k 4+b  ->  int8 value * 16
+                    bf[j] = v4i{(int)(((unsigned)p[0] << 4) & 0xf0f0f0f0u), (int)((unsigned)p[0] & 0xf0f0f0f0u),
+                                (int)(((unsigned)p[1] << 4) & 0xf0f0f0f0u), (int)((unsigned)p[1] & 0xf0f0f0f0u)};
+                } else {
+                    bf[j] = *reinterpret_cast<const v4i *>(pb + j * 32 * LDB + ks * 32);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    // a weight group (= one K step) starts from a zero accumulator
+                    const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], (W4 && ks == 0) ? zero : acc[i][j], 0, 0, 0);
+                }
+        }
+        if (W4) {
+            // the weight group ends here: fold its int32 partial sums into the fp32 sum with the group scale
+            const int g = kt;
+            const float *sc = sS + (g & 1) * BN + wn * TN * 32 + frag_row;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const float s16 = sc[j * 32];
+                const int n = n0 + wn * TN * 32 + j * 32 + frag_row;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        if (a.acc_out) {
+                            const int m = m0 + wm * TM * 32 + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
+                            if (m < M && n < N) a.acc_out[(unsigned)((m * G + g) * N + n)] = acc[i][j][r] >> 4;
+                        }
+                        fsum[i][j][r] = __builtin_fmaf((float)acc[i][j][r], s16, fsum[i][j][r]);
+                    }
+            }
+        }
+        if (kt + 1 < nk) store_tile(kt + 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: activation scale per row (staged in LDS), weight scale and bias per column
+    float *sRow = reinterpret_cast<float *>(smem);
+    for (int t = tid; t < BM; t += NT) sRow[t] = a.s_a[min(m0 + t, M - 1) / a.R];
+    __syncthreads();
+    _Float16 *y = static_cast<_Float16 *>(a.y);
+    const unsigned short *bias = static_cast<const unsigned short *>(a.bias);
+    const bool full = (m0 + BM <= M) && (n0 + BN <= N);
+    auto emit = [&](auto edge) {
+        constexpr bool EDGE = decltype(edge)::value;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = n0 + wn * TN * 32 + j * 32 + frag_row;
+            const bool n_ok = !EDGE || n < N;
+            const float sw = (!W4 && n_ok) ? static_cast<const float *>(a.s_w)[n] : 1.0f;
+            const float b = (bias && n_ok) ? half_to_float_dev(bias[n]) : 0.0f;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = wm * TM * 32 + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
+                    const int m = m0 + row;
+                    if (!EDGE || (m < M && n_ok)) {
+                        const float sa = sRow[row];
+                        const unsigned off = (unsigned)(m * N + n);
+                        float u;
+                        if (W4) {
+                            u = bias ? __builtin_fmaf(fsum[i][j][r], sa, b) : fsum[i][j][r] * sa;
+                        } else {
+                            const float t = (float)acc[i][j][r] * sa;
+                            u = bias ? __builtin_fmaf(t, sw, b) : t * sw;
+                            if (a.acc_out) a.acc_out[off] = acc[i][j][r];
+                        }
+                        y[off] = (_Float16)u;
+                    }
+                }
+        }
+    };
+    if (full) emit(std::false_type{});
+    else emit(std::true_type{});
+}
+
+// Any shape, no alignment needs: one thread per output element.
+__global__ __launch_bounds__(256) void qgemm_naive(GemmArgs a)
+{
+    const int n = blockIdx.y * 64 + (threadIdx.x & 63);
+    const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (m >= a.M || n >= a.N) return;
+    const int K = a.K;
+    const float sa = a.s_a[m / a.R];
+    const unsigned short *bias = static_cast<const unsigned short *>(a.bias);
+    const float b = bias ? half_to_float_dev(bias[n]) : 0.0f;
+    const int8_t *q = a.q + (size_t)m * K;
+    float u;
+    if (a.w_bits == 8) {
+        const int8_t *w = static_cast<const int8_t *>(a.w) + (size_t)n * K;
+        int s = 0;
+        for (int k = 0; k < K; ++k) s += (int)q[k] * (int)w[k];
+        if (a.acc_out) a.acc_out[(size_t)m * a.N + n] = s;
+        const float t = (float)s * sa;
+        const float sw = static_cast<const float *>(a.s_w)[n];
+        u = bias ? __builtin_fmaf(t, sw, b) : t * sw;
+    } else {
+        const unsigned char *w = static_cast<const unsigned char *>(a.w) + (size_t)n * (K / 2);
+        const int G = K / 128;
+        float f = 0.0f;
+        for (int g = 0; g < G; ++g) {
+            int s = 0;
+            for (int k = 128 * g; k < 128 * g + 128; ++k) {
+                const unsigned byte = w[4 * (k / 8) + (k % 4)];
+                int v = (k % 8) >= 4 ? (int)(byte >> 4) : (int)(byte & 0xf);
+                v = v >= 8 ? v - 16 : v;
+                s += (int)q[k] * v;
+            }
+            if (a.acc_out) a.acc_out[((size_t)m * G + g) * a.N + n] = s;
+            f = __builtin_fmaf((float)s, half_to_float_dev(static_cast<const unsigned short *>(a.s_w)[(size_t)n * G + g]), f);
+        }
+        u = bias ? __builtin_fmaf(f, sa, b) : f * sa;
+    }
+    static_cast<_Float16 *>(a.y)[(size_t)m * a.N + n] = (_Float16)u;
+}
+
+// ---- variants -----------------------------------------------------------------
+template <class T>
+static hipError_t run_variant(const GemmArgs &a, hipStream_t s)
+{
+    static bool attr_set = false;  // per variant; LDS above 64 KB needs the opt-in once
+    if (!attr_set) {
+        if (T::LDS_BYTES > 64 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&qgemm_mfma<T>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+            if (e != hipSuccess) return e;
+        }
+        attr_set = true;
+    }
+    const int tiles_m = (a.M + T::BM - 1) / T::BM, tiles_n = (a.N + T::BN - 1) / T::BN;
+    const int nblk = tiles_m * tiles_n;
+    const int padded = (nblk + XCDS - 1) / XCDS * XCDS;
+    hipLaunchKernelGGL(qgemm_mfma<T>, dim3(padded), dim3(T::NT), T::LDS_BYTES, s, a, tiles_m, tiles_n, padded);
+    return hipGetLastError();
+}
+
+struct Variant {
+    const char *name;
+    int w_bits, BM, BN, BK;
+    hipError_t (*run)(const GemmArgs &, hipStream_t);
+};
+
+//                         TM TN WGM WGN BK  W4  WPS
+using W8_128x128_k64 = Tile<2, 2, 2, 2, 64, false, 2>;
+using W8_128x128_k128 = Tile<2, 2, 2, 2, 128, false, 2>;
+using W8_256x128_k64 = Tile<4, 2, 2, 2, 64, false, 2>;
+using W8_256x128_k128 = Tile<4, 2, 2, 2, 128, false, 2>;
+using W8_128x192_k64 = Tile<2, 3, 2, 2, 64, false, 2>;
+using W8_256x192_k64 = Tile<4, 3, 2, 2, 64, false, 1>;
+using W8_256x256_8w = Tile<4, 2, 2, 4, 64, false, 2>;
+using W8_64x64_k64 = Tile<1, 1, 2, 2, 64, false, 4>;
+using W8_128x128_k64_o3 = Tile<2, 2, 2, 2, 64, false, 3>;
+using W4_128x128_k128 = Tile<2, 2, 2, 2, 128, true, 2>;
+using W4_64x128_k128 = Tile<1, 2, 2, 2, 128, true, 2>;
+using W4_256x128_8w = Tile<2, 2, 4, 2, 128, true, 2>;
+using W4_128x64_k128 = Tile<2, 1, 2, 2, 128, true, 3>;
+
+static const Variant VARIANTS[] = {
+    {"w8 128x128 bk64 4w occ2", 8, 128, 128, 64, run_variant<W8_128x128_k64>},
+    {"w8 128x128 bk128 4w occ2", 8, 128, 128, 128, run_variant<W8_128x128_k128>},
+    {"w8 256x128 bk64 4w occ2", 8, 256, 128, 64, run_variant<W8_256x128_k64>},
+    {"w8 256x128 bk128 4w occ2", 8, 256, 128, 128, run_variant<W8_256x128_k128>},
+    {"w8 128x192 bk64 4w occ2", 8, 128, 192, 64, run_variant<W8_128x192_k64>},
+    {"w8 256x192 bk64 4w occ1", 8, 256, 192, 64, run_variant<W8_256x192_k64>},
+    {"w8 256x256 bk64 8w occ2", 8, 256, 256, 64, run_variant<W8_256x256_8w>},
+    {"w8 64x64 bk64 4w occ4", 8, 64, 64, 64, run_variant<W8_64x64_k64>},
+    {"w8 128x128 bk64 4w occ3", 8, 128, 128, 64, run_variant<W8_128x128_k64_o3>},
+    {"w4 128x128 bk128 4w occ2", 4, 128, 128, 128, run_variant<W4_128x128_k128>},
+    {"w4 64x128 bk128 4w occ2", 4, 64, 128, 128, run_variant<W4_64x128_k128>},
+    {"w4 256x128 bk128 8w occ2", 4, 256, 128, 128, run_variant<W4_256x128_8w>},
+    {"w4 128x64 bk128 4w occ3", 4, 128, 64, 128, run_variant<W4_128x64_k128>},
+};
+constexpr int NUM_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);
+
+int num_gemm_variants() { return NUM_VARIANTS; }
+const char *gemm_variant_name(int v) { return (v >= 0 && v < NUM_VARIANTS) ? VARIANTS[v].name : "naive (any shape)"; }
+
+static int choose_variant(const GemmArgs &a)
+{
+    if (a.w_bits == 8) return a.M >= 4096 ? 2 : 0;
+    return 9;
+}
+
+hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream)
+{
+    // MFMA tiles need 16-byte loads along K and a whole number of K steps
+    const bool fast = (a.K % 64 == 0) && ((uintptr_t)a.q % 16 == 0) && ((uintptr_t)a.w % 16 == 0) &&
+                      (a.w_bits == 8 || a.K % 128 == 0);
+    if (!fast || variant >= NUM_VARIANTS) {
+        hipLaunchKernelGGL(qgemm_naive, dim3((a.M + 3) / 4, (a.N + 63) / 64), dim3(256), 0, stream, a);
+        return hipGetLastError();
+    }
+    int v = variant;
+    if (v < 0 || VARIANTS[v].w_bits != a.w_bits || a.K % VARIANTS[v].BK != 0) v = choose_variant(a);
+    return VARIANTS[v].run(a, stream);
+}
+
+}  // namespace ql

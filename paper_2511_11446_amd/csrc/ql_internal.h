@@ -1,0 +1,45 @@
+// Internal launch interface between the host API (api.hip) and the kernels.
+// Not part of the public ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ql {
+
+// ---- DAQ (Step 3, eq. (4), tau = block absmax) ---------------------------
+// mode of the row kernels
+enum DaqMode : int {
+    DAQ_FUSED = 0,   // per-token: absmax, scale, codes in one pass over a row held in registers
+    DAQ_ABSMAX = 1,  // R > 1, phase 1: row absmax -> atomic max into blockmax[row / R]
+    DAQ_QUANT = 2    // R > 1, phase 2: codes from blockmax[row / R]
+};
+
+struct DaqArgs {
+    const void *x;       // [M,K] fp16
+    int8_t *q;           // [M,K]
+    float *scales;       // [M/R]
+    unsigned *blockmax;  // [M/R] fp16 bit patterns of block maxima (workspace), R > 1 only
+    int M, K, R;
+};
+
+hipError_t launch_daq(const DaqArgs &a, hipStream_t stream);
+
+// ---- GEMM + dequantization -------------------------------------------------
+struct GemmArgs {
+    const int8_t *q;      // [M,K] activation codes
+    const float *s_a;     // [M/R]
+    const void *w;        // int8 [N,K] or packed 4-bit [N,K/2]
+    const void *s_w;      // fp32 [N] (W8) or fp16 [N,K/128] (W4)
+    const void *bias;     // fp16 [N] or null
+    void *y;              // fp16 [M,N]
+    int32_t *acc_out;     // optional export: [M,N] (W8) or [M,K/128,N] (W4)
+    int M, N, K, R;
+    int w_bits;           // 8 or 4
+};
+
+int num_gemm_variants();
+const char *gemm_variant_name(int v);
+// variant < 0: choose by shape
+hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream);
+
+}  // namespace ql

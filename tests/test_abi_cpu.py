@@ -1,0 +1,146 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what the header declares,
+rejects bad arguments before touching a device, and its host helpers work."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2511_11446_amd as ql
+import workload
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "diffpro_qlinear.h")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b([a-z_0-9]+)\s*\([^;{]*\)\s*;", text)
+    return sorted(set(n for n in names if n not in ("defined",)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    L = ql.lib()
+    declared = _declared_functions()
+    assert len(declared) >= 19
+    for name in declared:
+        assert hasattr(L, name), name
+    assert sorted(declared) == sorted(ql.EXPORTS)
+    assert L.ql_version() >= 1000
+    assert L.ql_status_string(0) == b"QL_OK" and L.ql_status_string(5) == b"QL_ERR_WORKSPACE"
+    assert L.ql_num_gemm_variants() >= 4
+    assert all(ql.gemm_variants())
+
+
+FAKE = ctypes.c_void_p(0x1000)       # never dereferenced: every call below must fail validation first
+FAKE_ODD = ctypes.c_void_p(0x1001)
+
+
+def test_daq_argument_checks():
+    L = ql.lib()
+    assert L.daq_quantize(None, 4, 8, 1, FAKE, FAKE, None, 0, None) == 1
+    assert L.daq_quantize(FAKE, 4, 8, 1, None, FAKE, None, 0, None) == 1
+    assert L.daq_quantize(FAKE, 0, 8, 1, FAKE, FAKE, None, 0, None) == 2
+    assert L.daq_quantize(FAKE, 4, 0, 1, FAKE, FAKE, None, 0, None) == 2
+    assert L.daq_quantize(FAKE, 6, 8, 4, FAKE, FAKE, None, 0, None) == 2          # M % R != 0
+    assert L.daq_quantize(FAKE, 4, 133144, 1, FAKE, FAKE, None, 0, None) == 2      # K too long for int32 sums
+    assert L.daq_quantize(FAKE_ODD, 4, 8, 1, FAKE, FAKE, None, 0, None) == 3
+    assert L.daq_quantize(FAKE, 8, 8, 4, FAKE, FAKE, None, 0, None) == 5           # R > 1 needs a workspace
+    assert L.daq_quantize(FAKE, 8, 8, 4, FAKE, FAKE, FAKE, 4, None) == 5           # too small
+    assert L.daq_quantize(FAKE, 8, 8, 4, FAKE, FAKE, ctypes.c_void_p(0x1010), 4096, None) == 3  # not 256-aligned
+    assert ql.daq_workspace_bytes(8, 8, 1) == 0 and ql.daq_workspace_bytes(8, 8, 4) >= 8
+
+
+def test_qlinear_argument_checks():
+    L = ql.lib()
+    big = 1 << 30
+    for fn in (L.qlinear_w8a8, L.qlinear_w4a8):
+        assert fn(None, 4, 128, 1, FAKE, FAKE, None, 8, FAKE, None, FAKE, big, None) == 1
+        assert fn(FAKE, 4, 128, 1, None, FAKE, None, 8, FAKE, None, FAKE, big, None) == 1
+        assert fn(FAKE, 4, 128, 1, FAKE, None, None, 8, FAKE, None, FAKE, big, None) == 1
+        assert fn(FAKE, 4, 128, 1, FAKE, FAKE, None, 8, None, None, FAKE, big, None) == 1
+        assert fn(FAKE, 4, 128, 1, FAKE, FAKE, None, 0, FAKE, None, FAKE, big, None) == 2
+        assert fn(FAKE, 4, 128, 3, FAKE, FAKE, None, 8, FAKE, None, FAKE, big, None) == 2
+        assert fn(FAKE, 4, 128, 1, FAKE, FAKE, None, 8, FAKE, None, None, 0, None) == 5
+        assert fn(FAKE, 4, 128, 1, FAKE, FAKE, None, 8, FAKE, None, FAKE, 16, None) == 5
+        assert fn(FAKE, 4, 128, 1, FAKE, FAKE_ODD, None, 8, FAKE, None, FAKE, big, None) == 3
+        assert fn(FAKE, 1 << 20, 1 << 12, 1, FAKE, FAKE, None, 8, FAKE, None, FAKE, big, None) == 2  # M*K >= 2^31
+    # 4-bit weights need whole groups of 128
+    assert L.qlinear_w4a8(FAKE, 4, 192, 1, FAKE, FAKE, None, 8, FAKE, None, FAKE, big, None) == 2
+    assert L.qgemm_w4a8(FAKE, FAKE, 4, 192, 1, FAKE, FAKE, None, 8, FAKE, None, None) == 2
+    assert L.qgemm_w8a8(None, FAKE, 4, 128, 1, FAKE, FAKE, None, 8, FAKE, None, None) == 1
+    assert L.qgemm_w8a8(FAKE, FAKE, 4, 128, 1, FAKE, FAKE, None, 8, FAKE, FAKE_ODD, None) == 3
+    assert ql.qlinear_workspace_bytes(16, 128, 1) >= 16 * 128 + 16 * 4
+    assert ql.qlinear_workspace_bytes(16, 128, 4) > ql.qlinear_workspace_bytes(16, 128, 16) - 512
+
+
+def test_plan_argument_checks():
+    L = ql.lib()
+    h = ctypes.c_void_p()
+
+    def desc(K=1152, N=1152, bits=8, group=0, w=0x1000, s=0x2000, b=0):
+        return ql.ql_layer_desc(K, N, bits, group, w, s, b)
+
+    arr = (ql.ql_layer_desc * 2)(desc(), desc(bits=4, group=128))
+    assert L.ql_plan_create(arr, 2, 256, ctypes.byref(h)) == 0 and h.value
+    assert L.ql_plan_num_layers(h) == 2
+    assert L.ql_plan_workspace_bytes(h, 256, 1) >= 256 * 1152
+    assert L.ql_plan_workspace_bytes(h, 512, 1) == 0          # beyond M_max
+    xs = (ctypes.c_void_p * 2)(0x1000, 0x1000)
+    ys = (ctypes.c_void_p * 2)(0x1000, 0)
+    assert L.qlinear_plan_run(h, xs, ys, 256, 1, FAKE, 1 << 30, None) == 1   # a NULL output
+    ys = (ctypes.c_void_p * 2)(0x1000, 0x1000)
+    assert L.qlinear_plan_run(h, xs, ys, 512, 1, FAKE, 1 << 30, None) == 2   # M > M_max
+    assert L.qlinear_plan_run(h, xs, ys, 256, 7, FAKE, 1 << 30, None) == 2   # M % R
+    assert L.qlinear_plan_run(h, xs, ys, 256, 1, FAKE, 64, None) == 5
+    assert L.qlinear_plan_run(None, xs, ys, 256, 1, FAKE, 1 << 30, None) == 1
+    L.ql_plan_destroy(h)
+    bad = [(desc(bits=6), 4), (desc(bits=8, group=128), 4), (desc(bits=4, group=0), 4), (desc(bits=4, group=64), 4),
+           (desc(K=1100, bits=4, group=128), 2), (desc(w=0), 1), (desc(s=0), 1), (desc(N=0), 2), (desc(s=0x2001), 3)]
+    for d, want in bad:
+        arr = (ql.ql_layer_desc * 1)(d)
+        assert L.ql_plan_create(arr, 1, 256, ctypes.byref(h)) == want
+        assert not h.value
+    assert L.ql_plan_create(arr, 0, 256, ctypes.byref(h)) == 2
+    assert L.ql_plan_create(None, 1, 256, ctypes.byref(h)) == 1
+
+
+def test_variant_override_range():
+    L = ql.lib()
+    n = L.ql_num_gemm_variants()
+    assert L.ql_set_gemm_variant(n + 1) == 4 and L.ql_set_gemm_variant(-2) == 4
+    assert L.ql_set_gemm_variant(n) == 0      # n selects the generic kernel
+    assert L.ql_set_gemm_variant(-1) == 0
+
+
+def test_pack_w4_host_matches_documented_order(orc):
+    # hand-derived from the storage rule: byte j of a run of 8 holds k=j (low) and k=4+j (high)
+    w = np.array([[0, 1, 2, 3, 4, 5, 6, 7, -8, -7, -6, -5, -4, -3, -2, -1]], np.int8)
+    assert ql.ql_pack_w4_host(w).tolist() == [[0x40, 0x51, 0x62, 0x73, 0xC8, 0xD9, 0xEA, 0xFB]]
+    codes = workload.w4_codes(33, 256, "abi")
+    packed = ql.ql_pack_w4_host(codes)
+    # the oracle's independent packer and unpacker agree with the library's host packer
+    assert np.array_equal(packed, orc.pack_w4(codes))
+    assert np.array_equal(orc.unpack_w4(packed, 256), codes)
+    bad = codes.copy()
+    bad[3, 7] = 8
+    with pytest.raises(ql.QlError):
+        ql.ql_pack_w4_host(bad)
+
+
+def test_workload_recipe_is_deterministic():
+    a = workload.activations(8, 1152, "det", 3)
+    b = workload.activations(8, 1152, "det", 3)
+    assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
+    assert not np.array_equal(a, workload.activations(8, 1152, "det", 4))
+    ch = workload.outlier_channels(1152, 8, "det", 3)
+    assert len(set(ch.tolist())) == 8
+    assert np.abs(a[:, ch].astype(np.float32)).mean() > 5 * np.abs(a.astype(np.float32)).mean() / 2
+    plan = workload.bit_plan()
+    assert len(plan) == 112 and all(p["bits"] == 8 for p in plan[:12] + plan[-12:])
+    n4 = sum(p["bits"] == 4 for p in plan)
+    assert 60 <= n4 <= 88 and plan == workload.bit_plan()
+    s = workload.sigma_schedule(25)
+    assert abs(s[0] - 5.0) < 1e-12 and abs(s[-1] - 0.2) < 1e-12 and np.all(np.diff(s) < 0)

@@ -1,0 +1,438 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the
+same seeded inputs.  Integer codes, activation scales and int32 accumulators must be
+bit-identical; fp16 outputs must agree within 1e-3 relative (one fp16 ulp is at most
+2^-10 = 9.8e-4 relative; below the fp16 normal range one subnormal step 2^-24)."""
+import sys
+
+import numpy as np
+import pytest
+
+import workload
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    import paper_2511_11446_amd as ql
+    ql.lib()
+    assert torch.cuda.is_available()
+    ql.set_gemm_variant(-1)
+    return ql
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def assert_y_close(y_gpu, y_ref):
+    """|y_gpu - y_ref| <= 1e-3 |y_ref| (or one subnormal step near zero); returns the number of differing elements."""
+    a = y_gpu.astype(np.float64)
+    b = y_ref.astype(np.float64)
+    assert np.isfinite(b).all()
+    tol = np.maximum(1e-3 * np.abs(b), 2.0 ** -24)
+    bad = np.abs(a - b) > tol
+    assert not bad.any(), "max rel err %g at %s" % (np.max(np.abs(a - b) / np.maximum(np.abs(b), 1e-30)),
+                                                     np.argwhere(bad)[:4].tolist())
+    return int((y_gpu.view(np.uint16) != y_ref.view(np.uint16)).sum())
+
+
+# ------------------------------------------------------------------ DAQ
+
+DAQ_CASES = [
+    # M, K, R
+    (256, 1152, 256),   # one 256-token image, per tensor
+    (64, 1152, 1),      # per token, K/8 = 144 chunks: 2 full lanes-rounds + a ragged third
+    (37, 1152, 1),      # rows not a multiple of the 4 rows per workgroup
+    (16, 4608, 1),      # 9 chunks per lane
+    (6, 8192, 1),       # 16 chunks per lane (largest register-cached row)
+    (3, 16384, 1),      # longer than the register cache: re-read path
+    (8, 64, 1), (8, 8, 1), (8, 520, 1),
+    (5, 100, 1), (7, 1151, 1), (9, 3, 3),   # K % 8 != 0: element-wise kernel
+    (512, 1152, 256), (48, 256, 4), (48, 256, 48), (1024, 384, 1024),
+]
+
+
+@pytest.mark.parametrize("M,K,R", DAQ_CASES)
+def test_daq_parity(gpu, orc, M, K, R):
+    say("daq", M, K, R)
+    x = workload.activations(M, K, "daq", R, sigma=float(workload.rng("dsig", M, K).uniform(0.05, 6.0)))
+    q_ref, s_ref = orc.daq(x, R, nthreads=8)
+    q, s = gpu.daq_quantize(dev(x), R)
+    assert np.array_equal(host(q), q_ref)
+    assert np.array_equal(host(s).view(np.uint32), s_ref.view(np.uint32))
+
+
+def test_daq_edge_values(gpu, orc):
+    say("daq edge values")
+    K = 1152
+    x = workload.activations(12, K, "edge")
+    x[0] = 0                                    # all-zero row: scale 1, codes 0
+    x[1] = np.float16(-0.0)
+    x[2] = np.float16(65504.0)                  # largest finite fp16 everywhere
+    x[3, :] = np.float16(6e-8)                  # smallest subnormal
+    x[4, ::2] = np.float16(6e-8)
+    x[4, 1::2] = np.float16(-3e-5)              # subnormal mixture
+    x[5, :] = 0
+    x[5, 77] = np.float16(-123.5)               # single non-zero element
+    x[6] = (np.arange(K) % 255 - 127).astype(np.float16)       # amax 127 -> alpha 1: pure ties-to-even check
+    x[7] = ((np.arange(K) % 255 - 127) / 2.0).astype(np.float16)  # half-integers / alpha 0.5
+    x[8] = (np.arange(K) % 509 - 254).astype(np.float16) * np.float16(0.5)  # .5 ties with alpha = 1
+    for R in (1, 4, 12):
+        q_ref, s_ref = orc.daq(x, R)
+        q, s = gpu.daq_quantize(dev(x), R)
+        assert np.array_equal(host(q), q_ref), R
+        assert np.array_equal(host(s).view(np.uint32), s_ref.view(np.uint32)), R
+    q, s = gpu.daq_quantize(dev(x), 1)
+    assert not host(q)[0].any() and host(s)[0] == 1.0
+    assert host(q)[6].tolist() == [int(np.rint(v)) for v in x[6].astype(np.float64)]
+
+
+def test_daq_power_of_two_invariance_on_gpu(gpu):
+    say("daq power-of-two invariance")
+    x = workload.activations(32, 1152, "p2gpu", n_outlier=0)
+    x = np.where(np.abs(x) < 2.0 ** -6, np.float16(2.0 ** -6), x).astype(np.float16)
+    q0, s0 = gpu.daq_quantize(dev(x), 1)
+    for j in (-6, 3, 7):
+        xs = (x.astype(np.float32) * np.float32(2.0 ** j)).astype(np.float16)
+        q, s = gpu.daq_quantize(dev(xs), 1)
+        assert np.array_equal(host(q), host(q0))
+        assert np.array_equal(host(s), host(s0) * np.float32(2.0 ** j))
+
+
+# ------------------------------------------------------------------ W8A8 layer
+
+def run_w8(gpu, orc, M, K, N, R, key, use_bias=True, sigma=1.0, check_exact=False):
+    x = workload.activations(M, K, key, sigma=sigma)
+    lw = workload.layer_weights(key, K, N, 8, "gpu")
+    b = lw["bias"] if use_bias else None
+    ref = orc.qlinear_w8a8(x, R, lw["w"], lw["s_w"], b, nthreads=16)
+    out = gpu.qlinear_w8a8(dev(x), R, dev(lw["w"]), dev(lw["s_w"]), None if b is None else dev(b), debug=True)
+    assert np.array_equal(host(out["q"]), ref["q"])
+    assert np.array_equal(host(out["s_a"]).view(np.uint32), ref["s_a"].view(np.uint32))
+    assert np.array_equal(host(out["acc"]), ref["acc"])
+    ndiff = assert_y_close(host(out["y"]), ref["y"])
+    # without the debug exports the same y must come out
+    y2 = gpu.qlinear_w8a8(dev(x), R, dev(lw["w"]), dev(lw["s_w"]), None if b is None else dev(b))
+    assert np.array_equal(host(y2).view(np.uint16), host(out["y"]).view(np.uint16))
+    if check_exact:
+        assert ndiff == 0
+    return ndiff
+
+
+def test_w8a8_c1_single_linear(gpu, orc):
+    say("C1 single W8A8 256x1152x1152 per-tensor")
+    ndiff = run_w8(gpu, orc, 256, 1152, 1152, 256, "c1", check_exact=True)
+    assert ndiff == 0
+
+
+W8_SHAPES = [
+    # M, K, N, R: several tiles plus ragged tails in M and N
+    (300, 192, 200, 1), (129, 64, 33, 1), (1, 64, 1, 1), (257, 128, 385, 1), (512, 1152, 1152, 256),
+    (96, 4608, 160, 32), (64, 1152, 3456, 1),
+]
+
+
+@pytest.mark.parametrize("M,K,N,R", W8_SHAPES)
+def test_w8a8_shapes_default_variant(gpu, orc, M, K, N, R):
+    say("w8a8", M, K, N, R)
+    run_w8(gpu, orc, M, K, N, R, ("w8", M, K, N), use_bias=(M % 2 == 0), check_exact=True)
+
+
+def test_w8a8_every_variant(gpu, orc):
+    names = gpu.gemm_variants()
+    try:
+        for v, name in enumerate(names + ["generic"]):
+            if v < len(names) and not name.startswith("w8"):
+                continue
+            gpu.set_gemm_variant(v)
+            for (M, K, N, R) in [(300, 256, 200, 1), (520, 1152, 1152, 1), (260, 128, 640, 4)]:
+                say("w8a8 variant", v, name, M, K, N, R)
+                run_w8(gpu, orc, M, K, N, R, ("w8v", M, K, N), check_exact=True)
+    finally:
+        gpu.set_gemm_variant(-1)
+
+
+def test_w8a8_unaligned_k_uses_generic_kernel(gpu, orc):
+    for (M, K, N, R) in [(33, 100, 50, 1), (16, 72, 16, 4), (5, 7, 3, 5), (20, 1160, 40, 1)]:
+        say("w8a8 generic", M, K, N, R)
+        run_w8(gpu, orc, M, K, N, R, ("w8g", M, K, N), check_exact=True)
+
+
+def test_w8a8_extreme_fill_and_zero_input(gpu, orc):
+    say("w8a8 extreme fill")
+    M, K, N = 64, 4608, 128
+    x = np.full((M, K), 3.0, np.float16)
+    x[1::2] = np.float16(-3.0)
+    w = np.full((N, K), 127, np.int8)
+    w[:, ::3] = -127
+    s_w = np.full((N,), 2.0 ** -12, np.float32)
+    ref = orc.qlinear_w8a8(x, 1, w, s_w, None, nthreads=8)
+    out = gpu.qlinear_w8a8(dev(x), 1, dev(w), dev(s_w), None, debug=True)
+    assert np.array_equal(host(out["acc"]), ref["acc"])
+    assert np.abs(ref["acc"]).max() == 127 * 127 * (K - 2 * len(range(0, K, 3)))
+    assert_y_close(host(out["y"]), ref["y"])
+    w[:] = 127
+    out = gpu.qlinear_w8a8(dev(x), 1, dev(w), dev(s_w), None, debug=True)
+    assert np.abs(host(out["acc"])).max() == 4608 * 127 * 127      # the largest sum the DiT shapes can reach
+    say("w8a8 zero input -> bias")
+    lw = workload.layer_weights("z", 1152, 256, 8, "z")
+    y = gpu.qlinear_w8a8(dev(np.zeros((40, 1152), np.float16)), 1, dev(lw["w"]), dev(lw["s_w"]), dev(lw["bias"]))
+    assert np.array_equal(host(y), np.repeat(lw["bias"][None], 40, 0))
+
+
+# ------------------------------------------------------------------ W4A8 layer
+
+def run_w4(gpu, orc, M, K, N, R, key, use_bias=True, check_exact=False):
+    x = workload.activations(M, K, key)
+    lw = workload.layer_weights(key, K, N, 4, "gpu")
+    b = lw["bias"] if use_bias else None
+    w4 = gpu.ql_pack_w4_host(lw["w"])
+    ref = orc.qlinear_w4a8(x, R, orc.pack_w4(lw["w"]), lw["s_w"], b, nthreads=16)
+    out = gpu.qlinear_w4a8(dev(x), R, dev(w4), dev(lw["s_w"]), None if b is None else dev(b), debug=True)
+    assert np.array_equal(host(out["q"]), ref["q"])
+    assert np.array_equal(host(out["s_a"]).view(np.uint32), ref["s_a"].view(np.uint32))
+    assert np.array_equal(host(out["P"]), ref["P"])
+    ndiff = assert_y_close(host(out["y"]), ref["y"])
+    y2 = gpu.qlinear_w4a8(dev(x), R, dev(w4), dev(lw["s_w"]), None if b is None else dev(b))
+    assert np.array_equal(host(y2).view(np.uint16), host(out["y"]).view(np.uint16))
+    if check_exact:
+        assert ndiff == 0
+    return ndiff
+
+
+W4_SHAPES = [(300, 256, 200, 1), (129, 128, 33, 1), (64, 1152, 1152, 1), (260, 1152, 384, 4), (40, 4608, 160, 1),
+             (1, 128, 1, 1)]
+
+
+@pytest.mark.parametrize("M,K,N,R", W4_SHAPES)
+def test_w4a8_shapes_default_variant(gpu, orc, M, K, N, R):
+    say("w4a8", M, K, N, R)
+    run_w4(gpu, orc, M, K, N, R, ("w4", M, K, N), use_bias=(M % 2 == 0), check_exact=True)
+
+
+def test_w4a8_every_variant(gpu, orc):
+    names = gpu.gemm_variants()
+    try:
+        for v, name in enumerate(names + ["generic"]):
+            if v < len(names) and not name.startswith("w4"):
+                continue
+            gpu.set_gemm_variant(v)
+            for (M, K, N, R) in [(300, 256, 200, 1), (264, 1152, 320, 1)]:
+                say("w4a8 variant", v, name, M, K, N, R)
+                run_w4(gpu, orc, M, K, N, R, ("w4v", M, K, N), check_exact=True)
+    finally:
+        gpu.set_gemm_variant(-1)
+
+
+def test_w4a8_nibble_extremes(gpu, orc):
+    say("w4a8 nibble extremes")
+    M, K, N = 32, 256, 64
+    x = workload.activations(M, K, "nib")
+    codes = np.full((N, K), -8, np.int8)
+    codes[1::2] = 7
+    codes[:, 5::7] = -1
+    s = workload.w4_scales(N, K, "nib")
+    ref = orc.qlinear_w4a8(x, 1, orc.pack_w4(codes), s, None)
+    out = gpu.qlinear_w4a8(dev(x), 1, dev(gpu.ql_pack_w4_host(codes)), dev(s), None, debug=True)
+    assert np.array_equal(host(out["P"]), ref["P"])
+    assert assert_y_close(host(out["y"]), ref["y"]) == 0
+
+
+# ------------------------------------------------------------------ GEMM stage alone, determinism
+
+def test_qgemm_on_given_codes_and_determinism(gpu, orc):
+    say("qgemm on given codes")
+    import torch
+    M, K, N, R = 384, 1152, 640, 1
+    g = workload.rng("qg")
+    q = g.integers(-127, 128, size=(M, K), dtype=np.int8)
+    s_a = g.uniform(1e-3, 1e-1, M // R).astype(np.float32)
+    lw = workload.layer_weights("qg", K, N, 8, 0)
+    acc_ref = orc.gemm_i8(q, lw["w"], nthreads=8)
+    y_ref = orc.epilogue_w8(acc_ref, s_a, R, lw["s_w"], lw["bias"])
+    acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    args = (dev(q), dev(s_a), R, dev(lw["w"]), dev(lw["s_w"]), dev(lw["bias"]))
+    y = gpu.qgemm_w8a8(*args, acc=acc)
+    assert np.array_equal(host(acc), acc_ref)
+    assert assert_y_close(host(y), y_ref) == 0
+    for _ in range(3):   # integer results cannot depend on timing: any difference is a race
+        acc2 = torch.empty_like(acc)
+        y2 = gpu.qgemm_w8a8(*args, acc=acc2)
+        assert torch.equal(acc2, acc) and torch.equal(y2.view(torch.int16), y.view(torch.int16))
+    l4 = workload.layer_weights("qg", K, N, 4, 0)
+    P_ref = orc.gemm_w4g128(q, orc.pack_w4(l4["w"]), nthreads=8)
+    y4_ref = orc.epilogue_w4(P_ref, s_a, R, l4["s_w"], l4["bias"])
+    P = torch.empty((M, K // 128, N), dtype=torch.int32, device="cuda")
+    y4 = gpu.qgemm_w4a8(dev(q), dev(s_a), R, dev(gpu.ql_pack_w4_host(l4["w"])), dev(l4["s_w"]), dev(l4["bias"]), acc=P)
+    assert np.array_equal(host(P), P_ref)
+    assert assert_y_close(host(y4), y4_ref) == 0
+
+
+# ------------------------------------------------------------------ DiT block shapes (configs of the benchmark)
+
+def test_c2_block_m2048_full_compare(gpu, orc):
+    """One DiT-XL/2 block at 8 images x 256 tokens, per-token DAQ, every output element compared."""
+    M, R = 2048, 1
+    y_fc1 = None
+    for name, K, N in workload.BLOCK_LAYERS:
+        say("C2", name, M, K, N)
+        if name == "fc2":
+            x = workload.gelu_tanh_f16(y_fc1)     # fc2 sees GELU of the oracle's fc1 output
+        else:
+            x = workload.activations(M, K, "c2", name)
+        lw = workload.layer_weights(name, K, N, 8, "c2")
+        ref = orc.qlinear_w8a8(x, R, lw["w"], lw["s_w"], lw["bias"], nthreads=16)
+        if name == "fc1":
+            y_fc1 = ref["y"]
+        out = gpu.qlinear_w8a8(dev(x), R, dev(lw["w"]), dev(lw["s_w"]), dev(lw["bias"]), debug=True)
+        assert np.array_equal(host(out["q"]), ref["q"])
+        assert np.array_equal(host(out["s_a"]).view(np.uint32), ref["s_a"].view(np.uint32))
+        assert np.array_equal(host(out["acc"]), ref["acc"])
+        assert assert_y_close(host(out["y"]), ref["y"]) == 0
+
+
+def _sampled_layer_check(gpu, orc, name, K, N, bits, M, R, rows, key, sigma):
+    """Full-size launch on the GPU; the oracle recomputes a sample of rows (whole scale blocks)."""
+    import torch
+    x = workload.activations(M, K, key, name, sigma=sigma)
+    lw = workload.layer_weights(name, K, N, bits, key)
+    xd = dev(x)
+    if bits == 8:
+        out = gpu.qlinear_w8a8(xd, R, dev(lw["w"]), dev(lw["s_w"]), dev(lw["bias"]), debug=True)
+        ref = orc.qlinear_w8a8(x[rows], R if R == 1 else len(rows), lw["w"], lw["s_w"], lw["bias"], nthreads=16)
+        accname = "acc"
+    else:
+        out = gpu.qlinear_w4a8(xd, R, dev(gpu.ql_pack_w4_host(lw["w"])), dev(lw["s_w"]), dev(lw["bias"]), debug=True)
+        ref = orc.qlinear_w4a8(x[rows], R if R == 1 else len(rows), orc.pack_w4(lw["w"]), lw["s_w"], lw["bias"],
+                               nthreads=16)
+        accname = "P"
+    idx = torch.from_numpy(rows).cuda()
+    assert np.array_equal(host(out["q"][idx]), ref["q"])
+    assert np.array_equal(host(out[accname][idx]), ref[accname])
+    sidx = idx if R == 1 else idx[:1] // R
+    assert np.array_equal(host(out["s_a"][sidx]).view(np.uint32), ref["s_a"].view(np.uint32))
+    assert assert_y_close(host(out["y"][idx]), ref["y"]) == 0
+    # properties that hold at any size: codes bounded, every scale block reaches +-127
+    qa = out["q"].view(M // R, -1).abs().amax(dim=1)
+    assert int(qa.max()) == 127 and int(qa.min()) == 127
+    del out
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("name,K,N,bits", [("qkv", 1152, 3456, 8), ("proj", 1152, 1152, 8),
+                                           ("fc1", 1152, 4608, 4), ("fc2", 4608, 1152, 4)])
+def test_c3_mixed_m8192_sampled(gpu, orc, name, K, N, bits):
+    M = 8192
+    rows = np.sort(workload.rng("c3rows", name).choice(M, size=96, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    say("C3", name, bits, "rows", len(rows))
+    _sampled_layer_check(gpu, orc, name, K, N, bits, M, 1, rows, "c3", 1.0)
+
+
+@pytest.mark.parametrize("name,K,N", [("qkv", 1152, 3456), ("fc2", 4608, 1152)])
+def test_c4_m16384_drift_sampled(gpu, orc, name, K, N):
+    M = 16384
+    sig = workload.sigma_schedule(50)
+    for step in (0, 49):
+        rows = np.sort(workload.rng("c4rows", name, step).choice(M, size=64, replace=False))
+        rows[0], rows[-1] = 0, M - 1
+        say("C4", name, "step", step, "sigma", float(sig[step]))
+        _sampled_layer_check(gpu, orc, name, K, N, 8, M, 1, rows, ("c4", step), float(sig[step]))
+
+
+def test_c4_per_sample_scales_m16384(gpu, orc):
+    """The paper's own granularity: one scale per image (1024 tokens) per timestep."""
+    M, R = 16384, 1024
+    rows = np.arange(5 * R, 6 * R)          # one whole image
+    say("C4 per-sample proj, image 5")
+    _sampled_layer_check(gpu, orc, "proj", 1152, 1152, 8, M, R, rows, "c4ps", 2.0)
+
+
+# ------------------------------------------------------------------ plan runner
+
+def test_plan_runner_small_mixed_plan(gpu, orc):
+    import torch
+    M, R = 320, 1
+    shapes = [("a", 256, 384, 8), ("b", 384, 256, 4), ("c", 256, 200, 4), ("d", 128, 128, 8), ("e", 1152, 96, 8)]
+    layers, xs, refs = [], [], []
+    for name, K, N, bits in shapes:
+        lw = workload.layer_weights(name, K, N, bits, "plan")
+        x = workload.activations(M, K, "plan", name)
+        if bits == 8:
+            refs.append(orc.qlinear_w8a8(x, R, lw["w"], lw["s_w"], lw["bias"], want_debug=False)["y"])
+            w = dev(lw["w"])
+        else:
+            refs.append(orc.qlinear_w4a8(x, R, orc.pack_w4(lw["w"]), lw["s_w"], lw["bias"], want_debug=False)["y"])
+            w = dev(gpu.ql_pack_w4_host(lw["w"]))
+        layers.append(dict(K=K, N=N, bits=bits, w=w, w_scale=dev(lw["s_w"]), bias=dev(lw["bias"])))
+        xs.append(dev(x))
+    say("plan create/run", len(layers), "layers")
+    plan = gpu.Plan(layers, M_max=512)
+    ys = [torch.zeros((M, l["N"]), dtype=torch.float16, device="cuda") for l in layers]
+    ws = gpu.workspace(plan.workspace_bytes(M, R))
+    for rep in range(2):
+        plan.run(xs, ys, M, R, ws)
+        torch.cuda.synchronize()
+        for y, ref in zip(ys, refs):
+            assert assert_y_close(host(y), ref) == 0
+    # per-sample scales through the same plan
+    plan.run(xs, ys, M, 64, ws)
+    x0 = workload.activations(M, 256, "plan", "a")
+    lw0 = workload.layer_weights("a", 256, 384, 8, "plan")
+    ref0 = orc.qlinear_w8a8(x0, 64, lw0["w"], lw0["s_w"], lw0["bias"], want_debug=False)["y"]
+    assert assert_y_close(host(ys[0]), ref0) == 0
+    plan.close()
+
+
+def test_c5_plan_stack_m16384_sampled(gpu, orc):
+    """The 112-layer stack under the seeded bit plan at full size; the oracle checks sampled rows of sampled layers."""
+    import torch
+    M, R = 16384, 1
+    plan_desc = workload.bit_plan()
+    sig = float(workload.sigma_schedule(25)[3])
+    x_by_type = {name: workload.activations(M, K, "c5", name, sigma=sig) for name, K, N in workload.BLOCK_LAYERS}
+    xd = {k: dev(v) for k, v in x_by_type.items()}
+    yd = {name: torch.empty((M, N), dtype=torch.float16, device="cuda") for name, K, N in workload.BLOCK_LAYERS}
+    layers, host_w = [], {}
+    for i, p in enumerate(plan_desc):
+        lw = workload.layer_weights(p["name"], p["K"], p["N"], p["bits"], "c5", p["block"])
+        w = dev(lw["w"]) if p["bits"] == 8 else dev(gpu.ql_pack_w4_host(lw["w"]))
+        layers.append(dict(K=p["K"], N=p["N"], bits=p["bits"], w=w, w_scale=dev(lw["s_w"]), bias=dev(lw["bias"])))
+        host_w[i] = lw
+    plan = gpu.Plan(layers, M_max=M)
+    ws = gpu.workspace(plan.workspace_bytes(M, R))
+    check = [0, 1, 2, 3, 14, 15, 57, 110, 111]   # includes W4 and W8 layers of every type
+    rows = np.sort(workload.rng("c5rows").choice(M, size=48, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    idx = torch.from_numpy(rows).cuda()
+    # give every checked layer its own output buffer so the run can be compared afterwards
+    x_in = [xd[p["name"]] for p in plan_desc]
+    y_out = [yd[p["name"]] for p in plan_desc]
+    for i in check:
+        y_out[i] = torch.empty((M, plan_desc[i]["N"]), dtype=torch.float16, device="cuda")
+    say("C5 plan run", len(layers), "layers", sum(p["bits"] == 4 for p in plan_desc), "at W4")
+    plan.run(x_in, y_out, M, R, ws)
+    torch.cuda.synchronize()
+    for i in check:
+        p, lw = plan_desc[i], host_w[i]
+        say("C5 check layer", i, p["name"], p["bits"])
+        xs = x_by_type[p["name"]][rows]
+        if p["bits"] == 8:
+            ref = orc.qlinear_w8a8(xs, 1, lw["w"], lw["s_w"], lw["bias"], nthreads=16, want_debug=False)["y"]
+        else:
+            ref = orc.qlinear_w4a8(xs, 1, orc.pack_w4(lw["w"]), lw["s_w"], lw["bias"], nthreads=16,
+                                   want_debug=False)["y"]
+        assert assert_y_close(host(y_out[i][idx]), ref) == 0
+    plan.close()
