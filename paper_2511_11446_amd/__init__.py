@@ -54,6 +54,11 @@ def lib():
     if not os.path.exists(LIB_PATH):
         raise ImportError("%s is missing: build it with `python -m paper_2511_11446_amd.build` "
                           "(there is no fallback path)" % LIB_PATH)
+    # PyTorch-ROCm ships its own HIP runtime (soname libamdhip64.so.7).  Loading torch first makes the
+    # dynamic loader resolve this library's libamdhip64.so.7 dependency to that same copy, so torch's
+    # device pointers and streams and this library's kernels live in ONE runtime.  The other order
+    # would put two HIP runtimes in the process, and the second one finds no device.
+    import torch  # noqa: F401
     L = ctypes.CDLL(LIB_PATH)
     L.ql_status_string.restype = ctypes.c_char_p
     L.ql_status_string.argtypes = [_int]
