@@ -16,6 +16,14 @@ namespace ql {
 typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+// LDS staging is written as fp16 scalars and read back as 16-byte vectors: tell the compiler these may alias
+typedef _Float16 half_alias __attribute__((may_alias));
+typedef int v4i_alias __attribute__((ext_vector_type(4), may_alias));
+
+// Timing hook for kernel phase studies; expands to nothing in the library build.
+#ifndef QL_PHASE
+#define QL_PHASE(id)
+#endif
 
 constexpr int XCDS = 8;    // L2 domains of the chip; consecutive workgroup ids go round-robin over them
 constexpr int GROUP_M = 4; // tile rows walked together so that one L2 sees few distinct A and W panels
@@ -237,6 +245,276 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
     else emit(std::true_type{});
 }
 
+// ---------------------------------------------------------------------------------------------
+// Epilogue for a full tile (no ragged edge, N % 8 == 0).  Each wavefront dequantizes one 32-row
+// block of its accumulators at a time, parks the fp16 results in a private LDS strip
+// [32 rows][TN*32 columns] (row pitch padded by 16 bytes), and reads the strip back as 16-byte
+// pieces, so that every global store instruction writes whole contiguous row segments of
+// TN*64 bytes instead of 2-byte elements.
+//   value(i, j, r) -> fp32 result before the fp16 rounding (W8: fma(float(acc)*s_a, s_w, bias))
+// ---------------------------------------------------------------------------------------------
+template <int TM, int TN, class ValueFn>
+__device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane, _Float16 *y, int N, int m_base, int n_base,
+                                                  ValueFn value)
+{
+    constexpr int PITCH = TN * 64 + 16;
+    constexpr int CH = TN * 4;  // 16-byte pieces per row
+    const int frag_row = lane & 31, frag_half = lane >> 5;
+    unsigned char *wr = strip + (4 * frag_half) * PITCH + frag_row * 2;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float u = value(i, j, r);
+                // keep the fp32 rounding of the fused multiply-add: without this the compiler may select a
+                // mixed-precision fma that rounds straight to fp16 (one rounding instead of the defined two)
+                asm volatile("" : "+v"(u));
+                const _Float16 h = (_Float16)u;
+                *reinterpret_cast<half_alias *>(wr + (8 * (r / 4) + (r % 4)) * PITCH + j * 64) = h;
+            }
+        asm volatile("" ::: "memory");  // the strip reads below see other lanes' writes: keep program order
+#pragma unroll
+        for (int t = 0; t < 32 * CH / 64; ++t) {
+            const int id = lane + 64 * t;
+            const int row = id / CH, ch = id % CH;
+            const v4i v = *reinterpret_cast<const v4i_alias *>(strip + row * PITCH + ch * 16);
+            *reinterpret_cast<v4i_alias *>(y + (unsigned)((m_base + i * 32 + row) * N + n_base + ch * 8)) = v;
+        }
+        asm volatile("" ::: "memory");
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Pipelined variant: tiles go from global memory straight into LDS (global_load_lds_dwordx4, no
+// register staging) through a ring of S stages, so S-1 K steps of loads are in flight while one
+// is being multiplied; one s_barrier per K step.  One K step is 64 int8 = one 64-byte LDS row.
+// The 16-byte chunk c of row r is kept at slot c ^ ((r >> 2) & 3) of its row: rows are unpadded
+// (a wavefront's DMA writes 1024 contiguous bytes = 16 rows), and the XOR spreads the 16 lanes
+// that read the same chunk index of 16 consecutive rows over all 64 banks.
+// ---------------------------------------------------------------------------------------------
+template <int TM_, int TN_, int WGM_, int WGN_, int S_, int WPS_>
+struct TileD {
+    static constexpr int TM = TM_, TN = TN_, WGM = WGM_, WGN = WGN_, S = S_, WPS = WPS_;
+    static constexpr int NW = WGM * WGN, NT = NW * 64;
+    static constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32, BK = 64;
+    static constexpr int GROUPS = (BM + BN) / 16;         // 16-row DMA groups per K step (A rows first, then B rows)
+    static constexpr int LPT = (GROUPS + NW - 1) / NW;     // DMA instructions per wavefront per K step ...
+    static constexpr int REM = GROUPS % NW;                // ... except that wavefronts >= REM issue one less when REM != 0
+    static constexpr int STAGE_BYTES = (BM + BN) * 64;
+    static constexpr int STRIP_OFF = (BM * 4 + 255) / 256 * 256;   // epilogue: row scales first, then one strip per wavefront
+    static constexpr int STRIP_BYTES = 32 * (TN * 64 + 16);
+    static constexpr int LDS_BYTES = S * STAGE_BYTES > STRIP_OFF + NW * STRIP_BYTES ? S * STAGE_BYTES : STRIP_OFF + NW * STRIP_BYTES;
+    static_assert(S >= 3 && (S - 2) * LPT <= 63, "vmcnt is a 6-bit counter");
+    static_assert(BM * 4 <= LDS_BYTES, "row-scale staging reuses the ring");
+};
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void global_void;
+
+template <class T>
+__global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles_m, int tiles_n, int nblk_padded)
+{
+    constexpr int TM = T::TM, TN = T::TN, BM = T::BM, BN = T::BN, NT = T::NT, S = T::S, NW = T::NW;
+    extern __shared__ __align__(1024) unsigned char smem[];
+
+    const int per_xcd = nblk_padded / XCDS;
+    const int logical = (blockIdx.x % XCDS) * per_xcd + blockIdx.x / XCDS;
+    if (logical >= tiles_m * tiles_n) return;
+    const int group_sz = GROUP_M * tiles_n;
+    const int first_m = (logical / group_sz) * GROUP_M;
+    const int gm = min(tiles_m - first_m, GROUP_M);
+    const int tile_m = first_m + (logical % group_sz) % gm;
+    const int tile_n = (logical % group_sz) / gm;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it in a scalar register
+    const int wm = wave / T::WGN, wn = wave % T::WGN;
+    const int M = a.M, N = a.N, K = a.K;
+    const int nk = K / 64;
+    QL_PHASE(0)
+
+    // DMA addressing: lane l of a wavefront fills bytes [16 l, 16 l + 16) of a 1024-byte group = row l/4, slot l%4
+    // Group g covers stage rows [16 g, 16 g + 16): A rows for g < BM/16, W rows after.  Wavefront w takes g = w, w+NW, ...
+    const int my_loads = (T::REM == 0 || wave < T::REM) ? T::LPT : T::LPT - 1;
+    const int8_t *gbase[T::LPT];
+    unsigned goff[T::LPT];
+#pragma unroll
+    for (int i = 0; i < T::LPT; ++i) {
+        const int g = min(wave + i * NW, T::GROUPS - 1);
+        const int row = 16 * g + (lane >> 2);
+        const int c = (lane & 3) ^ ((row >> 2) & 3);
+        const bool is_a = g < BM / 16;
+        gbase[i] = is_a ? a.q : static_cast<const int8_t *>(a.w);
+        goff[i] = (unsigned)((is_a ? min(m0 + row, M - 1) : min(n0 + row - BM, N - 1)) * K + 16 * c);
+    }
+    auto issue = [&](int kt, int slot) {
+        unsigned char *st = smem + slot * T::STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < T::LPT; ++i)
+            if (i < my_loads)
+                __builtin_amdgcn_global_load_lds((global_void *)(gbase[i] + (size_t)kt * 64 + goff[i]),
+                                                 (lds_void *)(st + (wave + i * NW) * 1024), 16, 0, 0);
+    };
+    // wait until at most n K steps of this wavefront's loads are still in flight (n is a compile-time constant)
+    auto wait_steps = [&](auto n_tag) {
+        constexpr int n = decltype(n_tag)::value;
+        if (T::REM == 0 || wave < T::REM) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n * T::LPT) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n * (T::LPT - 1)) : "memory");
+    };
+
+    v16i acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    const int frag_row = lane & 31, frag_half = lane >> 5;
+    const int sw = (lane >> 2) & 3;  // swizzle key of this lane's row (tile rows start at multiples of 32)
+    const int a_off = (wm * TM * 32 + frag_row) * 64;
+    const int b_off = BM * 64 + (wn * TN * 32 + frag_row) * 64;
+    const int slot_ks0 = (frag_half ^ sw) * 16, slot_ks1 = ((2 + frag_half) ^ sw) * 16;
+
+#pragma unroll
+    for (int s = 0; s < S - 1; ++s)
+        if (s < nk) issue(s, s);
+
+    QL_PHASE(1)
+    // Software pipeline over the two 32-wide halves of a K step.  While the MFMAs of one half run, the
+    // fragments of the next half are already being read from LDS; the s_barrier that hands over the next
+    // K step sits between the two MFMA batches, so no wavefront waits on LDS right after it.
+    v4i af0[TM], bf0[TN], af1[TM], bf1[TN];
+    auto read_frags = [&](int sl, int so, v4i(&af)[TM], v4i(&bf)[TN]) {
+        const unsigned char *st = smem + sl * T::STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const v4i *>(st + a_off + i * 32 * 64 + so);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bf[j] = *reinterpret_cast<const v4i *>(st + b_off + j * 32 * 64 + so);
+    };
+    // MFMAs number [first, last) of one half step, in (i, j) order
+    auto mma = [&](const v4i(&af)[TM], const v4i(&bf)[TN], int first, int last) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                if (i * TN + j >= first && i * TN + j < last)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+    };
+    constexpr int NMMA = TM * TN;
+    constexpr int CUT = NMMA >= 4 ? NMMA / 2 : 1;  // where the hand-over barrier goes inside the first batch
+    // K step 0 has landed once at most S-2 later steps are outstanding
+    if (nk >= S - 1) wait_steps(std::integral_constant<int, S - 2>{});
+    else wait_steps(std::integral_constant<int, 0>{});
+    __builtin_amdgcn_s_barrier();
+    read_frags(0, slot_ks0, af0, bf0);
+    int slot = 0, fill = S - 1;
+    for (int kt = 0; kt < nk; ++kt) {
+        // every non-MFMA instruction of the step is tucked behind an MFMA that is already executing
+        mma(af0, bf0, 0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(slot, slot_ks1, af1, bf1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(af0, bf0, 1, CUT);
+        __builtin_amdgcn_sched_barrier(0);
+        // K step kt+1 must be in LDS: steps up to kt+S-2 were issued, so S-3 of them may still be in flight
+        if (kt + S - 1 <= nk) wait_steps(std::integral_constant<int, S - 3>{});
+        else wait_steps(std::integral_constant<int, 0>{});
+        __builtin_amdgcn_s_barrier();  // everyone sees step kt+1; everyone has finished reading step kt-1
+        if (kt + S - 1 < nk) issue(kt + S - 1, fill);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(af0, bf0, CUT, NMMA);
+        mma(af1, bf1, 0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        const int next = slot + 1 == S ? 0 : slot + 1;
+        if (kt + 1 < nk) read_frags(next, slot_ks0, af0, bf0);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(af1, bf1, 1, NMMA);
+        __builtin_amdgcn_sched_barrier(0);
+        slot = next;
+        fill = fill + 1 == S ? 0 : fill + 1;
+    }
+    QL_PHASE(2)
+    __syncthreads();
+
+    float *sRow = reinterpret_cast<float *>(smem);
+    for (int t = tid; t < BM; t += NT) sRow[t] = a.s_a[min(m0 + t, M - 1) / a.R];
+    __syncthreads();
+    QL_PHASE(3)
+    _Float16 *y = static_cast<_Float16 *>(a.y);
+    const unsigned short *bias = static_cast<const unsigned short *>(a.bias);
+    const bool full = (m0 + BM <= M) && (n0 + BN <= N);
+    if (full && (N % 8) == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0 && !a.acc_out) {
+        float swt[TN], bj[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = n0 + wn * TN * 32 + j * 32 + frag_row;
+            swt[j] = static_cast<const float *>(a.s_w)[n];
+            bj[j] = bias ? half_to_float_dev(bias[n]) : 0.0f;
+        }
+        unsigned char *strip = smem + T::STRIP_OFF + wave * T::STRIP_BYTES;
+        const float *sr = sRow + wm * TM * 32 + 4 * frag_half;
+        if (bias)
+            store_tile_staged<TM, TN>(strip, lane, y, N, m0 + wm * TM * 32, n0 + wn * TN * 32, [&](int i, int j, int r) {
+                return __builtin_fmaf((float)acc[i][j][r] * sr[i * 32 + 8 * (r / 4) + (r % 4)], swt[j], bj[j]);
+            });
+        else
+            store_tile_staged<TM, TN>(strip, lane, y, N, m0 + wm * TM * 32, n0 + wn * TN * 32, [&](int i, int j, int r) {
+                return (float)acc[i][j][r] * sr[i * 32 + 8 * (r / 4) + (r % 4)] * swt[j];
+            });
+    } else {
+        auto emit = [&](auto edge) {
+            constexpr bool EDGE = decltype(edge)::value;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int n = n0 + wn * TN * 32 + j * 32 + frag_row;
+                const bool n_ok = !EDGE || n < N;
+                const float swt = n_ok ? static_cast<const float *>(a.s_w)[n] : 1.0f;
+                const float b = (bias && n_ok) ? half_to_float_dev(bias[n]) : 0.0f;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int row = wm * TM * 32 + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
+                        const int m = m0 + row;
+                        if (!EDGE || (m < M && n_ok)) {
+                            const unsigned off = (unsigned)(m * N + n);
+                            const float t = (float)acc[i][j][r] * sRow[row];
+                            const float u = bias ? __builtin_fmaf(t, swt, b) : t * swt;
+                            if (a.acc_out) a.acc_out[off] = acc[i][j][r];
+                            y[off] = (_Float16)u;
+                        }
+                    }
+            }
+        };
+        if (full) emit(std::false_type{});
+        else emit(std::true_type{});
+    }
+    QL_PHASE(4)
+}
+
+template <class T>
+static hipError_t run_dma(const GemmArgs &a, hipStream_t s)
+{
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (T::LDS_BYTES > 64 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&qgemm_dma<T>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+            if (e != hipSuccess) return e;
+        }
+        attr_set = true;
+    }
+    const int tiles_m = (a.M + T::BM - 1) / T::BM, tiles_n = (a.N + T::BN - 1) / T::BN;
+    const int nblk = tiles_m * tiles_n;
+    const int padded = (nblk + XCDS - 1) / XCDS * XCDS;
+    hipLaunchKernelGGL(qgemm_dma<T>, dim3(padded), dim3(T::NT), T::LDS_BYTES, s, a, tiles_m, tiles_n, padded);
+    return hipGetLastError();
+}
+
 // Any shape, no alignment needs: one thread per output element.
 __global__ __launch_bounds__(256) void qgemm_naive(GemmArgs a)
 {
@@ -318,7 +596,33 @@ using W4_64x128_k128 = Tile<1, 2, 2, 2, 128, true, 2>;
 using W4_256x128_8w = Tile<2, 2, 4, 2, 128, true, 2>;
 using W4_128x64_k128 = Tile<2, 1, 2, 2, 128, true, 3>;
 
+//                          TM TN WGM WGN S WPS
+using D8_128x128_s4 = TileD<2, 2, 2, 2, 4, 2>;
+using D8_128x192_s4 = TileD<2, 3, 2, 2, 4, 2>;
+using D8_128x192_s3 = TileD<2, 3, 2, 2, 3, 2>;
+using D8_256x128_s4 = TileD<4, 2, 2, 2, 4, 2>;
+using D8_256x192_s4 = TileD<4, 3, 2, 2, 4, 1>;
+using D8_256x192_s5 = TileD<4, 3, 2, 2, 5, 1>;
+using D8_256x256_8w = TileD<4, 2, 2, 4, 4, 2>;
+using D8_64x64_s4 = TileD<1, 1, 2, 2, 4, 4>;
+using D8_128x128_s3 = TileD<2, 2, 2, 2, 3, 3>;
+using D8_256x192_8w = TileD<2, 3, 4, 2, 4, 2>;
+using D8_256x192_8w_s3 = TileD<2, 3, 4, 2, 3, 2>;
+using D8_128x64_s3 = TileD<2, 1, 2, 2, 3, 4>;
+
 static const Variant VARIANTS[] = {
+    {"w8 dma 128x128 s4 4w", 8, 128, 128, 64, run_dma<D8_128x128_s4>},
+    {"w8 dma 128x192 s4 4w", 8, 128, 192, 64, run_dma<D8_128x192_s4>},
+    {"w8 dma 128x192 s3 4w", 8, 128, 192, 64, run_dma<D8_128x192_s3>},
+    {"w8 dma 256x128 s4 4w", 8, 256, 128, 64, run_dma<D8_256x128_s4>},
+    {"w8 dma 256x192 s4 4w", 8, 256, 192, 64, run_dma<D8_256x192_s4>},
+    {"w8 dma 256x192 s5 4w", 8, 256, 192, 64, run_dma<D8_256x192_s5>},
+    {"w8 dma 256x256 s4 8w", 8, 256, 256, 64, run_dma<D8_256x256_8w>},
+    {"w8 dma 64x64 s4 4w", 8, 64, 64, 64, run_dma<D8_64x64_s4>},
+    {"w8 dma 128x128 s3 4w occ3", 8, 128, 128, 64, run_dma<D8_128x128_s3>},
+    {"w8 dma 256x192 s4 8w", 8, 256, 192, 64, run_dma<D8_256x192_8w>},
+    {"w8 dma 256x192 s3 8w", 8, 256, 192, 64, run_dma<D8_256x192_8w_s3>},
+    {"w8 dma 128x64 s3 4w occ4", 8, 128, 64, 64, run_dma<D8_128x64_s3>},
     {"w8 128x128 bk64 4w occ2", 8, 128, 128, 64, run_variant<W8_128x128_k64>},
     {"w8 128x128 bk128 4w occ2", 8, 128, 128, 128, run_variant<W8_128x128_k128>},
     {"w8 256x128 bk64 4w occ2", 8, 256, 128, 64, run_variant<W8_256x128_k64>},
@@ -340,8 +644,8 @@ const char *gemm_variant_name(int v) { return (v >= 0 && v < NUM_VARIANTS) ? VAR
 
 static int choose_variant(const GemmArgs &a)
 {
-    if (a.w_bits == 8) return a.M >= 4096 ? 2 : 0;
-    return 9;
+    if (a.w_bits == 8) return a.M >= 4096 ? 14 : 12;
+    return 21;
 }
 
 hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream)
