@@ -288,26 +288,29 @@ __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane
 
 // ---------------------------------------------------------------------------------------------
 // Pipelined variant: tiles go from global memory straight into LDS (global_load_lds_dwordx4, no
-// register staging) through a ring of S stages, so S-1 K steps of loads are in flight while one
-// is being multiplied; one s_barrier per K step.  One K step is 64 int8 = one 64-byte LDS row.
-// The 16-byte chunk c of row r is kept at slot c ^ ((r >> 2) & 3) of its row: rows are unpadded
-// (a wavefront's DMA writes 1024 contiguous bytes = 16 rows), and the XOR spreads the 16 lanes
-// that read the same chunk index of 16 consecutive rows over all 64 banks.
+// register staging) through a ring of S stages.  One K step is 128 int8 = one 128-byte LDS row, so
+// every DMA instruction moves 8 rows x 128 contiguous bytes (whole cache lines; 64-byte pieces were
+// measured at little more than half the L1 fill rate).  The 16-byte chunk c of row r is kept at slot
+// c ^ ((r >> 1) & 7) of its row: rows are unpadded (a wavefront's DMA writes 1024 contiguous bytes),
+// and the XOR spreads the 16 lanes that read one chunk index of 16 consecutive rows over all banks.
+// The K step is multiplied in four 32-wide quarters with double-buffered fragments: the reads of
+// the next quarter, the hand-over barrier and the next DMA issue all sit behind an MFMA that is
+// already executing.
 // ---------------------------------------------------------------------------------------------
 template <int TM_, int TN_, int WGM_, int WGN_, int S_, int WPS_>
 struct TileD {
     static constexpr int TM = TM_, TN = TN_, WGM = WGM_, WGN = WGN_, S = S_, WPS = WPS_;
     static constexpr int NW = WGM * WGN, NT = NW * 64;
-    static constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32, BK = 64;
-    static constexpr int GROUPS = (BM + BN) / 16;         // 16-row DMA groups per K step (A rows first, then B rows)
+    static constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32, BK = 128;
+    static constexpr int GROUPS = (BM + BN) / 8;          // 8-row DMA groups per K step (A rows first, then W rows)
     static constexpr int LPT = (GROUPS + NW - 1) / NW;     // DMA instructions per wavefront per K step ...
     static constexpr int REM = GROUPS % NW;                // ... except that wavefronts >= REM issue one less when REM != 0
-    static constexpr int STAGE_BYTES = (BM + BN) * 64;
+    static constexpr int STAGE_BYTES = (BM + BN) * 128;
     static constexpr int STRIP_OFF = (BM * 4 + 255) / 256 * 256;   // epilogue: row scales first, then one strip per wavefront
     static constexpr int STRIP_BYTES = 32 * (TN * 64 + 16);
     static constexpr int LDS_BYTES = S * STAGE_BYTES > STRIP_OFF + NW * STRIP_BYTES ? S * STAGE_BYTES : STRIP_OFF + NW * STRIP_BYTES;
-    static_assert(S >= 3 && (S - 2) * LPT <= 63, "vmcnt is a 6-bit counter");
-    static_assert(BM * 4 <= LDS_BYTES, "row-scale staging reuses the ring");
+    static_assert(S >= 2 && (S - 1) * LPT <= 63, "vmcnt is a 6-bit counter");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS of one CU");
 };
 
 typedef __attribute__((address_space(3))) void lds_void;
@@ -333,30 +336,31 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it in a scalar register
     const int wm = wave / T::WGN, wn = wave % T::WGN;
     const int M = a.M, N = a.N, K = a.K;
-    const int nk = K / 64;
+    const int nk = K / 128;
     QL_PHASE(0)
 
-    // DMA addressing: lane l of a wavefront fills bytes [16 l, 16 l + 16) of a 1024-byte group = row l/4, slot l%4
-    // Group g covers stage rows [16 g, 16 g + 16): A rows for g < BM/16, W rows after.  Wavefront w takes g = w, w+NW, ...
+    // DMA addressing: lane l of a wavefront fills bytes [16 l, 16 l + 16) of a 1024-byte group = row l/8, slot l%8.
+    // Group g covers stage rows [8 g, 8 g + 8): A rows for g < BM/8, W rows after.  Wavefront w takes g = w, w+NW, ...
     const int my_loads = (T::REM == 0 || wave < T::REM) ? T::LPT : T::LPT - 1;
-    const int8_t *gbase[T::LPT];
     unsigned goff[T::LPT];
 #pragma unroll
     for (int i = 0; i < T::LPT; ++i) {
         const int g = min(wave + i * NW, T::GROUPS - 1);
-        const int row = 16 * g + (lane >> 2);
-        const int c = (lane & 3) ^ ((row >> 2) & 3);
-        const bool is_a = g < BM / 16;
-        gbase[i] = is_a ? a.q : static_cast<const int8_t *>(a.w);
+        const int row = 8 * g + (lane >> 3);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
+        const bool is_a = g < BM / 8;
         goff[i] = (unsigned)((is_a ? min(m0 + row, M - 1) : min(n0 + row - BM, N - 1)) * K + 16 * c);
     }
     auto issue = [&](int kt, int slot) {
         unsigned char *st = smem + slot * T::STAGE_BYTES;
+        const int8_t *qa = a.q + (size_t)kt * 128;
+        const int8_t *wb = static_cast<const int8_t *>(a.w) + (size_t)kt * 128;
 #pragma unroll
         for (int i = 0; i < T::LPT; ++i)
-            if (i < my_loads)
-                __builtin_amdgcn_global_load_lds((global_void *)(gbase[i] + (size_t)kt * 64 + goff[i]),
-                                                 (lds_void *)(st + (wave + i * NW) * 1024), 16, 0, 0);
+            if (i < my_loads) {
+                const int8_t *base = (wave + i * NW) < BM / 8 ? qa : wb;  // wave-uniform choice
+                __builtin_amdgcn_global_load_lds((global_void *)(base + goff[i]), (lds_void *)(st + (wave + i * NW) * 1024), 16, 0, 0);
+            }
     };
     // wait until at most n K steps of this wavefront's loads are still in flight (n is a compile-time constant)
     auto wait_steps = [&](auto n_tag) {
@@ -373,29 +377,20 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
+    // fragment of a lane: row (lane & 31) of a 32-row tile, 16 k starting at 32 * quarter + 16 * (lane >> 5)
     const int frag_row = lane & 31, frag_half = lane >> 5;
-    const int sw = (lane >> 2) & 3;  // swizzle key of this lane's row (tile rows start at multiples of 32)
-    const int a_off = (wm * TM * 32 + frag_row) * 64;
-    const int b_off = BM * 64 + (wn * TN * 32 + frag_row) * 64;
-    const int slot_ks0 = (frag_half ^ sw) * 16, slot_ks1 = ((2 + frag_half) ^ sw) * 16;
-
-#pragma unroll
-    for (int s = 0; s < S - 1; ++s)
-        if (s < nk) issue(s, s);
-
-    QL_PHASE(1)
-    // Software pipeline over the two 32-wide halves of a K step.  While the MFMAs of one half run, the
-    // fragments of the next half are already being read from LDS; the s_barrier that hands over the next
-    // K step sits between the two MFMA batches, so no wavefront waits on LDS right after it.
-    v4i af0[TM], bf0[TN], af1[TM], bf1[TN];
-    auto read_frags = [&](int sl, int so, v4i(&af)[TM], v4i(&bf)[TN]) {
+    const int key = (lane >> 1) & 7;  // swizzle key of this lane's row (tile rows start at multiples of 32)
+    const int a_off = (wm * TM * 32 + frag_row) * 128;
+    const int b_off = BM * 128 + (wn * TN * 32 + frag_row) * 128;
+    auto read_frags = [&](int sl, int quarter, v4i(&af)[TM], v4i(&bf)[TN]) {
         const unsigned char *st = smem + sl * T::STAGE_BYTES;
+        const int so = ((2 * quarter + frag_half) ^ key) * 16;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const v4i *>(st + a_off + i * 32 * 64 + so);
+        for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const v4i *>(st + a_off + i * 32 * 128 + so);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bf[j] = *reinterpret_cast<const v4i *>(st + b_off + j * 32 * 64 + so);
+        for (int j = 0; j < TN; ++j) bf[j] = *reinterpret_cast<const v4i *>(st + b_off + j * 32 * 128 + so);
     };
-    // MFMAs number [first, last) of one half step, in (i, j) order
+    // MFMAs number [first, last) of one quarter, in (i, j) order
     auto mma = [&](const v4i(&af)[TM], const v4i(&bf)[TN], int first, int last) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -405,37 +400,55 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
     };
     constexpr int NMMA = TM * TN;
-    constexpr int CUT = NMMA >= 4 ? NMMA / 2 : 1;  // where the hand-over barrier goes inside the first batch
-    // K step 0 has landed once at most S-2 later steps are outstanding
-    if (nk >= S - 1) wait_steps(std::integral_constant<int, S - 2>{});
+
+#pragma unroll
+    for (int s = 0; s < S; ++s)
+        if (s < nk) issue(s, s);
+    QL_PHASE(1)
+    v4i af0[TM], bf0[TN], af1[TM], bf1[TN];
+    // K step 0 has landed once at most S-1 later steps are outstanding
+    if (nk >= S) wait_steps(std::integral_constant<int, S - 1>{});
     else wait_steps(std::integral_constant<int, 0>{});
     __builtin_amdgcn_s_barrier();
-    read_frags(0, slot_ks0, af0, bf0);
-    int slot = 0, fill = S - 1;
+    read_frags(0, 0, af0, bf0);
+    int slot = 0;
     for (int kt = 0; kt < nk; ++kt) {
-        // every non-MFMA instruction of the step is tucked behind an MFMA that is already executing
+        const int next = slot + 1 == S ? 0 : slot + 1;
+        // quarter 0 (fragments 0) while reading quarter 1 (fragments 1)
         mma(af0, bf0, 0, 1);
         __builtin_amdgcn_sched_barrier(0);
-        read_frags(slot, slot_ks1, af1, bf1);
+        read_frags(slot, 1, af1, bf1);
         __builtin_amdgcn_sched_barrier(0);
-        mma(af0, bf0, 1, CUT);
+        mma(af0, bf0, 1, NMMA);
         __builtin_amdgcn_sched_barrier(0);
-        // K step kt+1 must be in LDS: steps up to kt+S-2 were issued, so S-3 of them may still be in flight
-        if (kt + S - 1 <= nk) wait_steps(std::integral_constant<int, S - 3>{});
-        else wait_steps(std::integral_constant<int, 0>{});
-        __builtin_amdgcn_s_barrier();  // everyone sees step kt+1; everyone has finished reading step kt-1
-        if (kt + S - 1 < nk) issue(kt + S - 1, fill);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(af0, bf0, CUT, NMMA);
+        // quarter 1 while reading quarter 2
         mma(af1, bf1, 0, 1);
         __builtin_amdgcn_sched_barrier(0);
-        const int next = slot + 1 == S ? 0 : slot + 1;
-        if (kt + 1 < nk) read_frags(next, slot_ks0, af0, bf0);
+        read_frags(slot, 2, af0, bf0);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(af1, bf1, 1, NMMA);
+        __builtin_amdgcn_sched_barrier(0);
+        // quarter 2 while reading quarter 3
+        mma(af0, bf0, 0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(slot, 3, af1, bf1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(af0, bf0, 1, NMMA);
+        __builtin_amdgcn_sched_barrier(0);
+        // quarter 3: its first MFMA needs the last fragments of this K step, so once it has issued every read of
+        // this stage by this wavefront is complete.  Then hand over: step kt+1 must be in LDS (steps up to kt+S-1
+        // were issued, so S-2 of them may still be in flight), and after the barrier this stage can be refilled.
+        mma(af1, bf1, 0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (kt + S <= nk) wait_steps(std::integral_constant<int, (S >= 2 ? S - 2 : 0)>{});
+        else wait_steps(std::integral_constant<int, 0>{});
+        __builtin_amdgcn_s_barrier();
+        if (kt + S < nk) issue(kt + S, slot);
+        if (kt + 1 < nk) read_frags(next, 0, af0, bf0);
         __builtin_amdgcn_sched_barrier(0);
         mma(af1, bf1, 1, NMMA);
         __builtin_amdgcn_sched_barrier(0);
         slot = next;
-        fill = fill + 1 == S ? 0 : fill + 1;
     }
     QL_PHASE(2)
     __syncthreads();
@@ -597,32 +610,28 @@ using W4_256x128_8w = Tile<2, 2, 4, 2, 128, true, 2>;
 using W4_128x64_k128 = Tile<2, 1, 2, 2, 128, true, 3>;
 
 //                          TM TN WGM WGN S WPS
-using D8_128x128_s4 = TileD<2, 2, 2, 2, 4, 2>;
-using D8_128x192_s4 = TileD<2, 3, 2, 2, 4, 2>;
+using D8_128x128_s3 = TileD<2, 2, 2, 2, 3, 2>;
+using D8_128x128_s2 = TileD<2, 2, 2, 2, 2, 2>;
 using D8_128x192_s3 = TileD<2, 3, 2, 2, 3, 2>;
-using D8_256x128_s4 = TileD<4, 2, 2, 2, 4, 2>;
-using D8_256x192_s4 = TileD<4, 3, 2, 2, 4, 1>;
-using D8_256x192_s5 = TileD<4, 3, 2, 2, 5, 1>;
-using D8_256x256_8w = TileD<4, 2, 2, 4, 4, 2>;
+using D8_128x192_s2 = TileD<2, 3, 2, 2, 2, 2>;
+using D8_256x128_s3 = TileD<4, 2, 2, 2, 3, 1>;
+using D8_256x192_s2 = TileD<4, 3, 2, 2, 2, 1>;
+using D8_256x256_s2 = TileD<4, 4, 2, 2, 2, 1>;
+using D8_256x256_8w = TileD<4, 2, 2, 4, 2, 2>;
+using D8_256x192_8w = TileD<2, 3, 4, 2, 2, 2>;
 using D8_64x64_s4 = TileD<1, 1, 2, 2, 4, 4>;
-using D8_128x128_s3 = TileD<2, 2, 2, 2, 3, 3>;
-using D8_256x192_8w = TileD<2, 3, 4, 2, 4, 2>;
-using D8_256x192_8w_s3 = TileD<2, 3, 4, 2, 3, 2>;
-using D8_128x64_s3 = TileD<2, 1, 2, 2, 3, 4>;
 
 static const Variant VARIANTS[] = {
-    {"w8 dma 128x128 s4 4w", 8, 128, 128, 64, run_dma<D8_128x128_s4>},
-    {"w8 dma 128x192 s4 4w", 8, 128, 192, 64, run_dma<D8_128x192_s4>},
-    {"w8 dma 128x192 s3 4w", 8, 128, 192, 64, run_dma<D8_128x192_s3>},
-    {"w8 dma 256x128 s4 4w", 8, 256, 128, 64, run_dma<D8_256x128_s4>},
-    {"w8 dma 256x192 s4 4w", 8, 256, 192, 64, run_dma<D8_256x192_s4>},
-    {"w8 dma 256x192 s5 4w", 8, 256, 192, 64, run_dma<D8_256x192_s5>},
-    {"w8 dma 256x256 s4 8w", 8, 256, 256, 64, run_dma<D8_256x256_8w>},
-    {"w8 dma 64x64 s4 4w", 8, 64, 64, 64, run_dma<D8_64x64_s4>},
-    {"w8 dma 128x128 s3 4w occ3", 8, 128, 128, 64, run_dma<D8_128x128_s3>},
-    {"w8 dma 256x192 s4 8w", 8, 256, 192, 64, run_dma<D8_256x192_8w>},
-    {"w8 dma 256x192 s3 8w", 8, 256, 192, 64, run_dma<D8_256x192_8w_s3>},
-    {"w8 dma 128x64 s3 4w occ4", 8, 128, 64, 64, run_dma<D8_128x64_s3>},
+    {"w8 dma 128x128 s3 4w", 8, 128, 128, 128, run_dma<D8_128x128_s3>},
+    {"w8 dma 128x128 s2 4w", 8, 128, 128, 128, run_dma<D8_128x128_s2>},
+    {"w8 dma 128x192 s3 4w", 8, 128, 192, 128, run_dma<D8_128x192_s3>},
+    {"w8 dma 128x192 s2 4w", 8, 128, 192, 128, run_dma<D8_128x192_s2>},
+    {"w8 dma 256x128 s3 4w", 8, 256, 128, 128, run_dma<D8_256x128_s3>},
+    {"w8 dma 256x192 s2 4w", 8, 256, 192, 128, run_dma<D8_256x192_s2>},
+    {"w8 dma 256x256 s2 4w", 8, 256, 256, 128, run_dma<D8_256x256_s2>},
+    {"w8 dma 256x256 s2 8w", 8, 256, 256, 128, run_dma<D8_256x256_8w>},
+    {"w8 dma 256x192 s2 8w", 8, 256, 192, 128, run_dma<D8_256x192_8w>},
+    {"w8 dma 64x64 s4 4w", 8, 64, 64, 128, run_dma<D8_64x64_s4>},
     {"w8 128x128 bk64 4w occ2", 8, 128, 128, 64, run_variant<W8_128x128_k64>},
     {"w8 128x128 bk128 4w occ2", 8, 128, 128, 128, run_variant<W8_128x128_k128>},
     {"w8 256x128 bk64 4w occ2", 8, 256, 128, 64, run_variant<W8_256x128_k64>},
@@ -644,8 +653,8 @@ const char *gemm_variant_name(int v) { return (v >= 0 && v < NUM_VARIANTS) ? VAR
 
 static int choose_variant(const GemmArgs &a)
 {
-    if (a.w_bits == 8) return a.M >= 4096 ? 14 : 12;
-    return 21;
+    if (a.w_bits == 8) return a.M >= 4096 ? 12 : 10;
+    return 19;
 }
 
 hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream)
