@@ -651,10 +651,24 @@ constexpr int NUM_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);
 int num_gemm_variants() { return NUM_VARIANTS; }
 const char *gemm_variant_name(int v) { return (v >= 0 && v < NUM_VARIANTS) ? VARIANTS[v].name : "naive (any shape)"; }
 
+static int find_variant(const char *name)
+{
+    for (int v = 0; v < NUM_VARIANTS; ++v)
+        if (__builtin_strcmp(VARIANTS[v].name, name) == 0) return v;
+    return 0;
+}
+
+// Tile choice by shape, from sweeps over the DiT-XL/2 layer shapes on MI355X.
 static int choose_variant(const GemmArgs &a)
 {
-    if (a.w_bits == 8) return a.M >= 4096 ? 12 : 10;
-    return 19;
+    static const int w8_small = find_variant("w8 dma 64x64 s4 4w"), w8_mid = find_variant("w8 dma 128x128 s2 4w"),
+                     w8_big = find_variant("w8 dma 256x192 s2 8w"), w8_k64 = find_variant("w8 128x128 bk64 4w occ3"),
+                     w4_any = find_variant("w4 128x64 bk128 4w occ3");
+    if (a.w_bits == 4) return w4_any;
+    if (a.K % 128 != 0) return w8_k64;
+    if (a.M <= 512) return w8_small;
+    if (a.M < 4096) return w8_mid;
+    return w8_big;
 }
 
 hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream)
