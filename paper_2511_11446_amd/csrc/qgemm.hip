@@ -253,36 +253,57 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
 // TN*64 bytes instead of 2-byte elements.
 //   value(i, j, r) -> fp32 result before the fp16 rounding (W8: fma(float(acc)*s_a, s_w, bias))
 // ---------------------------------------------------------------------------------------------
-template <int TM, int TN, class ValueFn>
+// The MFMA result layout gives a lane ONE column (lane & 31) and 16 rows.  Two neighbouring lanes swap
+// one value per pair of consecutive rows (DPP quad_perm), so that the even lane ends up with columns
+// (n, n+1) of the even row and the odd lane with columns (n-1, n) of the odd row: every element then
+// leaves the lane as half of a 4-byte word instead of a 2-byte store.
+//   STAGED: the words go to the LDS strip and are read back as 16-byte pieces (whole row segments per store);
+//   otherwise they are stored to global memory directly (64-byte row segments per half wavefront).
+template <int TM, int TN, bool STAGED, class ValueFn>
 __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane, _Float16 *y, int N, int m_base, int n_base,
                                                   ValueFn value)
 {
     constexpr int PITCH = TN * 64 + 16;
     constexpr int CH = TN * 4;  // 16-byte pieces per row
-    const int frag_row = lane & 31, frag_half = lane >> 5;
-    unsigned char *wr = strip + (4 * frag_half) * PITCH + frag_row * 2;
+    const int frag_row = lane & 31, frag_half = lane >> 5, odd = lane & 1;
+    // v_perm_b32 selector: bytes of {hi source = neighbour's pair, lo source = own pair}
+    //   even lane: (own.lo16, nbr.lo16) -> bytes 0,1 of own then 0,1 of neighbour = 0x05040100
+    //   odd lane:  (nbr.hi16, own.hi16) -> bytes 2,3 of neighbour then 2,3 of own = 0x03020706
+    const unsigned sel = odd ? 0x03020706u : 0x05040100u;
+    unsigned char *wr = strip + (4 * frag_half + odd) * PITCH + (frag_row - odd) * 2;
+    const unsigned g_off = (unsigned)((m_base + 4 * frag_half + odd) * N + n_base + frag_row - odd);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float u = value(i, j, r);
+            for (int r = 0; r < 16; r += 2) {
+                float u0 = value(i, j, r), u1 = value(i, j, r + 1);
                 // keep the fp32 rounding of the fused multiply-add: without this the compiler may select a
                 // mixed-precision fma that rounds straight to fp16 (one rounding instead of the defined two)
-                asm volatile("" : "+v"(u));
-                const _Float16 h = (_Float16)u;
-                *reinterpret_cast<half_alias *>(wr + (8 * (r / 4) + (r % 4)) * PITCH + j * 64) = h;
+                asm volatile("" : "+v"(u0), "+v"(u1));
+                typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+                const h2 pr = {(_Float16)u0, (_Float16)u1};
+                const unsigned own = __builtin_bit_cast(unsigned, pr);
+                const unsigned nbr = (unsigned)__builtin_amdgcn_update_dpp(0, (int)own, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, false);
+                const unsigned word = __builtin_amdgcn_perm(nbr, own, sel);
+                const int row = 8 * (r / 4) + (r % 4);  // + 4*frag_half + odd, already in the lane's base
+                if (STAGED)
+                    *reinterpret_cast<unsigned __attribute__((may_alias)) *>(wr + row * PITCH + j * 64) = word;
+                else
+                    *reinterpret_cast<unsigned __attribute__((may_alias)) *>(y + (g_off + (unsigned)((i * 32 + row) * N + j * 32))) = word;
             }
-        asm volatile("" ::: "memory");  // the strip reads below see other lanes' writes: keep program order
+        if (STAGED) {
+            asm volatile("" ::: "memory");  // the strip reads below see other lanes' writes: keep program order
 #pragma unroll
-        for (int t = 0; t < 32 * CH / 64; ++t) {
-            const int id = lane + 64 * t;
-            const int row = id / CH, ch = id % CH;
-            const v4i v = *reinterpret_cast<const v4i_alias *>(strip + row * PITCH + ch * 16);
-            *reinterpret_cast<v4i_alias *>(y + (unsigned)((m_base + i * 32 + row) * N + n_base + ch * 8)) = v;
+            for (int t = 0; t < 32 * CH / 64; ++t) {
+                const int id = lane + 64 * t;
+                const int row = id / CH, ch = id % CH;
+                const v4i v = *reinterpret_cast<const v4i_alias *>(strip + row * PITCH + ch * 16);
+                *reinterpret_cast<v4i_alias *>(y + (unsigned)((m_base + i * 32 + row) * N + n_base + ch * 8)) = v;
+            }
+            asm volatile("" ::: "memory");
         }
-        asm volatile("" ::: "memory");
     }
 }
 
@@ -297,7 +318,7 @@ __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane
 // the next quarter, the hand-over barrier and the next DMA issue all sit behind an MFMA that is
 // already executing.
 // ---------------------------------------------------------------------------------------------
-template <int TM_, int TN_, int WGM_, int WGN_, int S_, int WPS_>
+template <int TM_, int TN_, int WGM_, int WGN_, int S_, int WPS_, bool STG_ = true>
 struct TileD {
     static constexpr int TM = TM_, TN = TN_, WGM = WGM_, WGN = WGN_, S = S_, WPS = WPS_;
     static constexpr int NW = WGM * WGN, NT = NW * 64;
@@ -306,6 +327,7 @@ struct TileD {
     static constexpr int LPT = (GROUPS + NW - 1) / NW;     // DMA instructions per wavefront per K step ...
     static constexpr int REM = GROUPS % NW;                // ... except that wavefronts >= REM issue one less when REM != 0
     static constexpr int STAGE_BYTES = (BM + BN) * 128;
+    static constexpr bool STAGED_STORE = STG_;
     static constexpr int STRIP_OFF = (BM * 4 + 255) / 256 * 256;   // epilogue: row scales first, then one strip per wavefront
     static constexpr int STRIP_BYTES = 32 * (TN * 64 + 16);
     static constexpr int LDS_BYTES = S * STAGE_BYTES > STRIP_OFF + NW * STRIP_BYTES ? S * STAGE_BYTES : STRIP_OFF + NW * STRIP_BYTES;
@@ -471,11 +493,11 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
         unsigned char *strip = smem + T::STRIP_OFF + wave * T::STRIP_BYTES;
         const float *sr = sRow + wm * TM * 32 + 4 * frag_half;
         if (bias)
-            store_tile_staged<TM, TN>(strip, lane, y, N, m0 + wm * TM * 32, n0 + wn * TN * 32, [&](int i, int j, int r) {
+            store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, m0 + wm * TM * 32, n0 + wn * TN * 32, [&](int i, int j, int r) {
                 return __builtin_fmaf((float)acc[i][j][r] * sr[i * 32 + 8 * (r / 4) + (r % 4)], swt[j], bj[j]);
             });
         else
-            store_tile_staged<TM, TN>(strip, lane, y, N, m0 + wm * TM * 32, n0 + wn * TN * 32, [&](int i, int j, int r) {
+            store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, m0 + wm * TM * 32, n0 + wn * TN * 32, [&](int i, int j, int r) {
                 return (float)acc[i][j][r] * sr[i * 32 + 8 * (r / 4) + (r % 4)] * swt[j];
             });
     } else {
@@ -619,6 +641,8 @@ using D8_256x192_s2 = TileD<4, 3, 2, 2, 2, 1>;
 using D8_256x256_s2 = TileD<4, 4, 2, 2, 2, 1>;
 using D8_256x256_8w = TileD<4, 2, 2, 4, 2, 2>;
 using D8_256x192_8w = TileD<2, 3, 4, 2, 2, 2>;
+using D8_256x192_8w_direct = TileD<2, 3, 4, 2, 2, 2, false>;
+using D8_128x192_s2_direct = TileD<2, 3, 2, 2, 2, 2, false>;
 using D8_64x64_s4 = TileD<1, 1, 2, 2, 4, 4>;
 
 static const Variant VARIANTS[] = {
@@ -632,6 +656,8 @@ static const Variant VARIANTS[] = {
     {"w8 dma 256x256 s2 8w", 8, 256, 256, 128, run_dma<D8_256x256_8w>},
     {"w8 dma 256x192 s2 8w", 8, 256, 192, 128, run_dma<D8_256x192_8w>},
     {"w8 dma 64x64 s4 4w", 8, 64, 64, 128, run_dma<D8_64x64_s4>},
+    {"w8 dma 256x192 s2 8w direct-store", 8, 256, 192, 128, run_dma<D8_256x192_8w_direct>},
+    {"w8 dma 128x192 s2 4w direct-store", 8, 128, 192, 128, run_dma<D8_128x192_s2_direct>},
     {"w8 128x128 bk64 4w occ2", 8, 128, 128, 64, run_variant<W8_128x128_k64>},
     {"w8 128x128 bk128 4w occ2", 8, 128, 128, 128, run_variant<W8_128x128_k128>},
     {"w8 256x128 bk64 4w occ2", 8, 256, 128, 64, run_variant<W8_256x128_k64>},
