@@ -318,7 +318,7 @@ __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane
 // the next quarter, the hand-over barrier and the next DMA issue all sit behind an MFMA that is
 // already executing.
 // ---------------------------------------------------------------------------------------------
-template <int TM_, int TN_, int WGM_, int WGN_, int S_, int WPS_, bool STG_ = true>
+template <int TM_, int TN_, int WGM_, int WGN_, int S_, int WPS_, bool STG_ = true, int EV_ = 0>
 struct TileD {
     static constexpr int TM = TM_, TN = TN_, WGM = WGM_, WGN = WGN_, S = S_, WPS = WPS_;
     static constexpr int NW = WGM * WGN, NT = NW * 64;
@@ -328,6 +328,7 @@ struct TileD {
     static constexpr int REM = GROUPS % NW;                // ... except that wavefronts >= REM issue one less when REM != 0
     static constexpr int STAGE_BYTES = (BM + BN) * 128;
     static constexpr bool STAGED_STORE = STG_;
+    static constexpr int DMA_EVERY = EV_;                 // one DMA instruction behind every EV_-th MFMA; 0: all at the hand-over
     static constexpr int STRIP_OFF = (BM * 4 + 255) / 256 * 256;   // epilogue: row scales first, then one strip per wavefront
     static constexpr int STRIP_BYTES = 32 * (TN * 64 + 16);
     static constexpr int LDS_BYTES = S * STAGE_BYTES > STRIP_OFF + NW * STRIP_BYTES ? S * STAGE_BYTES : STRIP_OFF + NW * STRIP_BYTES;
@@ -384,6 +385,11 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
                 __builtin_amdgcn_global_load_lds((global_void *)(base + goff[i]), (lds_void *)(st + (wave + i * NW) * 1024), 16, 0, 0);
             }
     };
+    auto issue_one = [&](int kt, int slot, int i) {
+        const int8_t *base = ((wave + i * NW) < BM / 8 ? a.q : static_cast<const int8_t *>(a.w)) + (size_t)kt * 128;
+        __builtin_amdgcn_global_load_lds((global_void *)(base + goff[i]),
+                                         (lds_void *)(smem + slot * T::STAGE_BYTES + (wave + i * NW) * 1024), 16, 0, 0);
+    };
     // wait until at most n K steps of this wavefront's loads are still in flight (n is a compile-time constant)
     auto wait_steps = [&](auto n_tag) {
         constexpr int n = decltype(n_tag)::value;
@@ -422,6 +428,28 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
     };
     constexpr int NMMA = TM * TN;
+    // The same, with one DMA instruction of K step kt_i slipped in after every EVERY-th MFMA, starting with load i0:
+    // 64 loads issued back to back fill the texture-address queue and stall the MFMA issue of every wavefront.
+    constexpr int EVERY = T::DMA_EVERY > 0 ? T::DMA_EVERY : 1;
+    constexpr bool SPREAD = T::DMA_EVERY > 0;
+    auto mma_dma = [&](const v4i(&af)[TM], const v4i(&bf)[TN], int first, int last, bool on, int kt_i, int slot_i, int i0) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int idx = i * TN + j;
+                if (idx >= first && idx < last) {
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+                    const int li = i0 + (idx - first) / EVERY;
+                    if (SPREAD && (idx - first) % EVERY == EVERY - 1 && li < T::LPT) {
+                        if (on && li < my_loads) issue_one(kt_i, slot_i, li);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            }
+    };
+    constexpr int N_Q = (NMMA - 1) / EVERY;    // loads that fit behind the MFMAs of one quarter
+    static_assert(!SPREAD || 3 * N_Q >= T::LPT, "the loads of a K step must be issued within three quarters");
 
 #pragma unroll
     for (int s = 0; s < S; ++s)
@@ -434,21 +462,23 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     __builtin_amdgcn_s_barrier();
     read_frags(0, 0, af0, bf0);
     int slot = 0;
+    bool refill = false;  // loads of K step kt-1+S into the previous slot are still being issued
     for (int kt = 0; kt < nk; ++kt) {
         const int next = slot + 1 == S ? 0 : slot + 1;
+        const int prev = slot == 0 ? S - 1 : slot - 1;
         // quarter 0 (fragments 0) while reading quarter 1 (fragments 1)
         mma(af0, bf0, 0, 1);
         __builtin_amdgcn_sched_barrier(0);
         read_frags(slot, 1, af1, bf1);
         __builtin_amdgcn_sched_barrier(0);
-        mma(af0, bf0, 1, NMMA);
+        mma_dma(af0, bf0, 1, NMMA, refill, kt - 1 + S, prev, N_Q);
         __builtin_amdgcn_sched_barrier(0);
         // quarter 1 while reading quarter 2
         mma(af1, bf1, 0, 1);
         __builtin_amdgcn_sched_barrier(0);
         read_frags(slot, 2, af0, bf0);
         __builtin_amdgcn_sched_barrier(0);
-        mma(af1, bf1, 1, NMMA);
+        mma_dma(af1, bf1, 1, NMMA, refill, kt - 1 + S, prev, 2 * N_Q);
         __builtin_amdgcn_sched_barrier(0);
         // quarter 2 while reading quarter 3
         mma(af0, bf0, 0, 1);
@@ -465,10 +495,11 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
         if (kt + S <= nk) wait_steps(std::integral_constant<int, (S >= 2 ? S - 2 : 0)>{});
         else wait_steps(std::integral_constant<int, 0>{});
         __builtin_amdgcn_s_barrier();
-        if (kt + S < nk) issue(kt + S, slot);
+        refill = kt + S < nk;
+        if (!SPREAD && refill) issue(kt + S, slot);
         if (kt + 1 < nk) read_frags(next, 0, af0, bf0);
         __builtin_amdgcn_sched_barrier(0);
-        mma(af1, bf1, 1, NMMA);
+        mma_dma(af1, bf1, 1, NMMA, refill, kt + S, slot, 0);
         __builtin_amdgcn_sched_barrier(0);
         slot = next;
     }
@@ -641,8 +672,10 @@ using D8_256x192_s2 = TileD<4, 3, 2, 2, 2, 1>;
 using D8_256x256_s2 = TileD<4, 4, 2, 2, 2, 1>;
 using D8_256x256_8w = TileD<4, 2, 2, 4, 2, 2>;
 using D8_256x192_8w = TileD<2, 3, 4, 2, 2, 2>;
-using D8_256x192_8w_direct = TileD<2, 3, 4, 2, 2, 2, false>;
-using D8_128x192_s2_direct = TileD<2, 3, 2, 2, 2, 2, false>;
+using D8_256x192_8w_e1 = TileD<2, 3, 4, 2, 2, 2, true, 1>;
+using D8_256x256_8w_e1 = TileD<4, 2, 2, 4, 2, 2, true, 1>;
+using D8_256x256_8w_e2 = TileD<4, 2, 2, 4, 2, 2, true, 2>;
+using D8_256x192_4w_e2 = TileD<4, 3, 2, 2, 2, 1, true, 2>;
 using D8_64x64_s4 = TileD<1, 1, 2, 2, 4, 4>;
 
 static const Variant VARIANTS[] = {
@@ -656,8 +689,10 @@ static const Variant VARIANTS[] = {
     {"w8 dma 256x256 s2 8w", 8, 256, 256, 128, run_dma<D8_256x256_8w>},
     {"w8 dma 256x192 s2 8w", 8, 256, 192, 128, run_dma<D8_256x192_8w>},
     {"w8 dma 64x64 s4 4w", 8, 64, 64, 128, run_dma<D8_64x64_s4>},
-    {"w8 dma 256x192 s2 8w direct-store", 8, 256, 192, 128, run_dma<D8_256x192_8w_direct>},
-    {"w8 dma 128x192 s2 4w direct-store", 8, 128, 192, 128, run_dma<D8_128x192_s2_direct>},
+    {"w8 dma 256x192 s2 8w spread1", 8, 256, 192, 128, run_dma<D8_256x192_8w_e1>},
+    {"w8 dma 256x256 s2 8w spread1", 8, 256, 256, 128, run_dma<D8_256x256_8w_e1>},
+    {"w8 dma 256x256 s2 8w spread2", 8, 256, 256, 128, run_dma<D8_256x256_8w_e2>},
+    {"w8 dma 256x192 s2 4w spread2", 8, 256, 192, 128, run_dma<D8_256x192_4w_e2>},
     {"w8 128x128 bk64 4w occ2", 8, 128, 128, 64, run_variant<W8_128x128_k64>},
     {"w8 128x128 bk128 4w occ2", 8, 128, 128, 128, run_variant<W8_128x128_k128>},
     {"w8 256x128 bk64 4w occ2", 8, 256, 128, 64, run_variant<W8_256x128_k64>},
