@@ -318,20 +318,25 @@ __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane
 // the next quarter, the hand-over barrier and the next DMA issue all sit behind an MFMA that is
 // already executing.
 // ---------------------------------------------------------------------------------------------
-template <int TM_, int TN_, int WGM_, int WGN_, int S_, int WPS_, bool STG_ = true, int EV_ = 0>
+template <int TM_, int TN_, int WGM_, int WGN_, int S_, int WPS_, bool STG_ = true, int EV_ = 0, bool W4_ = false>
 struct TileD {
     static constexpr int TM = TM_, TN = TN_, WGM = WGM_, WGN = WGN_, S = S_, WPS = WPS_;
+    static constexpr bool W4 = W4_;
     static constexpr int NW = WGM * WGN, NT = NW * 64;
     static constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32, BK = 128;
-    static constexpr int GROUPS = (BM + BN) / 8;          // 8-row DMA groups per K step (A rows first, then W rows)
+    // 1024-byte DMA groups per K step: A rows first (8 rows x 128 B), then W rows (8 x 128 B, or 16 x 64 B packed 4-bit)
+    static constexpr int A_GROUPS = BM / 8, B_GROUPS = W4 ? BN / 16 : BN / 8, GROUPS = A_GROUPS + B_GROUPS;
     static constexpr int LPT = (GROUPS + NW - 1) / NW;     // DMA instructions per wavefront per K step ...
     static constexpr int REM = GROUPS % NW;                // ... except that wavefronts >= REM issue one less when REM != 0
-    static constexpr int STAGE_BYTES = (BM + BN) * 128;
+    static constexpr int STAGE_BYTES = GROUPS * 1024;
     static constexpr bool STAGED_STORE = STG_;
     static constexpr int DMA_EVERY = EV_;                 // one DMA instruction behind every EV_-th MFMA; 0: all at the hand-over
     static constexpr int STRIP_OFF = (BM * 4 + 255) / 256 * 256;   // epilogue: row scales first, then one strip per wavefront
     static constexpr int STRIP_BYTES = 32 * (TN * 64 + 16);
-    static constexpr int LDS_BYTES = S * STAGE_BYTES > STRIP_OFF + NW * STRIP_BYTES ? S * STAGE_BYTES : STRIP_OFF + NW * STRIP_BYTES;
+    static constexpr int RING_BYTES = S * STAGE_BYTES > STRIP_OFF + NW * STRIP_BYTES ? S * STAGE_BYTES : STRIP_OFF + NW * STRIP_BYTES;
+    static constexpr int MAX_GROUPS_K = 40;               // 4-bit: group scales of the tile's columns live in LDS (K <= 5120)
+    static constexpr int SCALE_BYTES = W4 ? BN * MAX_GROUPS_K * 2 : 0;
+    static constexpr int LDS_BYTES = RING_BYTES + SCALE_BYTES;
     static_assert(S >= 2 && (S - 1) * LPT <= 63, "vmcnt is a 6-bit counter");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS of one CU");
 };
@@ -343,6 +348,7 @@ template <class T>
 __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles_m, int tiles_n, int nblk_padded)
 {
     constexpr int TM = T::TM, TN = T::TN, BM = T::BM, BN = T::BN, NT = T::NT, S = T::S, NW = T::NW;
+    constexpr bool W4 = T::W4;
     extern __shared__ __align__(1024) unsigned char smem[];
 
     const int per_xcd = nblk_padded / XCDS;
@@ -359,8 +365,17 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it in a scalar register
     const int wm = wave / T::WGN, wn = wave % T::WGN;
     const int M = a.M, N = a.N, K = a.K;
-    const int nk = K / 128;
+    const int nk = K / 128;   // K steps; for 4-bit weights also the number of weight groups
     QL_PHASE(0)
+
+    // 4-bit weights: the fp16 group scales of this tile's columns, [BN][nk], copied once (the first barrier of the
+    // pipeline below orders the copy before their first use at the end of K step 0)
+    unsigned short *sScale = reinterpret_cast<unsigned short *>(smem + T::RING_BYTES);
+    if (W4) {
+        const unsigned short *gsw = static_cast<const unsigned short *>(a.s_w);
+        for (int idx = tid; idx < BN * nk; idx += NT)
+            sScale[idx] = gsw[(size_t)min(n0 + idx / nk, N - 1) * nk + idx % nk];
+    }
 
     // DMA addressing: lane l of a wavefront fills bytes [16 l, 16 l + 16) of a 1024-byte group = row l/8, slot l%8.
     // Group g covers stage rows [8 g, 8 g + 8): A rows for g < BM/8, W rows after.  Wavefront w takes g = w, w+NW, ...
@@ -369,24 +384,32 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
 #pragma unroll
     for (int i = 0; i < T::LPT; ++i) {
         const int g = min(wave + i * NW, T::GROUPS - 1);
-        const int row = 8 * g + (lane >> 3);
-        const int c = (lane & 7) ^ ((row >> 1) & 7);
-        const bool is_a = g < BM / 8;
-        goff[i] = (unsigned)((is_a ? min(m0 + row, M - 1) : min(n0 + row - BM, N - 1)) * K + 16 * c);
+        const bool is_a = g < T::A_GROUPS;
+        if (is_a || !W4) {
+            const int row = 8 * g + (lane >> 3);            // stage row: A rows, then W rows
+            const int c = (lane & 7) ^ ((row >> 1) & 7);
+            goff[i] = (unsigned)((is_a ? min(m0 + row, M - 1) : min(n0 + row - BM, N - 1)) * K + 16 * c);
+        } else {
+            // packed 4-bit rows are 64 bytes per K step: 16 rows per group, chunk c of row r at slot c ^ ((r >> 2) & 3)
+            const int row = 16 * (g - T::A_GROUPS) + (lane >> 2);
+            const int c = (lane & 3) ^ ((row >> 2) & 3);
+            goff[i] = (unsigned)(min(n0 + row, N - 1) * (K / 2) + 16 * c);
+        }
     }
     auto issue = [&](int kt, int slot) {
         unsigned char *st = smem + slot * T::STAGE_BYTES;
         const int8_t *qa = a.q + (size_t)kt * 128;
-        const int8_t *wb = static_cast<const int8_t *>(a.w) + (size_t)kt * 128;
+        const int8_t *wb = static_cast<const int8_t *>(a.w) + (size_t)kt * (W4 ? 64 : 128);
 #pragma unroll
         for (int i = 0; i < T::LPT; ++i)
             if (i < my_loads) {
-                const int8_t *base = (wave + i * NW) < BM / 8 ? qa : wb;  // wave-uniform choice
+                const int8_t *base = (wave + i * NW) < T::A_GROUPS ? qa : wb;  // wave-uniform choice
                 __builtin_amdgcn_global_load_lds((global_void *)(base + goff[i]), (lds_void *)(st + (wave + i * NW) * 1024), 16, 0, 0);
             }
     };
     auto issue_one = [&](int kt, int slot, int i) {
-        const int8_t *base = ((wave + i * NW) < BM / 8 ? a.q : static_cast<const int8_t *>(a.w)) + (size_t)kt * 128;
+        const int8_t *base = (wave + i * NW) < T::A_GROUPS ? a.q + (size_t)kt * 128
+                                                            : static_cast<const int8_t *>(a.w) + (size_t)kt * (W4 ? 64 : 128);
         __builtin_amdgcn_global_load_lds((global_void *)(base + goff[i]),
                                          (lds_void *)(smem + slot * T::STAGE_BYTES + (wave + i * NW) * 1024), 16, 0, 0);
     };
@@ -404,42 +427,91 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+    // 4-bit weights: fp32 sum over the weight groups, f = sum_g fma(float(P_g), s_w[n,g], f)
+    float fsum[W4 ? TM : 1][W4 ? TN : 1][16];
+    if (W4) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) fsum[i][j][r] = 0.0f;
+    }
 
     // fragment of a lane: row (lane & 31) of a 32-row tile, 16 k starting at 32 * quarter + 16 * (lane >> 5)
     const int frag_row = lane & 31, frag_half = lane >> 5;
     const int key = (lane >> 1) & 7;  // swizzle key of this lane's row (tile rows start at multiples of 32)
+    const int key4 = (lane >> 2) & 3; // the same for the 64-byte rows of packed 4-bit weights
     const int a_off = (wm * TM * 32 + frag_row) * 128;
-    const int b_off = BM * 128 + (wn * TN * 32 + frag_row) * 128;
+    const int b_off = BM * 128 + (wn * TN * 32 + frag_row) * (W4 ? 64 : 128);
     auto read_frags = [&](int sl, int quarter, v4i(&af)[TM], v4i(&bf)[TN]) {
         const unsigned char *st = smem + sl * T::STAGE_BYTES;
         const int so = ((2 * quarter + frag_half) ^ key) * 16;
 #pragma unroll
         for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const v4i *>(st + a_off + i * 32 * 128 + so);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bf[j] = *reinterpret_cast<const v4i *>(st + b_off + j * 32 * 128 + so);
+        for (int j = 0; j < TN; ++j) {
+            if (W4) {
+                // 16 k of a quarter's half = 8 packed bytes; byte b of a word: low nibble = k b, high nibble = k 4+b
+                const v2i p = *reinterpret_cast<const v2i *>(st + b_off + j * 32 * 64 + ((quarter ^ key4) * 16) + frag_half * 8);
+                bf[j] = v4i{(int)(((unsigned)p[0] << 4) & 0xf0f0f0f0u), (int)((unsigned)p[0] & 0xf0f0f0f0u),
+                            (int)(((unsigned)p[1] << 4) & 0xf0f0f0f0u), (int)((unsigned)p[1] & 0xf0f0f0f0u)};  // int8 value * 16
+            } else {
+                bf[j] = *reinterpret_cast<const v4i *>(st + b_off + j * 32 * 128 + so);
+            }
+        }
     };
-    // MFMAs number [first, last) of one quarter, in (i, j) order
-    auto mma = [&](const v4i(&af)[TM], const v4i(&bf)[TN], int first, int last) {
+    // 4-bit weights: K step kt is weight group kt.  Its int32 partial sums (times 16) are folded into the fp32 sum
+    // right before the accumulator is restarted; the group scale carries the 1/16 (exact: a power of two).
+    int flush_group = -1;  // group whose partial sums are still in acc
+    auto flush_tile = [&](int i, int j) {
+        const int n_loc = wn * TN * 32 + j * 32 + frag_row;
+        const float s16 = half_to_float_dev(sScale[n_loc * nk + flush_group]) * 0.0625f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            if (a.acc_out) {
+                const int m = m0 + wm * TM * 32 + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4), n = n0 + n_loc;
+                if (m < M && n < N) a.acc_out[(unsigned)((m * nk + flush_group) * N + n)] = acc[i][j][r] >> 4;
+            }
+            fsum[W4 ? i : 0][W4 ? j : 0][r] = __builtin_fmaf((float)acc[i][j][r], s16, fsum[W4 ? i : 0][W4 ? j : 0][r]);
+        }
+    };
+    // MFMAs number [first, last) of one quarter, in (i, j) order; restart = first quarter of a 4-bit weight group
+    auto mma = [&](const v4i(&af)[TM], const v4i(&bf)[TN], int first, int last, bool restart = false) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                if (i * TN + j >= first && i * TN + j < last)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+                if (i * TN + j >= first && i * TN + j < last) {
+                    if (W4 && restart) {
+                        if (flush_group >= 0) flush_tile(i, j);
+                        const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], zero, 0, 0, 0);
+                    } else {
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+                    }
+                }
     };
     constexpr int NMMA = TM * TN;
     // The same, with one DMA instruction of K step kt_i slipped in after every EVERY-th MFMA, starting with load i0:
     // 64 loads issued back to back fill the texture-address queue and stall the MFMA issue of every wavefront.
     constexpr int EVERY = T::DMA_EVERY > 0 ? T::DMA_EVERY : 1;
     constexpr bool SPREAD = T::DMA_EVERY > 0;
-    auto mma_dma = [&](const v4i(&af)[TM], const v4i(&bf)[TN], int first, int last, bool on, int kt_i, int slot_i, int i0) {
+    auto mma_dma = [&](const v4i(&af)[TM], const v4i(&bf)[TN], int first, int last, bool on, int kt_i, int slot_i, int i0,
+                       bool restart = false) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int idx = i * TN + j;
                 if (idx >= first && idx < last) {
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+                    if (W4 && restart) {
+                        if (flush_group >= 0) flush_tile(i, j);
+                        const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], zero, 0, 0, 0);
+                    } else {
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+                    }
                     const int li = i0 + (idx - first) / EVERY;
                     if (SPREAD && (idx - first) % EVERY == EVERY - 1 && li < T::LPT) {
                         if (on && li < my_loads) issue_one(kt_i, slot_i, li);
@@ -467,11 +539,12 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
         const int next = slot + 1 == S ? 0 : slot + 1;
         const int prev = slot == 0 ? S - 1 : slot - 1;
         // quarter 0 (fragments 0) while reading quarter 1 (fragments 1)
-        mma(af0, bf0, 0, 1);
+        mma(af0, bf0, 0, 1, true);
         __builtin_amdgcn_sched_barrier(0);
         read_frags(slot, 1, af1, bf1);
         __builtin_amdgcn_sched_barrier(0);
-        mma_dma(af0, bf0, 1, NMMA, refill, kt - 1 + S, prev, N_Q);
+        mma_dma(af0, bf0, 1, NMMA, refill, kt - 1 + S, prev, N_Q, true);
+        flush_group = kt;
         __builtin_amdgcn_sched_barrier(0);
         // quarter 1 while reading quarter 2
         mma(af1, bf1, 0, 1);
@@ -503,6 +576,12 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
         __builtin_amdgcn_sched_barrier(0);
         slot = next;
     }
+    if (W4) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) flush_tile(i, j);
+    }
     QL_PHASE(2)
     __syncthreads();
 
@@ -513,17 +592,25 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     _Float16 *y = static_cast<_Float16 *>(a.y);
     const unsigned short *bias = static_cast<const unsigned short *>(a.bias);
     const bool full = (m0 + BM <= M) && (n0 + BN <= N);
-    if (full && (N % 8) == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0 && !a.acc_out) {
+    if (full && (N % 8) == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0 && (W4 || !a.acc_out)) {
         float swt[TN], bj[TN];
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int n = n0 + wn * TN * 32 + j * 32 + frag_row;
-            swt[j] = static_cast<const float *>(a.s_w)[n];
+            swt[j] = W4 ? 1.0f : static_cast<const float *>(a.s_w)[n];
             bj[j] = bias ? half_to_float_dev(bias[n]) : 0.0f;
         }
         unsigned char *strip = smem + T::STRIP_OFF + wave * T::STRIP_BYTES;
         const float *sr = sRow + wm * TM * 32 + 4 * frag_half;
-        if (bias)
+        if (W4 && bias)
+            store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, m0 + wm * TM * 32, n0 + wn * TN * 32, [&](int i, int j, int r) {
+                return __builtin_fmaf(fsum[W4 ? i : 0][W4 ? j : 0][r], sr[i * 32 + 8 * (r / 4) + (r % 4)], bj[j]);
+            });
+        else if (W4)
+            store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, m0 + wm * TM * 32, n0 + wn * TN * 32, [&](int i, int j, int r) {
+                return fsum[W4 ? i : 0][W4 ? j : 0][r] * sr[i * 32 + 8 * (r / 4) + (r % 4)];
+            });
+        else if (bias)
             store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, m0 + wm * TM * 32, n0 + wn * TN * 32, [&](int i, int j, int r) {
                 return __builtin_fmaf((float)acc[i][j][r] * sr[i * 32 + 8 * (r / 4) + (r % 4)], swt[j], bj[j]);
             });
@@ -538,7 +625,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
             for (int j = 0; j < TN; ++j) {
                 const int n = n0 + wn * TN * 32 + j * 32 + frag_row;
                 const bool n_ok = !EDGE || n < N;
-                const float swt = n_ok ? static_cast<const float *>(a.s_w)[n] : 1.0f;
+                const float swt = (!W4 && n_ok) ? static_cast<const float *>(a.s_w)[n] : 1.0f;
                 const float b = (bias && n_ok) ? half_to_float_dev(bias[n]) : 0.0f;
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
@@ -548,9 +635,16 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
                         const int m = m0 + row;
                         if (!EDGE || (m < M && n_ok)) {
                             const unsigned off = (unsigned)(m * N + n);
-                            const float t = (float)acc[i][j][r] * sRow[row];
-                            const float u = bias ? __builtin_fmaf(t, swt, b) : t * swt;
-                            if (a.acc_out) a.acc_out[off] = acc[i][j][r];
+                            float u;
+                            if (W4) {
+                                const float f = fsum[W4 ? i : 0][W4 ? j : 0][r];
+                                u = bias ? __builtin_fmaf(f, sRow[row], b) : f * sRow[row];
+                            } else {
+                                const float t = (float)acc[i][j][r] * sRow[row];
+                                u = bias ? __builtin_fmaf(t, swt, b) : t * swt;
+                                if (a.acc_out) a.acc_out[off] = acc[i][j][r];
+                            }
+                            asm volatile("" : "+v"(u));   // keep the fp32 rounding before the fp16 one
                             y[off] = (_Float16)u;
                         }
                     }
@@ -643,7 +737,7 @@ static hipError_t run_variant(const GemmArgs &a, hipStream_t s)
 
 struct Variant {
     const char *name;
-    int w_bits, BM, BN, BK;
+    int w_bits, BM, BN, BK;   // BK: K must be a multiple of this
     hipError_t (*run)(const GemmArgs &, hipStream_t);
 };
 
@@ -677,6 +771,7 @@ using D8_256x256_8w_e1 = TileD<4, 2, 2, 4, 2, 2, true, 1>;
 using D8_256x256_8w_e2 = TileD<4, 2, 2, 4, 2, 2, true, 2>;
 using D8_256x192_4w_e2 = TileD<4, 3, 2, 2, 2, 1, true, 2>;
 using D8_64x64_s4 = TileD<1, 1, 2, 2, 4, 4>;
+using D4_128x128_4w = TileD<2, 2, 2, 2, 2, 2, true, 0, true>;
 
 static const Variant VARIANTS[] = {
     {"w8 dma 128x128 s3 4w", 8, 128, 128, 128, run_dma<D8_128x128_s3>},
@@ -693,6 +788,7 @@ static const Variant VARIANTS[] = {
     {"w8 dma 256x256 s2 8w spread1", 8, 256, 256, 128, run_dma<D8_256x256_8w_e1>},
     {"w8 dma 256x256 s2 8w spread2", 8, 256, 256, 128, run_dma<D8_256x256_8w_e2>},
     {"w8 dma 256x192 s2 4w spread2", 8, 256, 192, 128, run_dma<D8_256x192_4w_e2>},
+    {"w4 dma 128x128 s2 4w", 4, 128, 128, 128, run_dma<D4_128x128_4w>},
     {"w8 128x128 bk64 4w occ2", 8, 128, 128, 64, run_variant<W8_128x128_k64>},
     {"w8 128x128 bk128 4w occ2", 8, 128, 128, 128, run_variant<W8_128x128_k128>},
     {"w8 256x128 bk64 4w occ2", 8, 256, 128, 64, run_variant<W8_256x128_k64>},
@@ -719,17 +815,19 @@ static int find_variant(const char *name)
     return 0;
 }
 
-// Tile choice by shape, from sweeps over the DiT-XL/2 layer shapes on MI355X.
+// Tile choice by shape, from sweeps over the DiT-XL/2 layer shapes on MI355X (256 CUs).
 static int choose_variant(const GemmArgs &a)
 {
-    static const int w8_small = find_variant("w8 dma 64x64 s4 4w"), w8_mid = find_variant("w8 dma 128x128 s2 4w"),
-                     w8_big = find_variant("w8 dma 256x192 s2 8w"), w8_k64 = find_variant("w8 128x128 bk64 4w occ3"),
-                     w4_any = find_variant("w4 128x64 bk128 4w occ3");
-    if (a.w_bits == 4) return w4_any;
+    static const int w8_small = find_variant("w8 dma 64x64 s4 4w"), w8_mid3 = find_variant("w8 dma 128x128 s3 4w"),
+                     w8_mid2 = find_variant("w8 dma 128x128 s2 4w"), w8_big = find_variant("w8 dma 256x192 s2 8w spread1"),
+                     w8_k64 = find_variant("w8 128x128 bk64 4w occ3"), w4_any = find_variant("w4 128x64 bk128 4w occ3");
+    if (a.w_bits == 4) return w4_any;   // the register-staged kernel at 3 wavefronts per SIMD hides the per-group VALU work best
     if (a.K % 128 != 0) return w8_k64;
     if (a.M <= 512) return w8_small;
-    if (a.M < 4096) return w8_mid;
-    return w8_big;
+    const long tiles_big = (long)((a.M + 255) / 256) * ((a.N + 191) / 192);
+    if (tiles_big >= 192) return w8_big;                      // at least 3/4 of the CUs get a 256x192 tile
+    const long tiles_mid = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
+    return tiles_mid >= 256 ? w8_mid2 : w8_mid3;              // two resident workgroups per CU only pay off when there are enough tiles
 }
 
 hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream)
@@ -743,6 +841,9 @@ hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream)
     }
     int v = variant;
     if (v < 0 || VARIANTS[v].w_bits != a.w_bits || a.K % VARIANTS[v].BK != 0) v = choose_variant(a);
+    // the pipelined 4-bit kernel keeps the group scales of a tile in LDS: at most 40 groups (K <= 5120)
+    if (a.w_bits == 4 && a.K > 128 * 40 && __builtin_strncmp(VARIANTS[v].name, "w4 dma", 6) == 0)
+        v = find_variant("w4 128x64 bk128 4w occ3");
     return VARIANTS[v].run(a, stream);
 }
 
