@@ -36,7 +36,15 @@ int check_shape(int64_t M, int64_t K, int64_t R, int64_t N)
 
 inline bool misaligned(const void *p, size_t a) { return p && ((uintptr_t)p % a) != 0; }
 
-// workspace layout of one layer: [codes M*K][scales M/R][block maxima M/R (R > 1)]
+// DAQ scratch for R > 1: [block maxima M/R][partial maxima (M/R) * parts]
+size_t daq_scratch_bytes(int64_t M, int64_t K, int64_t R)
+{
+    if (M < 1 || R <= 1 || M % R != 0) return 0;
+    const size_t nblk = (size_t)(M / R);
+    return align_up(nblk * 4, 256) + align_up(nblk * ql::daq_parts_per_block(K, R) * 4, 256);
+}
+
+// workspace layout of one layer: [codes M*K][scales M/R][DAQ scratch (R > 1)]
 struct LayerWs {
     size_t q_off, s_off, bm_off, total;
 };
@@ -47,7 +55,7 @@ LayerWs layer_ws(int64_t M, int64_t K, int64_t R)
     w.q_off = 0;
     w.s_off = align_up((size_t)(M * K), 256);
     w.bm_off = w.s_off + align_up((size_t)(M / R) * 4, 256);
-    w.total = w.bm_off + (R > 1 ? align_up((size_t)(M / R) * 4, 256) : 0);
+    w.total = w.bm_off + daq_scratch_bytes(M, K, R);
     return w;
 }
 
@@ -70,6 +78,7 @@ int run_layer(const void *x, int64_t M, int64_t K, int64_t R, int w_bits, const 
     d.q = (dbg && dbg->q) ? static_cast<int8_t *>(dbg->q) : reinterpret_cast<int8_t *>(base + lw.q_off);
     d.scales = (dbg && dbg->a_scales) ? static_cast<float *>(dbg->a_scales) : reinterpret_cast<float *>(base + lw.s_off);
     d.blockmax = R > 1 ? reinterpret_cast<unsigned *>(base + lw.bm_off) : nullptr;
+    d.partmax = R > 1 ? reinterpret_cast<unsigned *>(base + lw.bm_off + align_up((size_t)(M / R) * 4, 256)) : nullptr;
     d.M = (int)M;
     d.K = (int)K;
     d.R = (int)R;
@@ -173,9 +182,7 @@ int ql_version(void) { return 1000; }
 
 size_t daq_workspace_bytes(int64_t M, int64_t K, int64_t R)
 {
-    (void)K;
-    if (M < 1 || R <= 1 || M % R != 0) return 0;
-    return align_up((size_t)(M / R) * 4, 256);
+    return daq_scratch_bytes(M, K, R);
 }
 
 int daq_quantize(const void *x, int64_t M, int64_t K, int64_t R, void *q, void *scales, void *workspace,
@@ -192,6 +199,8 @@ int daq_quantize(const void *x, int64_t M, int64_t K, int64_t R, void *q, void *
     d.q = static_cast<int8_t *>(q);
     d.scales = static_cast<float *>(scales);
     d.blockmax = R > 1 ? static_cast<unsigned *>(workspace) : nullptr;
+    d.partmax = R > 1 ? reinterpret_cast<unsigned *>(static_cast<unsigned char *>(workspace) + align_up((size_t)(M / R) * 4, 256))
+                      : nullptr;
     d.M = (int)M;
     d.K = (int)K;
     d.R = (int)R;

@@ -4,7 +4,7 @@
 // block: alpha = amax / 127 (1 for an all-zero block),
 // code = clamp(round_half_even(x / alpha), -127, 127).
 //
-// One wavefront owns one row.  The row is read once with 16-byte loads and
+// One wavefront owns one or a few rows.  A row is read once with 16-byte loads and
 // kept in registers (2 bytes in, 1 byte out per element is all the HBM traffic
 // of the per-token mode).  The absolute maximum is taken on the fp16 bit
 // patterns: for non-negative binary16 numbers the integer order of the
@@ -28,14 +28,24 @@ __device__ __forceinline__ unsigned absmax_word(unsigned m, unsigned w)
     return __builtin_bit_cast(unsigned, __builtin_elementwise_max(a, b));
 }
 
+// maximum over the 64 lanes: rotations inside each row of 16 lanes (DPP, no LDS traffic), then the four row
+// results are combined in scalar registers; the result is wave-uniform
 __device__ __forceinline__ unsigned wave_max_u32(unsigned m)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        unsigned o = (unsigned)__shfl_xor((int)m, off, 64);
-        m = m > o ? m : o;
+#define QL_ROR_MAX(ctrl)                                                                       \
+    {                                                                                          \
+        const unsigned o = (unsigned)__builtin_amdgcn_update_dpp(0, (int)m, ctrl, 0xF, 0xF, false); \
+        m = m > o ? m : o;                                                                     \
     }
-    return m;
+    QL_ROR_MAX(0x128)  // row_ror:8
+    QL_ROR_MAX(0x124)  // row_ror:4
+    QL_ROR_MAX(0x122)  // row_ror:2
+    QL_ROR_MAX(0x121)  // row_ror:1
+#undef QL_ROR_MAX
+    const unsigned a = (unsigned)__builtin_amdgcn_readlane((int)m, 0), b = (unsigned)__builtin_amdgcn_readlane((int)m, 16);
+    const unsigned c = (unsigned)__builtin_amdgcn_readlane((int)m, 32), d = (unsigned)__builtin_amdgcn_readlane((int)m, 48);
+    const unsigned ab = a > b ? a : b, cd = c > d ? c : d;
+    return ab > cd ? ab : cd;
 }
 
 // eq. (4), last line without the multiplication back by alpha
@@ -57,6 +67,45 @@ __device__ __forceinline__ unsigned daq_pack4(unsigned w0, unsigned w1, float al
     return (unsigned)(c0 & 0xff) | ((unsigned)(c1 & 0xff) << 8) | ((unsigned)(c2 & 0xff) << 16) | ((unsigned)c3 << 24);
 }
 
+// Eight codes of one 16-byte piece without a division per element, bit-identical to daq_code().
+//
+// With rcp = fl(1/alpha) the exact product p = x*rcp differs from the correctly rounded quotient Q = fl(x/alpha) by at
+// most |x/alpha| * 2^-23 <= 1.52e-5 (|x/alpha| <= 127).  y = fma(x, rcp, 1.5*2^23) rounds p to the nearest integer r
+// (ties to even) and leaves r's two's-complement byte in the low mantissa bits.  d = fma(x, rcp, -r) is p - r; if
+// |d| < 0.5 - 2^-15 then p and Q lie in the same open interval (r - 0.5, r + 0.5), so rint(Q) = r.  Otherwise (6e-5 of
+// the elements, every exact tie of Q among them) the piece is redone with the division.  |r| <= 127 follows from
+// |x| <= amax, so the clamp of eq. (4) is the identity here.
+constexpr float DAQ_MAGIC = 12582912.0f;               // 1.5 * 2^23
+constexpr float DAQ_NEAR_TIE = 0.5f - 0.000030517578125f;  // 0.5 - 2^-15
+
+__device__ __forceinline__ unsigned daq_fast_code(unsigned hbits, float rcp, float &dmax)
+{
+    const float x = half_bits_to_float(hbits);
+    const float y = __builtin_fmaf(x, rcp, DAQ_MAGIC);
+    const float r = y - DAQ_MAGIC;
+    const float d = __builtin_fmaf(x, rcp, -r);
+    dmax = fmaxf(dmax, fabsf(d));
+    return __builtin_bit_cast(unsigned, y);
+}
+
+__device__ __forceinline__ unsigned daq_fast_pack4(unsigned w0, unsigned w1, float rcp, float &dmax)
+{
+    const unsigned y0 = daq_fast_code(w0 & 0xffffu, rcp, dmax), y1 = daq_fast_code(w0 >> 16, rcp, dmax);
+    const unsigned y2 = daq_fast_code(w1 & 0xffffu, rcp, dmax), y3 = daq_fast_code(w1 >> 16, rcp, dmax);
+    const unsigned p01 = __builtin_amdgcn_perm(y1, y0, 0x0c0c0400u);  // bytes: y0.0, y1.0, 0, 0
+    const unsigned p23 = __builtin_amdgcn_perm(y3, y2, 0x0c0c0400u);
+    return __builtin_amdgcn_perm(p23, p01, 0x05040100u);
+}
+
+__device__ __forceinline__ uint2 daq_piece(const uint4 &v, float alpha, float rcp)
+{
+    float dmax = 0.0f;
+    uint2 out = make_uint2(daq_fast_pack4(v.x, v.y, rcp, dmax), daq_fast_pack4(v.z, v.w, rcp, dmax));
+    if (__builtin_expect(!(dmax < DAQ_NEAR_TIE), 0))
+        out = make_uint2(daq_pack4(v.x, v.y, alpha), daq_pack4(v.z, v.w, alpha));
+    return out;
+}
+
 __device__ __forceinline__ float alpha_from_bits(unsigned amax_bits)
 {
     float amax = half_bits_to_float(amax_bits);
@@ -69,49 +118,63 @@ __device__ __forceinline__ void publish_block_max(unsigned *slot, unsigned bits)
     if (__hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < bits) atomicMax(slot, bits);
 }
 
-constexpr int ROWS_PER_BLOCK = 4;  // 4 wavefronts, one row each
+constexpr int ROWS_PER_BLOCK = 4;  // 4 wavefronts, one row each (loop kernels)
 
-// Row held in registers: CH 16-byte chunks per lane, K/8 <= 64*CH.
-template <int CH>
+// Rows held in registers: CH 16-byte chunks per lane and row (K/8 <= 64*CH), RW rows per wavefront.  All loads of
+// the RW rows are issued before the first reduction, so that enough bytes are in flight to cover the HBM latency.
+template <int CH, int RW>
 __global__ __launch_bounds__(256) void daq_rows_cached(DaqArgs a, int mode)
 {
     const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
-    if (row >= a.M) return;
+    // the second pass of the two-pass modes walks the rows backwards: the rows read last by the first pass are
+    // the ones most likely still in cache
+    const int wg = mode == DAQ_QUANT ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
+    const int row0 = (wg * 4 + (threadIdx.x >> 6)) * RW;
+    if (row0 >= a.M) return;
     const int nch = a.K >> 3;
-    const uint4 *xr = reinterpret_cast<const uint4 *>(static_cast<const unsigned short *>(a.x) + (size_t)row * a.K);
-    uint4 v[CH];
+    uint4 v[RW][CH];
 #pragma unroll
-    for (int i = 0; i < CH; ++i) {
-        int c = lane + 64 * i;
-        v[i] = c < nch ? xr[c] : make_uint4(0, 0, 0, 0);
-    }
-    unsigned bits;
-    if (mode != DAQ_QUANT) {
-        unsigned m = 0;
+    for (int r = 0; r < RW; ++r) {
+        const int row = min(row0 + r, a.M - 1);
+        const uint4 *xr = reinterpret_cast<const uint4 *>(static_cast<const unsigned short *>(a.x) + (size_t)row * a.K);
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            m = absmax_word(m, v[i].x);
-            m = absmax_word(m, v[i].y);
-            m = absmax_word(m, v[i].z);
-            m = absmax_word(m, v[i].w);
+            const int c = lane + 64 * i;
+            v[r][i] = c < nch ? xr[c] : make_uint4(0, 0, 0, 0);
         }
-        m = (m & 0xffffu) > (m >> 16) ? (m & 0xffffu) : (m >> 16);
-        bits = wave_max_u32(m);
-        if (mode == DAQ_ABSMAX) {
-            if (lane == 0) publish_block_max(a.blockmax + row / a.R, bits);
-            return;
-        }
-    } else {
-        bits = a.blockmax[row / a.R];
     }
-    const float alpha = alpha_from_bits(bits);
-    if (lane == 0 && (row % a.R) == 0) a.scales[row / a.R] = alpha;
-    uint2 *qr = reinterpret_cast<uint2 *>(a.q + (size_t)row * a.K);
 #pragma unroll
-    for (int i = 0; i < CH; ++i) {
-        int c = lane + 64 * i;
-        if (c < nch) qr[c] = make_uint2(daq_pack4(v[i].x, v[i].y, alpha), daq_pack4(v[i].z, v[i].w, alpha));
+    for (int r = 0; r < RW; ++r) {
+        const int row = row0 + r;
+        if (row >= a.M) break;
+        unsigned bits;
+        if (mode != DAQ_QUANT) {
+            unsigned m = 0;
+#pragma unroll
+            for (int i = 0; i < CH; ++i) {
+                m = absmax_word(m, v[r][i].x);
+                m = absmax_word(m, v[r][i].y);
+                m = absmax_word(m, v[r][i].z);
+                m = absmax_word(m, v[r][i].w);
+            }
+            m = (m & 0xffffu) > (m >> 16) ? (m & 0xffffu) : (m >> 16);
+            bits = wave_max_u32(m);
+            if (mode == DAQ_ABSMAX) {
+                if (lane == 0) publish_block_max(a.blockmax + row / a.R, bits);
+                continue;
+            }
+        } else {
+            bits = a.blockmax[row / a.R];
+        }
+        const float alpha = alpha_from_bits(bits);
+        const float rcp = 1.0f / alpha;
+        if (lane == 0 && (row % a.R) == 0) a.scales[row / a.R] = alpha;
+        uint2 *qr = reinterpret_cast<uint2 *>(a.q + (size_t)row * a.K);
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int c = lane + 64 * i;
+            if (c < nch) qr[c] = daq_piece(v[r][i], alpha, rcp);
+        }
     }
 }
 
@@ -149,15 +212,72 @@ __global__ __launch_bounds__(256) void daq_rows_loop(DaqArgs a, int mode)
         bits = a.blockmax[row / a.R];
     }
     const float alpha = alpha_from_bits(bits);
+    const float rcp = 1.0f / alpha;
     if (lane == 0 && (row % a.R) == 0) a.scales[row / a.R] = alpha;
     int8_t *qs = a.q + (size_t)row * a.K;
     for (int c = lane; c < nch; c += 64) {
         if (VEC == 8) {
             uint4 v = reinterpret_cast<const uint4 *>(xs)[c];
-            reinterpret_cast<uint2 *>(qs)[c] = make_uint2(daq_pack4(v.x, v.y, alpha), daq_pack4(v.z, v.w, alpha));
+            reinterpret_cast<uint2 *>(qs)[c] = daq_piece(v, alpha, rcp);
         } else {
             qs[c] = (int8_t)daq_code(half_bits_to_float(xs[c]), alpha);
         }
+    }
+}
+
+// First pass of the modes with several rows per scale: a scale block is one contiguous run of R*K values, cut into
+// parts of DAQ_PART_PIECES 16-byte pieces; one workgroup per part leaves the part's maximum in partmax (plain stores:
+// thousands of atomics on a few neighbouring words cost more than the whole pass).
+constexpr int ABSMAX_U = DAQ_PART_PIECES / 256;
+__global__ __launch_bounds__(256) void daq_part_absmax(const uint4 *x, unsigned pieces_per_block, unsigned parts_per_block,
+                                                       unsigned *partmax)
+{
+    __shared__ unsigned wave_max[4];
+    const unsigned b = blockIdx.x / parts_per_block, part = blockIdx.x - b * parts_per_block;
+    const uint4 *xb = x + (size_t)b * pieces_per_block;
+    const unsigned c0 = part * DAQ_PART_PIECES + threadIdx.x;
+    uint4 v[ABSMAX_U];
+#pragma unroll
+    for (int i = 0; i < ABSMAX_U; ++i) {
+        const unsigned c = c0 + 256 * i;
+        v[i] = c < pieces_per_block ? xb[c] : make_uint4(0, 0, 0, 0);
+    }
+    unsigned m = 0;
+#pragma unroll
+    for (int i = 0; i < ABSMAX_U; ++i) {
+        m = absmax_word(m, v[i].x);
+        m = absmax_word(m, v[i].y);
+        m = absmax_word(m, v[i].z);
+        m = absmax_word(m, v[i].w);
+    }
+    m = (m & 0xffffu) > (m >> 16) ? (m & 0xffffu) : (m >> 16);
+    m = wave_max_u32(m);
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned m01 = wave_max[0] > wave_max[1] ? wave_max[0] : wave_max[1];
+        const unsigned m23 = wave_max[2] > wave_max[3] ? wave_max[2] : wave_max[3];
+        partmax[blockIdx.x] = m01 > m23 ? m01 : m23;
+    }
+}
+
+// one workgroup per scale block: maximum of its partial maxima
+__global__ __launch_bounds__(256) void daq_reduce_parts(const unsigned *partmax, unsigned parts_per_block, unsigned *blockmax)
+{
+    __shared__ unsigned wave_max[4];
+    const unsigned *pm = partmax + (size_t)blockIdx.x * parts_per_block;
+    unsigned m = 0;
+    for (unsigned i = threadIdx.x; i < parts_per_block; i += 256) {
+        const unsigned o = pm[i];
+        m = m > o ? m : o;
+    }
+    m = wave_max_u32(m);
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned m01 = wave_max[0] > wave_max[1] ? wave_max[0] : wave_max[1];
+        const unsigned m23 = wave_max[2] > wave_max[3] ? wave_max[2] : wave_max[3];
+        blockmax[blockIdx.x] = m01 > m23 ? m01 : m23;
     }
 }
 
@@ -167,10 +287,11 @@ __global__ void fill_u32(unsigned *p, int n, unsigned v)
     if (i < n) p[i] = v;
 }
 
-template <int CH>
-static void run_cached(const DaqArgs &a, int mode, dim3 grid, hipStream_t s)
+template <int CH, int RW>
+static void run_cached(const DaqArgs &a, int mode, hipStream_t s)
 {
-    hipLaunchKernelGGL(daq_rows_cached<CH>, grid, dim3(256), 0, s, a, mode);
+    dim3 grid((a.M + 4 * RW - 1) / (4 * RW));
+    hipLaunchKernelGGL((daq_rows_cached<CH, RW>), grid, dim3(256), 0, s, a, mode);
 }
 
 static void run_rows(const DaqArgs &a, int mode, hipStream_t s)
@@ -182,14 +303,15 @@ static void run_rows(const DaqArgs &a, int mode, hipStream_t s)
         return;
     }
     const int per_lane = (a.K / 8 + 63) / 64;
-    if (per_lane <= 1) run_cached<1>(a, mode, grid, s);
-    else if (per_lane <= 2) run_cached<2>(a, mode, grid, s);
-    else if (per_lane <= 3) run_cached<3>(a, mode, grid, s);
-    else if (per_lane <= 4) run_cached<4>(a, mode, grid, s);
-    else if (per_lane <= 6) run_cached<6>(a, mode, grid, s);
-    else if (per_lane <= 9) run_cached<9>(a, mode, grid, s);
-    else if (per_lane <= 12) run_cached<12>(a, mode, grid, s);
-    else if (per_lane <= 16) run_cached<16>(a, mode, grid, s);
+    const bool many = a.M >= 8192;   // enough rows to give every wavefront several
+    if (per_lane <= 1) many ? run_cached<1, 4>(a, mode, s) : run_cached<1, 1>(a, mode, s);
+    else if (per_lane <= 2) many ? run_cached<2, 4>(a, mode, s) : run_cached<2, 1>(a, mode, s);
+    else if (per_lane <= 3) many ? run_cached<3, 4>(a, mode, s) : run_cached<3, 1>(a, mode, s);
+    else if (per_lane <= 4) many ? run_cached<4, 2>(a, mode, s) : run_cached<4, 1>(a, mode, s);
+    else if (per_lane <= 6) many ? run_cached<6, 2>(a, mode, s) : run_cached<6, 1>(a, mode, s);
+    else if (per_lane <= 9) many ? run_cached<9, 2>(a, mode, s) : run_cached<9, 1>(a, mode, s);
+    else if (per_lane <= 12) run_cached<12, 1>(a, mode, s);
+    else if (per_lane <= 16) run_cached<16, 1>(a, mode, s);
     else hipLaunchKernelGGL(daq_rows_loop<8>, grid, dim3(256), 0, s, a, mode);
 }
 
@@ -199,8 +321,15 @@ hipError_t launch_daq(const DaqArgs &a, hipStream_t stream)
         run_rows(a, DAQ_FUSED, stream);
     } else {
         const int nblk = a.M / a.R;
-        hipLaunchKernelGGL(fill_u32, dim3((nblk + 255) / 256), dim3(256), 0, stream, a.blockmax, nblk, 0u);
-        run_rows(a, DAQ_ABSMAX, stream);
+        const size_t parts = daq_parts_per_block(a.K, a.R);
+        if (parts > 0 && (uintptr_t)a.x % 16 == 0 && parts * nblk < (1ull << 31)) {
+            hipLaunchKernelGGL(daq_part_absmax, dim3((unsigned)(parts * nblk)), dim3(256), 0, stream,
+                               static_cast<const uint4 *>(a.x), (unsigned)((size_t)a.R * a.K / 8), (unsigned)parts, a.partmax);
+            hipLaunchKernelGGL(daq_reduce_parts, dim3(nblk), dim3(256), 0, stream, a.partmax, (unsigned)parts, a.blockmax);
+        } else {
+            hipLaunchKernelGGL(fill_u32, dim3((nblk + 255) / 256), dim3(256), 0, stream, a.blockmax, nblk, 0u);
+            run_rows(a, DAQ_ABSMAX, stream);
+        }
         run_rows(a, DAQ_QUANT, stream);
     }
     return hipGetLastError();

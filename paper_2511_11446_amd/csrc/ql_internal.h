@@ -10,7 +10,7 @@ namespace ql {
 // mode of the row kernels
 enum DaqMode : int {
     DAQ_FUSED = 0,   // per-token: absmax, scale, codes in one pass over a row held in registers
-    DAQ_ABSMAX = 1,  // R > 1, phase 1: row absmax -> atomic max into blockmax[row / R]
+    DAQ_ABSMAX = 1,  // R > 1, phase 1 (fallback): row absmax -> atomic max into blockmax[row / R]
     DAQ_QUANT = 2    // R > 1, phase 2: codes from blockmax[row / R]
 };
 
@@ -19,8 +19,20 @@ struct DaqArgs {
     int8_t *q;           // [M,K]
     float *scales;       // [M/R]
     unsigned *blockmax;  // [M/R] fp16 bit patterns of block maxima (workspace), R > 1 only
+    unsigned *partmax;   // [M/R][daq_parts_per_block] partial maxima (workspace), R > 1 only
     int M, K, R;
 };
+
+// R > 1: the first pass cuts every scale block (R*K contiguous values) into this many parts and leaves one partial
+// maximum per part; 0 when the shape takes the row kernels instead (no partials needed).
+constexpr int DAQ_PART_PIECES = 2048;  // 16-byte pieces per part: 256 threads x 8 loads
+inline size_t daq_parts_per_block(int64_t K, int64_t R)
+{
+    if (R <= 1 || K % 8 != 0) return 0;
+    const size_t pieces = (size_t)R * (size_t)K / 8;
+    if (pieces < (size_t)DAQ_PART_PIECES || pieces >= (1ull << 31)) return 0;
+    return (pieces + DAQ_PART_PIECES - 1) / DAQ_PART_PIECES;
+}
 
 hipError_t launch_daq(const DaqArgs &a, hipStream_t stream);
 
