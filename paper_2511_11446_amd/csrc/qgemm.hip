@@ -368,6 +368,22 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     const int nk = K / 128;   // K steps; for 4-bit weights also the number of weight groups
     QL_PHASE(0)
 
+    // Everything the epilogue needs from global memory is requested now, ahead of the first DMA (the oldest loads
+    // return first, so the vmcnt bookkeeping of the ring is unaffected): the activation scale of one tile row per
+    // thread, and the weight scale and bias of this lane's columns.
+    static_assert(BM <= NT, "one row scale per thread");
+    const float sa_pre = tid < BM ? a.s_a[min(m0 + tid, M - 1) / a.R] : 0.0f;
+    float swt[TN], bj[TN];
+    {
+        const unsigned short *bias_h = static_cast<const unsigned short *>(a.bias);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = min(n0 + wn * TN * 32 + j * 32 + (lane & 31), N - 1);
+            swt[j] = W4 ? 1.0f : static_cast<const float *>(a.s_w)[n];
+            bj[j] = bias_h ? half_to_float_dev(bias_h[n]) : 0.0f;
+        }
+    }
+
     // 4-bit weights: the fp16 group scales of this tile's columns, [BN][nk], copied once (the first barrier of the
     // pipeline below orders the copy before their first use at the end of K step 0)
     unsigned short *sScale = reinterpret_cast<unsigned short *>(smem + T::RING_BYTES);
@@ -586,20 +602,13 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     __syncthreads();
 
     float *sRow = reinterpret_cast<float *>(smem);
-    for (int t = tid; t < BM; t += NT) sRow[t] = a.s_a[min(m0 + t, M - 1) / a.R];
+    if (tid < BM) sRow[tid] = sa_pre;
     __syncthreads();
     QL_PHASE(3)
     _Float16 *y = static_cast<_Float16 *>(a.y);
     const unsigned short *bias = static_cast<const unsigned short *>(a.bias);
     const bool full = (m0 + BM <= M) && (n0 + BN <= N);
     if (full && (N % 8) == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0 && (W4 || !a.acc_out)) {
-        float swt[TN], bj[TN];
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int n = n0 + wn * TN * 32 + j * 32 + frag_row;
-            swt[j] = W4 ? 1.0f : static_cast<const float *>(a.s_w)[n];
-            bj[j] = bias ? half_to_float_dev(bias[n]) : 0.0f;
-        }
         unsigned char *strip = smem + T::STRIP_OFF + wave * T::STRIP_BYTES;
         const float *sr = sRow + wm * TM * 32 + 4 * frag_half;
         if (W4 && bias)
@@ -625,8 +634,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
             for (int j = 0; j < TN; ++j) {
                 const int n = n0 + wn * TN * 32 + j * 32 + frag_row;
                 const bool n_ok = !EDGE || n < N;
-                const float swt = (!W4 && n_ok) ? static_cast<const float *>(a.s_w)[n] : 1.0f;
-                const float b = (bias && n_ok) ? half_to_float_dev(bias[n]) : 0.0f;
+                const float b = bj[j];
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -641,7 +649,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
                                 u = bias ? __builtin_fmaf(f, sRow[row], b) : f * sRow[row];
                             } else {
                                 const float t = (float)acc[i][j][r] * sRow[row];
-                                u = bias ? __builtin_fmaf(t, swt, b) : t * swt;
+                                u = bias ? __builtin_fmaf(t, swt[j], b) : t * swt[j];
                                 if (a.acc_out) a.acc_out[off] = acc[i][j][r];
                             }
                             asm volatile("" : "+v"(u));   // keep the fp32 rounding before the fp16 one
