@@ -26,6 +26,10 @@ INT8_PEAK_TOPS = 5033.0   # MI355X dense INT8 matrix peak (256 CUs x 2.4 GHz x 8
 HBM_PEAK_GBS = 8000.0
 DEFAULT_WORKLOAD = "c2_block_w8a8_m2048"
 POOL = 4                  # distinct activation sets rotated over the steps (different drift sigma each)
+# HBM bytes per GEMM launch (reads + writes, mean over the layers of a step) from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs of `bench.py --traffic-probe`, each scaled by what the same counter reads for a device-to-device copy
+# of known size in the same run (summaries under profiles/).  Keyed by (workload, forced variant); absent = not measured.
+TRAFFIC_BYTES_PER_LAUNCH = {}
 
 
 def build_layers(ql, torch, wl_name):
@@ -115,6 +119,8 @@ def main():
     ap.add_argument("--variant", type=int, default=-1, help="force a GEMM tile variant (sweeps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for rocprofv3 --pmc runs: a few steps of the workload plus a device copy of known size, no timing")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (every GPU box here has one); --gpus %d is not supported. "
@@ -151,6 +157,20 @@ def main():
     sptr = ctypes.c_void_p(stream.cuda_stream)
     ops_per_step = sum(2.0 * M * l["N"] * l["K"] for l in layers)
 
+    if args.traffic_probe:
+        # counters are read per dispatch: 3 steps of the workload, then 3 copies of 256 MiB (read 256 MiB, write 256 MiB)
+        for i in range(3):
+            plan.run_ptrs(xs_pool[i % len(pool)], ys, M, R, ws, sptr)
+        torch.cuda.synchronize()
+        src = torch.ones(128 * 1024 * 1024, dtype=torch.float16, device="cuda")
+        dst = torch.empty_like(src)
+        for i in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_probe": args.workload, "copy_bytes_read": src.numel() * 2,
+                          "copy_bytes_written": src.numel() * 2, "steps": 3}))
+        return
+
     for i in range(warmup):
         plan.run_ptrs(xs_pool[i % len(pool)], ys, M, R, ws, sptr)
     torch.cuda.synchronize()
@@ -166,11 +186,29 @@ def main():
     ms_per_step = ms / steps
     tops = ops_per_step / (ms_per_step * 1e-3) / 1e12
 
-    # ---- per-kernel breakdown: the same layers, DAQ and GEMM launched separately with events around each
+    # ---- per-kernel breakdown: for every distinct layer, `reps` launches of the DAQ kernel and `reps` launches of the
+    # GEMM kernel, each batch captured into a HIP graph (back-to-back on the stream, no host time between them) and
+    # timed with events around the replay on that same stream
     roofline = None
     breakdown = {}
+    mfma_ceiling = None
     if not args.no_breakdown:
-        reps = max(3, min(steps, 20))
+        reps = 20 if not big else 10
+
+        def timed_graph(fn):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for _ in range(reps):
+                    fn()
+            g.replay()
+            torch.cuda.synchronize()
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a0.record(stream)
+            g.replay()
+            a1.record(stream)
+            torch.cuda.synchronize()
+            return a0.elapsed_time(a1) * 1e-3 / reps
+
         uniq = {}
         for l in layers:
             uniq.setdefault((l["name"], l["bits"]), l)
@@ -183,22 +221,17 @@ def main():
             q = torch.empty((M, l["K"]), dtype=torch.int8, device="cuda")
             sa = torch.empty((M // R,), dtype=torch.float32, device="cuda")
             dws = ql.workspace(ql.daq_workspace_bytes(M, l["K"], R))
-            y = y_by_type[l["name"]]
+            y = torch.empty((M, l["N"]), dtype=torch.float16, device="cuda")
             gfn = ql.qgemm_w8a8 if l["bits"] == 8 else ql.qgemm_w4a8
-            evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(reps)]
-            for _ in range(2):
-                ql.daq_quantize(x, R, q, sa, dws)
-                gfn(q, sa, R, l["w"], l["w_scale"], l["bias"], y=y)
+            # eager once (also the comparison for the graph replays below)
+            ql.daq_quantize(x, R, q, sa, dws)
+            gfn(q, sa, R, l["w"], l["w_scale"], l["bias"], y=y)
             torch.cuda.synchronize()
-            for r in range(reps):
-                evs[r][0].record(stream)
-                ql.daq_quantize(x, R, q, sa, dws)
-                evs[r][1].record(stream)
-                gfn(q, sa, R, l["w"], l["w_scale"], l["bias"], y=y)
-                evs[r][2].record(stream)
-            torch.cuda.synchronize()
-            td = float(np.mean([evs[r][0].elapsed_time(evs[r][1]) for r in range(reps)])) * 1e-3
-            tg = float(np.mean([evs[r][1].elapsed_time(evs[r][2]) for r in range(reps)])) * 1e-3
+            q_ref, y_ref = q.clone(), y.clone()
+            td = timed_graph(lambda: ql.daq_quantize(x, R, q, sa, dws))
+            tg = timed_graph(lambda: gfn(q, sa, R, l["w"], l["w_scale"], l["bias"], y=y))
+            if not (torch.equal(q, q_ref) and torch.equal(y, y_ref)):
+                raise RuntimeError("graph replay of %s/w%d differs from the eager launch" % key)
             ops = 2.0 * M * l["N"] * l["K"]
             dbytes = 3.0 * M * l["K"] + 4.0 * (M // R)
             breakdown["%s/w%d" % key] = {"daq_us": td * 1e6, "gemm_us": tg * 1e6, "gemm_tops": ops / tg / 1e12,
@@ -209,20 +242,37 @@ def main():
             daq_time += td * counts[key]
             daq_bytes += dbytes * counts[key]
             daq_n += counts[key]
+            del q, sa, y, q_ref, y_ref
+        # the matrix cores' own ceiling on this machine: a register-resident MFMA loop, 2 workgroups per CU
+        sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        for _ in range(2):
+            pops = ql.probe_mfma_int8(4096, 2 * cus, sink)
+        torch.cuda.synchronize()
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a0.record(stream)
+        for _ in range(5):
+            ql.probe_mfma_int8(4096, 2 * cus, sink)
+        a1.record(stream)
+        torch.cuda.synchronize()
+        mfma_ceiling = 5 * pops / (a0.elapsed_time(a1) * 1e-3) / 1e12
+        traffic = TRAFFIC_BYTES_PER_LAUNCH.get((args.workload, args.variant))
         if gemm_time >= daq_time:
             ach = gemm_ops / gemm_time / 1e12
-            roofline = {"bound": "mfma", "kernel": "qgemm_mfma (INT8 GEMM + dequantization), all layers of a step",
+            roofline = {"bound": "mfma", "kernel": "qgemm_dma / qgemm_mfma (INT8 GEMM + dequantization), all layers of a step",
                         "achieved": ach, "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": ach / INT8_PEAK_TOPS,
                         "avg_launch_us": gemm_time / gemm_n * 1e6, "ops_per_launch": gemm_ops / gemm_n,
-                        "traffic": None}
+                        "traffic": traffic}
         else:
             ach = daq_bytes / daq_time / 1e9
-            roofline = {"bound": "hbm", "kernel": "daq_rows (DAQ pass), all layers of a step", "achieved": ach,
+            roofline = {"bound": "hbm", "kernel": "daq_rows_cached (DAQ pass), all layers of a step", "achieved": ach,
                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                         "avg_launch_us": daq_time / daq_n * 1e6, "bytes_per_launch": daq_bytes / daq_n,
                         "traffic": None}
         roofline["daq_hbm_gbs"] = daq_bytes / daq_time / 1e9
         roofline["gemm_only_tops"] = gemm_ops / gemm_time / 1e12
+        roofline["measured_mfma_only_tops"] = mfma_ceiling
+        roofline["frac_of_measured_mfma"] = gemm_ops / gemm_time / 1e12 / mfma_ceiling
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -233,6 +283,7 @@ def main():
         "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "pct_int8_mfma_peak": 100.0 * tops / INT8_PEAK_TOPS,
+        "pct_measured_mfma_only": (100.0 * tops / mfma_ceiling) if mfma_ceiling else None,
         "config": {"workload": args.workload, "M": M, "rows_per_scale": R, "layers": L,
                    "w4_layers": sum(l["bits"] == 4 for l in layers), "activation_sets_rotated": len(pool),
                    "sigmas": sigmas, "gemm_variant": args.variant},

@@ -183,13 +183,26 @@ int qlinear_plan_run(const ql_plan *plan, const void *const *x_in, void *const *
 
 /* ------------------------------------------------------------------------
  * Tuning hooks (benchmark sweeps).  ql_set_gemm_variant(v) forces GEMM tile
- * variant v for later calls from this process (-1 = choose by shape);
- * ql_num_gemm_variants() gives the valid range; ql_gemm_variant_name(v) a
- * short description.  Results do not depend on the variant.
+ * variant v for later calls from this process (-1 = choose by shape;
+ * v == ql_num_gemm_variants() = the generic one-thread-per-element kernel);
+ * ql_num_gemm_variants() gives the number of tiled variants;
+ * ql_gemm_variant_name(v) a short description.  A forced variant that cannot
+ * take a shape (K not a multiple of its K step, misaligned operands) falls
+ * back to the generic kernel.  Results do not depend on the variant.
  * ---------------------------------------------------------------------- */
 int ql_set_gemm_variant(int variant);
 int ql_num_gemm_variants(void);
 const char *ql_gemm_variant_name(int variant);
+
+/* ------------------------------------------------------------------------
+ * Measurement aid (Section 6 reports time; this build reports the GEMM rate
+ * against the matrix cores' measured ceiling as well as the datasheet peak).
+ * Enqueues on `stream` a kernel of `blocks` workgroups x 4 wavefronts, each
+ * wavefront issuing 4*iters 32x32x32 INT8 MFMAs on registers only:
+ * 2*32*32*32 * 4*iters * 4*blocks operations in all.  sink: device int
+ * (4 bytes, never written in practice).  1 <= iters, 1 <= blocks <= 65535.
+ * ---------------------------------------------------------------------- */
+int ql_probe_mfma_int8(int iters, int blocks, void *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -21,7 +21,7 @@ EXPORTS = ("ql_status_string", "ql_last_device_error", "ql_version", "daq_worksp
            "qlinear_workspace_bytes", "qlinear_w8a8", "qlinear_w4a8", "qgemm_w8a8", "qgemm_w4a8",
            "ql_pack_w4_host", "ql_plan_create", "ql_plan_destroy", "ql_plan_num_layers",
            "ql_plan_workspace_bytes", "qlinear_plan_run", "ql_set_gemm_variant", "ql_num_gemm_variants",
-           "ql_gemm_variant_name")
+           "ql_gemm_variant_name", "ql_probe_mfma_int8")
 
 
 class QlError(RuntimeError):
@@ -64,6 +64,8 @@ def lib():
     L.ql_status_string.argtypes = [_int]
     L.ql_gemm_variant_name.restype = ctypes.c_char_p
     L.ql_gemm_variant_name.argtypes = [_int]
+    L.ql_probe_mfma_int8.restype = _int
+    L.ql_probe_mfma_int8.argtypes = [_int, _int, _vp, _vp]
     L.daq_workspace_bytes.restype = _sz
     L.daq_workspace_bytes.argtypes = [_i64, _i64, _i64]
     L.qlinear_workspace_bytes.restype = _sz
@@ -273,3 +275,9 @@ def set_gemm_variant(v):
 def gemm_variants():
     L = lib()
     return [L.ql_gemm_variant_name(i).decode() for i in range(L.ql_num_gemm_variants())]
+
+
+def probe_mfma_int8(iters, blocks, sink, stream=None):
+    """Enqueue the register-resident MFMA loop; returns the number of int8 operations it performs."""
+    _check(lib().ql_probe_mfma_int8(iters, blocks, _ptr(sink), _stream(stream)), "ql_probe_mfma_int8")
+    return 2.0 * 32 * 32 * 32 * 4 * iters * 4 * blocks

@@ -323,4 +323,12 @@ int ql_num_gemm_variants(void) { return ql::num_gemm_variants(); }
 
 const char *ql_gemm_variant_name(int variant) { return ql::gemm_variant_name(variant); }
 
+int ql_probe_mfma_int8(int iters, int blocks, void *sink, void *stream)
+{
+    if (!sink) return QL_ERR_NULL;
+    if (iters < 1 || blocks < 1 || blocks > 65535) return QL_ERR_SHAPE;
+    if (misaligned(sink, 4)) return QL_ERR_ALIGN;
+    return device_status(ql::launch_mfma_probe(iters, blocks, static_cast<int *>(sink), static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"

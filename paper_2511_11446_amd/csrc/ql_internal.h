@@ -54,4 +54,7 @@ const char *gemm_variant_name(int v);
 // variant < 0: choose by shape
 hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream);
 
+// measurement aid: blocks x 4 wavefronts, each issuing 4 * iters MFMAs (32x32x32 int8) on registers only
+hipError_t launch_mfma_probe(int iters, int blocks, int *sink, hipStream_t stream);
+
 }  // namespace ql
