@@ -318,26 +318,35 @@ __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane
 // the next quarter, the hand-over barrier and the next DMA issue all sit behind an MFMA that is
 // already executing.
 // ---------------------------------------------------------------------------------------------
-template <int TM_, int TN_, int WGM_, int WGN_, int S_, int WPS_, bool STG_ = true, int EV_ = 0, bool W4_ = false>
+template <int TM_, int TN_, int WGM_, int WGN_, int S_, int WPS_, bool STG_ = true, int EV_ = 0, bool W4_ = false, int SB_ = S_>
 struct TileD {
-    static constexpr int TM = TM_, TN = TN_, WGM = WGM_, WGN = WGN_, S = S_, WPS = WPS_;
+    static constexpr int TM = TM_, TN = TN_, WGM = WGM_, WGN = WGN_, WPS = WPS_;
+    // ring depth of the activation tile and of the weight tile (K steps resident or in flight); they may differ by one
+    static constexpr int SA = S_, SB = SB_;
     static constexpr bool W4 = W4_;
     static constexpr int NW = WGM * WGN, NT = NW * 64;
     static constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32, BK = 128;
-    // 1024-byte DMA groups per K step: A rows first (8 rows x 128 B), then W rows (8 x 128 B, or 16 x 64 B packed 4-bit)
-    static constexpr int A_GROUPS = BM / 8, B_GROUPS = W4 ? BN / 16 : BN / 8, GROUPS = A_GROUPS + B_GROUPS;
-    static constexpr int LPT = (GROUPS + NW - 1) / NW;     // DMA instructions per wavefront per K step ...
-    static constexpr int REM = GROUPS % NW;                // ... except that wavefronts >= REM issue one less when REM != 0
-    static constexpr int STAGE_BYTES = GROUPS * 1024;
+    // 1024-byte DMA groups per K step: A rows (8 rows x 128 B) and W rows (8 x 128 B, or 16 x 64 B packed 4-bit)
+    static constexpr int A_GROUPS = BM / 8, B_GROUPS = W4 ? BN / 16 : BN / 8;
+    static constexpr int NA = A_GROUPS / NW, NB = B_GROUPS / NW;   // DMA instructions per wavefront per K step
+    static constexpr int A_BYTES = A_GROUPS * 1024, B_BYTES = B_GROUPS * 1024;
+    static constexpr int B_RING = SA * A_BYTES;           // the weight ring follows the activation ring
     static constexpr bool STAGED_STORE = STG_;
     static constexpr int DMA_EVERY = EV_;                 // one DMA instruction behind every EV_-th MFMA; 0: all at the hand-over
     static constexpr int STRIP_OFF = (BM * 4 + 255) / 256 * 256;   // epilogue: row scales first, then one strip per wavefront
     static constexpr int STRIP_BYTES = 32 * (TN * 64 + 16);
-    static constexpr int RING_BYTES = S * STAGE_BYTES > STRIP_OFF + NW * STRIP_BYTES ? S * STAGE_BYTES : STRIP_OFF + NW * STRIP_BYTES;
+    static constexpr int RINGS = SA * A_BYTES + SB * B_BYTES;
+    static constexpr int RING_BYTES = RINGS > STRIP_OFF + NW * STRIP_BYTES ? RINGS : STRIP_OFF + NW * STRIP_BYTES;
     static constexpr int MAX_GROUPS_K = 40;               // 4-bit: group scales of the tile's columns live in LDS (K <= 5120)
     static constexpr int SCALE_BYTES = W4 ? BN * MAX_GROUPS_K * 2 : 0;
     static constexpr int LDS_BYTES = RING_BYTES + SCALE_BYTES;
-    static_assert(S >= 2 && (S - 1) * LPT <= 63, "vmcnt is a 6-bit counter");
+    static constexpr int SMAX = SA > SB ? SA : SB;
+    // loads that may still be in flight when K step 0 is first read, and at the hand-over from step kt to kt+1
+    static constexpr int WAIT_START = (SA - 1) * NA + (SB - 1) * NB;
+    static constexpr int WAIT_HAND = SA > SB ? NA + (SB - 2) * (NA + NB) : SA < SB ? NB + (SA - 2) * (NA + NB) : (SA - 2) * (NA + NB);
+    static_assert(A_GROUPS % NW == 0 && B_GROUPS % NW == 0, "every wavefront issues the same number of DMA instructions");
+    static_assert(SA >= 2 && SB >= 2 && (SA - SB) * (SA - SB) <= 1, "ring depths differ by at most one");
+    static_assert(WAIT_START <= 63, "vmcnt is a 6-bit counter");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS of one CU");
 };
 
@@ -347,7 +356,7 @@ typedef const __attribute__((address_space(1))) void global_void;
 template <class T>
 __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles_m, int tiles_n, int nblk_padded)
 {
-    constexpr int TM = T::TM, TN = T::TN, BM = T::BM, BN = T::BN, NT = T::NT, S = T::S, NW = T::NW;
+    constexpr int TM = T::TM, TN = T::TN, BM = T::BM, BN = T::BN, NT = T::NT, NW = T::NW;
     constexpr bool W4 = T::W4;
     extern __shared__ __align__(1024) unsigned char smem[];
 
@@ -394,46 +403,51 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     }
 
     // DMA addressing: lane l of a wavefront fills bytes [16 l, 16 l + 16) of a 1024-byte group = row l/8, slot l%8.
-    // Group g covers stage rows [8 g, 8 g + 8): A rows for g < BM/8, W rows after.  Wavefront w takes g = w, w+NW, ...
-    const int my_loads = (T::REM == 0 || wave < T::REM) ? T::LPT : T::LPT - 1;
-    unsigned goff[T::LPT];
+    // Group g covers tile rows [8 g, 8 g + 8) of its operand.  Wavefront w takes groups w, w+NW, ... of both operands.
+    constexpr int SA = T::SA, SB = T::SB, NA = T::NA, NB = T::NB;
+    unsigned goffA[NA], goffB[NB];
 #pragma unroll
-    for (int i = 0; i < T::LPT; ++i) {
-        const int g = min(wave + i * NW, T::GROUPS - 1);
-        const bool is_a = g < T::A_GROUPS;
-        if (is_a || !W4) {
-            const int row = 8 * g + (lane >> 3);            // stage row: A rows, then W rows
+    for (int i = 0; i < NA; ++i) {
+        const int row = 8 * (wave + i * NW) + (lane >> 3);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
+        goffA[i] = (unsigned)(min(m0 + row, M - 1) * K + 16 * c);
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        if (!W4) {
+            const int row = 8 * (wave + i * NW) + (lane >> 3);
             const int c = (lane & 7) ^ ((row >> 1) & 7);
-            goff[i] = (unsigned)((is_a ? min(m0 + row, M - 1) : min(n0 + row - BM, N - 1)) * K + 16 * c);
+            goffB[i] = (unsigned)(min(n0 + row, N - 1) * K + 16 * c);
         } else {
             // packed 4-bit rows are 64 bytes per K step: 16 rows per group, chunk c of row r at slot c ^ ((r >> 2) & 3)
-            const int row = 16 * (g - T::A_GROUPS) + (lane >> 2);
+            const int row = 16 * (wave + i * NW) + (lane >> 2);
             const int c = (lane & 3) ^ ((row >> 2) & 3);
-            goff[i] = (unsigned)(min(n0 + row, N - 1) * (K / 2) + 16 * c);
+            goffB[i] = (unsigned)(min(n0 + row, N - 1) * (K / 2) + 16 * c);
         }
     }
-    auto issue = [&](int kt, int slot) {
-        unsigned char *st = smem + slot * T::STAGE_BYTES;
-        const int8_t *qa = a.q + (size_t)kt * 128;
-        const int8_t *wb = static_cast<const int8_t *>(a.w) + (size_t)kt * (W4 ? 64 : 128);
-#pragma unroll
-        for (int i = 0; i < T::LPT; ++i)
-            if (i < my_loads) {
-                const int8_t *base = (wave + i * NW) < T::A_GROUPS ? qa : wb;  // wave-uniform choice
-                __builtin_amdgcn_global_load_lds((global_void *)(base + goff[i]), (lds_void *)(st + (wave + i * NW) * 1024), 16, 0, 0);
-            }
+    auto issue_a = [&](int kt, int slot, int i) {
+        __builtin_amdgcn_global_load_lds((global_void *)(a.q + (size_t)kt * 128 + goffA[i]),
+                                         (lds_void *)(smem + slot * T::A_BYTES + (wave + i * NW) * 1024), 16, 0, 0);
     };
-    auto issue_one = [&](int kt, int slot, int i) {
-        const int8_t *base = (wave + i * NW) < T::A_GROUPS ? a.q + (size_t)kt * 128
-                                                            : static_cast<const int8_t *>(a.w) + (size_t)kt * (W4 ? 64 : 128);
-        __builtin_amdgcn_global_load_lds((global_void *)(base + goff[i]),
-                                         (lds_void *)(smem + slot * T::STAGE_BYTES + (wave + i * NW) * 1024), 16, 0, 0);
+    auto issue_b = [&](int kt, int slot, int i) {
+        __builtin_amdgcn_global_load_lds((global_void *)(static_cast<const int8_t *>(a.w) + (size_t)kt * (W4 ? 64 : 128) + goffB[i]),
+                                         (lds_void *)(smem + T::B_RING + slot * T::B_BYTES + (wave + i * NW) * 1024), 16, 0, 0);
     };
-    // wait until at most n K steps of this wavefront's loads are still in flight (n is a compile-time constant)
-    auto wait_steps = [&](auto n_tag) {
+    // Refill window j = the loads issued after the hand-over barrier of K step j, into the slots that step used:
+    // weight tile of step j+SB and activation tile of step j+SA.  The operand with the shallower ring is needed sooner
+    // and goes first.  li numbers the NA+NB instructions of the window.
+    constexpr bool B_FIRST = SB <= SA;
+    auto issue_win = [&](int j, int slot_a, int slot_b, int li) {
+        const bool is_b = B_FIRST ? li < NB : li >= NA;
+        if (is_b) {
+            if (j + SB < nk) issue_b(j + SB, slot_b, B_FIRST ? li : li - NA);
+        } else {
+            if (j + SA < nk) issue_a(j + SA, slot_a, B_FIRST ? li - NB : li);
+        }
+    };
+    auto wait_vm = [&](auto n_tag) {
         constexpr int n = decltype(n_tag)::value;
-        if (T::REM == 0 || wave < T::REM) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n * T::LPT) : "memory");
-        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n * (T::LPT - 1)) : "memory");
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory");
     };
 
     v16i acc[TM][TN];
@@ -459,9 +473,10 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     const int key = (lane >> 1) & 7;  // swizzle key of this lane's row (tile rows start at multiples of 32)
     const int key4 = (lane >> 2) & 3; // the same for the 64-byte rows of packed 4-bit weights
     const int a_off = (wm * TM * 32 + frag_row) * 128;
-    const int b_off = BM * 128 + (wn * TN * 32 + frag_row) * (W4 ? 64 : 128);
-    auto read_frags = [&](int sl, int quarter, v4i(&af)[TM], v4i(&bf)[TN]) {
-        const unsigned char *st = smem + sl * T::STAGE_BYTES;
+    const int b_off = T::B_RING + (wn * TN * 32 + frag_row) * (W4 ? 64 : 128);
+    auto read_frags = [&](int sl_a, int sl_b, int quarter, v4i(&af)[TM], v4i(&bf)[TN]) {
+        const unsigned char *st = smem + sl_a * T::A_BYTES;
+        const unsigned char *stb = smem + sl_b * T::B_BYTES;
         const int so = ((2 * quarter + frag_half) ^ key) * 16;
 #pragma unroll
         for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const v4i *>(st + a_off + i * 32 * 128 + so);
@@ -469,11 +484,11 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
         for (int j = 0; j < TN; ++j) {
             if (W4) {
                 // 16 k of a quarter's half = 8 packed bytes; byte b of a word: low nibble = k b, high nibble = k 4+b
-                const v2i p = *reinterpret_cast<const v2i *>(st + b_off + j * 32 * 64 + ((quarter ^ key4) * 16) + frag_half * 8);
+                const v2i p = *reinterpret_cast<const v2i *>(stb + b_off + j * 32 * 64 + ((quarter ^ key4) * 16) + frag_half * 8);
                 bf[j] = v4i{(int)(((unsigned)p[0] << 4) & 0xf0f0f0f0u), (int)((unsigned)p[0] & 0xf0f0f0f0u),
                             (int)(((unsigned)p[1] << 4) & 0xf0f0f0f0u), (int)((unsigned)p[1] & 0xf0f0f0f0u)};  // int8 value * 16
             } else {
-                bf[j] = *reinterpret_cast<const v4i *>(st + b_off + j * 32 * 128 + so);
+                bf[j] = *reinterpret_cast<const v4i *>(stb + b_off + j * 32 * 128 + so);
             }
         }
     };
@@ -513,7 +528,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     // 64 loads issued back to back fill the texture-address queue and stall the MFMA issue of every wavefront.
     constexpr int EVERY = T::DMA_EVERY > 0 ? T::DMA_EVERY : 1;
     constexpr bool SPREAD = T::DMA_EVERY > 0;
-    auto mma_dma = [&](const v4i(&af)[TM], const v4i(&bf)[TN], int first, int last, bool on, int kt_i, int slot_i, int i0,
+    auto mma_dma = [&](const v4i(&af)[TM], const v4i(&bf)[TN], int first, int last, bool on, int win, int slot_a, int slot_b, int i0,
                        bool restart = false) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -529,68 +544,81 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
                         acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
                     }
                     const int li = i0 + (idx - first) / EVERY;
-                    if (SPREAD && (idx - first) % EVERY == EVERY - 1 && li < T::LPT) {
-                        if (on && li < my_loads) issue_one(kt_i, slot_i, li);
+                    if (SPREAD && (idx - first) % EVERY == EVERY - 1 && li < NA + NB) {
+                        if (on) issue_win(win, slot_a, slot_b, li);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
             }
     };
     constexpr int N_Q = (NMMA - 1) / EVERY;    // loads that fit behind the MFMAs of one quarter
-    static_assert(!SPREAD || 3 * N_Q >= T::LPT, "the loads of a K step must be issued within three quarters");
+    static_assert(!SPREAD || 3 * N_Q >= NA + NB, "the loads of a refill window must be issued within three quarters");
 
+    // prologue: the first SA activation tiles and SB weight tiles, in K-step order
 #pragma unroll
-    for (int s = 0; s < S; ++s)
-        if (s < nk) issue(s, s);
+    for (int st = 0; st < T::SMAX; ++st) {
+        if (st < SA && st < nk) {
+#pragma unroll
+            for (int i = 0; i < NA; ++i) issue_a(st, st, i);
+        }
+        if (st < SB && st < nk) {
+#pragma unroll
+            for (int i = 0; i < NB; ++i) issue_b(st, st, i);
+        }
+    }
     QL_PHASE(1)
     v4i af0[TM], bf0[TN], af1[TM], bf1[TN];
-    // K step 0 has landed once at most S-1 later steps are outstanding
-    if (nk >= S) wait_steps(std::integral_constant<int, S - 1>{});
-    else wait_steps(std::integral_constant<int, 0>{});
+    // K step 0 has landed once only the later steps of the prologue are outstanding
+    if (nk >= T::SMAX) wait_vm(std::integral_constant<int, T::WAIT_START>{});
+    else wait_vm(std::integral_constant<int, 0>{});
     __builtin_amdgcn_s_barrier();
-    read_frags(0, 0, af0, bf0);
-    int slot = 0;
-    bool refill = false;  // loads of K step kt-1+S into the previous slot are still being issued
+    read_frags(0, 0, 0, af0, bf0);
+    int sa = 0, sb = 0, pa = SA - 1, pb = SB - 1;   // ring slots of K step kt and of step kt-1
     for (int kt = 0; kt < nk; ++kt) {
-        const int next = slot + 1 == S ? 0 : slot + 1;
-        const int prev = slot == 0 ? S - 1 : slot - 1;
+        const int na = sa + 1 == SA ? 0 : sa + 1, nb = sb + 1 == SB ? 0 : sb + 1;
+        const bool refill = kt > 0;   // refill window kt-1 is still being issued during quarters 0 and 1
         // quarter 0 (fragments 0) while reading quarter 1 (fragments 1)
         mma(af0, bf0, 0, 1, true);
         __builtin_amdgcn_sched_barrier(0);
-        read_frags(slot, 1, af1, bf1);
+        read_frags(sa, sb, 1, af1, bf1);
         __builtin_amdgcn_sched_barrier(0);
-        mma_dma(af0, bf0, 1, NMMA, refill, kt - 1 + S, prev, N_Q, true);
+        mma_dma(af0, bf0, 1, NMMA, refill, kt - 1, pa, pb, N_Q, true);
         flush_group = kt;
         __builtin_amdgcn_sched_barrier(0);
         // quarter 1 while reading quarter 2
         mma(af1, bf1, 0, 1);
         __builtin_amdgcn_sched_barrier(0);
-        read_frags(slot, 2, af0, bf0);
+        read_frags(sa, sb, 2, af0, bf0);
         __builtin_amdgcn_sched_barrier(0);
-        mma_dma(af1, bf1, 1, NMMA, refill, kt - 1 + S, prev, 2 * N_Q);
+        mma_dma(af1, bf1, 1, NMMA, refill, kt - 1, pa, pb, 2 * N_Q);
         __builtin_amdgcn_sched_barrier(0);
         // quarter 2 while reading quarter 3
         mma(af0, bf0, 0, 1);
         __builtin_amdgcn_sched_barrier(0);
-        read_frags(slot, 3, af1, bf1);
+        read_frags(sa, sb, 3, af1, bf1);
         __builtin_amdgcn_sched_barrier(0);
         mma(af0, bf0, 1, NMMA);
         __builtin_amdgcn_sched_barrier(0);
         // quarter 3: its first MFMA needs the last fragments of this K step, so once it has issued every read of
-        // this stage by this wavefront is complete.  Then hand over: step kt+1 must be in LDS (steps up to kt+S-1
-        // were issued, so S-2 of them may still be in flight), and after the barrier this stage can be refilled.
+        // this step's slots by this wavefront is complete.  Then hand over: step kt+1 must be in LDS (only loads
+        // issued after its last one may still be in flight), and after the barrier this step's slots can be refilled.
         mma(af1, bf1, 0, 1);
         __builtin_amdgcn_sched_barrier(0);
-        if (kt + S <= nk) wait_steps(std::integral_constant<int, (S >= 2 ? S - 2 : 0)>{});
-        else wait_steps(std::integral_constant<int, 0>{});
+        if (kt + T::SMAX <= nk) wait_vm(std::integral_constant<int, T::WAIT_HAND>{});
+        else wait_vm(std::integral_constant<int, 0>{});
         __builtin_amdgcn_s_barrier();
-        refill = kt + S < nk;
-        if (!SPREAD && refill) issue(kt + S, slot);
-        if (kt + 1 < nk) read_frags(next, 0, af0, bf0);
+        if (!SPREAD) {
+#pragma unroll
+            for (int li = 0; li < NA + NB; ++li) issue_win(kt, sa, sb, li);
+        }
+        if (kt + 1 < nk) read_frags(na, nb, 0, af0, bf0);
         __builtin_amdgcn_sched_barrier(0);
-        mma_dma(af1, bf1, 1, NMMA, refill, kt + S, slot, 0);
+        mma_dma(af1, bf1, 1, NMMA, true, kt, sa, sb, 0);
         __builtin_amdgcn_sched_barrier(0);
-        slot = next;
+        pa = sa;
+        pb = sb;
+        sa = na;
+        sb = nb;
     }
     if (W4) {
 #pragma unroll
@@ -780,6 +808,13 @@ using D8_256x256_8w_e2 = TileD<4, 2, 2, 4, 2, 2, true, 2>;
 using D8_256x192_4w_e2 = TileD<4, 3, 2, 2, 2, 1, true, 2>;
 using D8_64x64_s4 = TileD<1, 1, 2, 2, 4, 4>;
 using D4_128x128_4w = TileD<2, 2, 2, 2, 2, 2, true, 0, true>;
+//                                                       SA                  SB
+using D8_256x192_8w_a3b2 = TileD<2, 3, 4, 2, 3, 2, true, 1, false, 2>;
+using D8_256x192_8w_a2b3 = TileD<2, 3, 4, 2, 2, 2, true, 1, false, 3>;
+using D8_256x256_8w_a3b2 = TileD<4, 2, 2, 4, 3, 2, true, 1, false, 2>;
+using D8_128x128_a3b2 = TileD<2, 2, 2, 2, 3, 2, true, 0, false, 2>;
+using D8_128x128_a3b2_e1 = TileD<2, 2, 2, 2, 3, 2, true, 1, false, 2>;
+using D8_128x128_s2_e1 = TileD<2, 2, 2, 2, 2, 2, true, 1>;
 
 static const Variant VARIANTS[] = {
     {"w8 dma 128x128 s3 4w", 8, 128, 128, 128, run_dma<D8_128x128_s3>},
@@ -797,6 +832,12 @@ static const Variant VARIANTS[] = {
     {"w8 dma 256x256 s2 8w spread2", 8, 256, 256, 128, run_dma<D8_256x256_8w_e2>},
     {"w8 dma 256x192 s2 4w spread2", 8, 256, 192, 128, run_dma<D8_256x192_4w_e2>},
     {"w4 dma 128x128 s2 4w", 4, 128, 128, 128, run_dma<D4_128x128_4w>},
+    {"w8 dma 256x192 a3b2 8w spread1", 8, 256, 192, 128, run_dma<D8_256x192_8w_a3b2>},
+    {"w8 dma 256x192 a2b3 8w spread1", 8, 256, 192, 128, run_dma<D8_256x192_8w_a2b3>},
+    {"w8 dma 256x256 a3b2 8w spread1", 8, 256, 256, 128, run_dma<D8_256x256_8w_a3b2>},
+    {"w8 dma 128x128 a3b2 4w", 8, 128, 128, 128, run_dma<D8_128x128_a3b2>},
+    {"w8 dma 128x128 a3b2 4w spread1", 8, 128, 128, 128, run_dma<D8_128x128_a3b2_e1>},
+    {"w8 dma 128x128 s2 4w spread1", 8, 128, 128, 128, run_dma<D8_128x128_s2_e1>},
     {"w8 128x128 bk64 4w occ2", 8, 128, 128, 64, run_variant<W8_128x128_k64>},
     {"w8 128x128 bk128 4w occ2", 8, 128, 128, 128, run_variant<W8_128x128_k128>},
     {"w8 256x128 bk64 4w occ2", 8, 256, 128, 64, run_variant<W8_256x128_k64>},
@@ -826,16 +867,23 @@ static int find_variant(const char *name)
 // Tile choice by shape, from sweeps over the DiT-XL/2 layer shapes on MI355X (256 CUs).
 static int choose_variant(const GemmArgs &a)
 {
-    static const int w8_small = find_variant("w8 dma 64x64 s4 4w"), w8_mid3 = find_variant("w8 dma 128x128 s3 4w"),
-                     w8_mid2 = find_variant("w8 dma 128x128 s2 4w"), w8_big = find_variant("w8 dma 256x192 s2 8w spread1"),
+    static const int w8_small = find_variant("w8 dma 64x64 s4 4w"),
+                     w8_mid = find_variant("w8 dma 128x128 a3b2 4w spread1"),
+                     w8_mid_deep = find_variant("w8 dma 128x128 a3b2 4w"),
+                     w8_big = find_variant("w8 dma 256x192 s2 8w spread1"),
+                     w8_big_b3 = find_variant("w8 dma 256x192 a2b3 8w spread1"),
+                     w8_wide = find_variant("w8 dma 256x256 s2 8w spread2"),
                      w8_k64 = find_variant("w8 128x128 bk64 4w occ3"), w4_any = find_variant("w4 128x64 bk128 4w occ3");
     if (a.w_bits == 4) return w4_any;   // the register-staged kernel at 3 wavefronts per SIMD hides the per-group VALU work best
     if (a.K % 128 != 0) return w8_k64;
     if (a.M <= 512) return w8_small;
     const long tiles_big = (long)((a.M + 255) / 256) * ((a.N + 191) / 192);
-    if (tiles_big >= 192) return w8_big;                      // at least 3/4 of the CUs get a 256x192 tile
-    const long tiles_mid = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
-    return tiles_mid >= 256 ? w8_mid2 : w8_mid3;              // two resident workgroups per CU only pay off when there are enough tiles
+    if (tiles_big >= 192) {                                   // at least 3/4 of the CUs get a 256x192 tile
+        if (a.N <= 1536 || a.K >= 2304) return w8_big_b3;     // few tile columns or a long K loop: a third weight stage pays
+        if (a.N % 256 == 0 && a.N >= 4096 && a.M >= 8192) return w8_wide;
+        return w8_big;
+    }
+    return a.K >= 2304 ? w8_mid_deep : w8_mid;
 }
 
 hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream)
