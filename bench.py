@@ -29,7 +29,10 @@ POOL = 4                  # distinct activation sets rotated over the steps (dif
 # HBM bytes per GEMM launch (reads + writes, mean over the layers of a step) from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of `bench.py --traffic-probe`, each scaled by what the same counter reads for a device-to-device copy
 # of known size in the same run (summaries under profiles/).  Keyed by (workload, forced variant); absent = not measured.
-TRAFFIC_BYTES_PER_LAUNCH = {}
+TRAFFIC_BYTES_PER_LAUNCH = {
+    ("c2_block_w8a8_m2048", -1): 33655 * 1024,    # (2*fetch + write) KiB, mean of the 4 GEMM launches of a step
+    ("c4_block_w8a8_m16384", -1): 203119 * 1024,
+}
 
 
 def build_layers(ql, torch, wl_name):
@@ -165,7 +168,7 @@ def main():
         src = torch.ones(128 * 1024 * 1024, dtype=torch.float16, device="cuda")
         dst = torch.empty_like(src)
         for i in range(3):
-            dst.copy_(src)
+            torch.mul(src, 1.0, out=dst)   # an elementwise kernel: 256 MiB read, 256 MiB written
         torch.cuda.synchronize()
         print(json.dumps({"traffic_probe": args.workload, "copy_bytes_read": src.numel() * 2,
                           "copy_bytes_written": src.numel() * 2, "steps": 3}))

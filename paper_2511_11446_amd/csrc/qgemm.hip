@@ -26,7 +26,9 @@ typedef int v4i_alias __attribute__((ext_vector_type(4), may_alias));
 #endif
 
 constexpr int XCDS = 8;    // L2 domains of the chip; consecutive workgroup ids go round-robin over them
-constexpr int GROUP_M = 4; // tile rows walked together so that one L2 sees few distinct A and W panels
+constexpr int GROUP_M = 4; // tile rows walked together so that one L2 sees few distinct A and W panels (2..8 measure alike)
+
+static int pick_group_m(int, int) { return GROUP_M; }
 
 __device__ __forceinline__ float half_to_float_dev(unsigned short h)
 {
@@ -58,7 +60,7 @@ struct Tile {
 };
 
 template <class T>
-__global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tiles_m, int tiles_n, int nblk_padded)
+__global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tiles_m, int tiles_n, int nblk_padded, int group_m)
 {
     constexpr int TM = T::TM, TN = T::TN, BK = T::BK, BM = T::BM, BN = T::BN, NT = T::NT;
     constexpr int LDA = T::LDA, LDB = T::LDB, BKB = T::BKB;
@@ -72,9 +74,9 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
     const int per_xcd = nblk_padded / XCDS;
     const int logical = (blockIdx.x % XCDS) * per_xcd + blockIdx.x / XCDS;
     if (logical >= tiles_m * tiles_n) return;
-    const int group_sz = GROUP_M * tiles_n;
-    const int first_m = (logical / group_sz) * GROUP_M;
-    const int gm = min(tiles_m - first_m, GROUP_M);
+    const int group_sz = group_m * tiles_n;
+    const int first_m = (logical / group_sz) * group_m;
+    const int gm = min(tiles_m - first_m, group_m);
     const int tile_m = first_m + (logical % group_sz) % gm;
     const int tile_n = (logical % group_sz) / gm;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
@@ -354,7 +356,7 @@ typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void global_void;
 
 template <class T>
-__global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles_m, int tiles_n, int nblk_padded)
+__global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles_m, int tiles_n, int nblk_padded, int group_m)
 {
     constexpr int TM = T::TM, TN = T::TN, BM = T::BM, BN = T::BN, NT = T::NT, NW = T::NW;
     constexpr bool W4 = T::W4;
@@ -363,9 +365,9 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     const int per_xcd = nblk_padded / XCDS;
     const int logical = (blockIdx.x % XCDS) * per_xcd + blockIdx.x / XCDS;
     if (logical >= tiles_m * tiles_n) return;
-    const int group_sz = GROUP_M * tiles_n;
-    const int first_m = (logical / group_sz) * GROUP_M;
-    const int gm = min(tiles_m - first_m, GROUP_M);
+    const int group_sz = group_m * tiles_n;
+    const int first_m = (logical / group_sz) * group_m;
+    const int gm = min(tiles_m - first_m, group_m);
     const int tile_m = first_m + (logical % group_sz) % gm;
     const int tile_n = (logical % group_sz) / gm;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
@@ -707,7 +709,7 @@ static hipError_t run_dma(const GemmArgs &a, hipStream_t s)
     const int tiles_m = (a.M + T::BM - 1) / T::BM, tiles_n = (a.N + T::BN - 1) / T::BN;
     const int nblk = tiles_m * tiles_n;
     const int padded = (nblk + XCDS - 1) / XCDS * XCDS;
-    hipLaunchKernelGGL(qgemm_dma<T>, dim3(padded), dim3(T::NT), T::LDS_BYTES, s, a, tiles_m, tiles_n, padded);
+    hipLaunchKernelGGL(qgemm_dma<T>, dim3(padded), dim3(T::NT), T::LDS_BYTES, s, a, tiles_m, tiles_n, padded, pick_group_m(tiles_m, tiles_n));
     return hipGetLastError();
 }
 
@@ -767,7 +769,7 @@ static hipError_t run_variant(const GemmArgs &a, hipStream_t s)
     const int tiles_m = (a.M + T::BM - 1) / T::BM, tiles_n = (a.N + T::BN - 1) / T::BN;
     const int nblk = tiles_m * tiles_n;
     const int padded = (nblk + XCDS - 1) / XCDS * XCDS;
-    hipLaunchKernelGGL(qgemm_mfma<T>, dim3(padded), dim3(T::NT), T::LDS_BYTES, s, a, tiles_m, tiles_n, padded);
+    hipLaunchKernelGGL(qgemm_mfma<T>, dim3(padded), dim3(T::NT), T::LDS_BYTES, s, a, tiles_m, tiles_n, padded, pick_group_m(tiles_m, tiles_n));
     return hipGetLastError();
 }
 
