@@ -109,6 +109,20 @@ def daq(x, R, nthreads=1):
     return q, s
 
 
+def daq_robust(x, R, p_ppm=999000, a_bits=8, nthreads=1):
+    """Eq. (4) as printed: x [M,K] float16 -> (codes int8 [M,K], alpha float32 [M/R]) with
+    tau = nearest-rank percentile (p_ppm parts per million) of |x| over each block of R rows, a_bits-bit codes."""
+    xb = _f16bits(x)
+    M, K = xb.shape
+    q = np.empty((M, K), np.int8)
+    s = np.empty((M // R if R > 0 else 0,), np.float32)
+    rc = lib().orc_daq_robust(_p(xb), ctypes.c_int64(M), ctypes.c_int64(K), ctypes.c_int64(R), ctypes.c_int64(p_ppm),
+                              ctypes.c_int(a_bits), _p(q), _p(s), ctypes.c_int(nthreads))
+    if rc:
+        raise ValueError("orc_daq_robust rc=%d" % rc)
+    return q, s
+
+
 def gemm_i8(q, w, nthreads=1):
     """q [M,K] int8, w [N,K] int8 -> acc int32 [M,N]."""
     q = _c(q, np.int8)

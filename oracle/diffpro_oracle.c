@@ -30,6 +30,7 @@
  * (nthreads <= 1 means serial).
  */
 #include <math.h>
+#include <stdlib.h>
 #include <stdint.h>
 #include <string.h>
 
@@ -127,6 +128,66 @@ int orc_daq(const uint16_t *x, int64_t M, int64_t K, int64_t R,
         }
     }
     return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Step 3, eq. (4) as printed: percentile clipping, and the activation */
+/* width b that Step 6 / Algorithm 2 Phase B set per time bin.         */
+/*   tau   = Percentile(|v|, p) over the scale block, nearest rank:    */
+/*           the k-th smallest magnitude, k = ceil(n * p_ppm / 10^6)   */
+/*           (p given in parts per million of 1, 999000 = the paper's  */
+/*           p = 99.9; k clamped to [1, n]; integer arithmetic)        */
+/*   alpha = tau / (2^(b-1) - 1)      (1 if tau = 0)                   */
+/*   code  = round(clip(v, -tau, tau) / alpha), ties to even           */
+/*   a_bits b in [2, 8]; codes are stored as int8                      */
+/* p_ppm = 10^6 and b = 8 is orc_daq().                                */
+/* ------------------------------------------------------------------ */
+static int cmp_u16(const void *a, const void *b)
+{
+    uint16_t x = *(const uint16_t *)a, y = *(const uint16_t *)b;
+    return (x > y) - (x < y);
+}
+
+int orc_daq_robust(const uint16_t *x, int64_t M, int64_t K, int64_t R, int64_t p_ppm, int a_bits,
+                   int8_t *q, float *scale, int nthreads)
+{
+    if (M < 0 || K < 0 || R <= 0 || (M % R) != 0) return 1;
+    if (p_ppm < 1 || p_ppm > 1000000 || a_bits < 2 || a_bits > 8) return 1;
+    int64_t nblk = M / R, n = R * K;
+    const float qmax = (float)((1 << (a_bits - 1)) - 1);
+    int fail = 0;
+    (void)nthreads;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) num_threads(nthreads > 1 ? nthreads : 1)
+#endif
+    for (int64_t b = 0; b < nblk; ++b) {
+        const uint16_t *xb = x + b * n;
+        if (n == 0) continue;
+        /* magnitudes as binary16 bit patterns with the sign cleared: for finite values their integer order is the
+         * numeric order, so sorting the patterns sorts the magnitudes */
+        uint16_t *mag = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)n);
+        if (!mag) { fail = 1; continue; }
+        for (int64_t i = 0; i < n; ++i) mag[i] = (uint16_t)(xb[i] & 0x7fffu);
+        qsort(mag, (size_t)n, sizeof(uint16_t), cmp_u16);
+        int64_t k = (n * p_ppm + 999999) / 1000000;   /* ceil(n p) */
+        if (k < 1) k = 1;
+        if (k > n) k = n;
+        float tau = orc_half_to_float(mag[k - 1]);
+        free(mag);
+        float alpha = (tau == 0.0f) ? 1.0f : tau / qmax;
+        scale[b] = alpha;
+        for (int64_t i = 0; i < n; ++i) {
+            float v = orc_half_to_float(xb[i]);
+            if (v > tau) v = tau;
+            if (v < -tau) v = -tau;
+            float t = v / alpha;
+            float r = nearbyintf(t);
+            if (r > qmax) r = qmax;
+            if (r < -qmax) r = -qmax;
+            q[b * n + i] = (int8_t)r;
+        }
+    }
+    return fail ? 3 : 0;
 }
 
 /* ------------------------------------------------------------------ */

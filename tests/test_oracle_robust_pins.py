@@ -1,0 +1,117 @@
+"""Pins for the oracle's percentile-clipped DAQ (eq. (4) as printed, activation width from Step 6): hand-worked
+cases, the special case that reduces to the absmax quantizer, numpy's nearest-rank percentile, the defining
+property of an order statistic checked by brute force, and invariants of the quantizer.  CPU only.
+"""
+import numpy as np
+import pytest
+
+import workload
+
+
+def f16(a):
+    return np.asarray(a, dtype=np.float16)
+
+
+def test_worked_example_p90_of_ten_values(orc):
+    # magnitudes sorted: 0.5 1 1.5 2 2.5 3 3.5 4 8 100 ; n = 10, p = 90 % -> k = 9 -> tau = 8
+    x = f16([[4.0, -100.0, 0.5, -1.0, 8.0, 1.5, -2.0, 2.5, 3.0, -3.5]])
+    q, s = orc.daq_robust(x, 1, p_ppm=900000, a_bits=8)
+    assert s[0] == np.float32(8.0) / np.float32(127.0)
+    # 8 -> 127, -100 is clipped to -8 -> -127; 4/alpha = 63.5 (exact in fp32? 4/(8/127) rounds to 63.5) -> tie to even 64
+    assert q[0, 4] == 127 and q[0, 1] == -127
+    want = np.rint(np.clip(x.astype(np.float32), -8, 8) / s[0]).astype(np.int8)
+    assert np.array_equal(q, want)
+
+
+def test_worked_example_four_bit_codes(orc):
+    # a_bits = 4 -> qmax = 7; tau = max (p = 100 %) = 7 -> alpha = 1 -> codes are the rounded values, ties to even
+    x = f16([[7.0, -2.5, 3.5, 0.5, -0.5, 1.5, -7.0, 6.49]])
+    q, s = orc.daq_robust(x, 1, p_ppm=1000000, a_bits=4)
+    assert s[0] == np.float32(1.0)
+    assert q.tolist() == [[7, -2, 4, 0, 0, 2, -7, 6]]
+
+
+@pytest.mark.parametrize("R", [1, 4, 16])
+def test_p100_b8_is_the_absmax_quantizer(orc, R):
+    x = workload.activations(16, 256, "robust-pin", R, sigma=1.3)
+    q0, s0 = orc.daq(x, R)
+    q1, s1 = orc.daq_robust(x, R, p_ppm=1000000, a_bits=8)
+    assert np.array_equal(q0, q1) and np.array_equal(s0.view(np.uint32), s1.view(np.uint32))
+
+
+@pytest.mark.parametrize("p_ppm", [999000, 990000, 900000, 500000, 1])
+@pytest.mark.parametrize("R,K", [(1, 1152), (8, 96), (32, 64)])
+def test_tau_is_numpys_nearest_rank_percentile(orc, p_ppm, R, K):
+    M = 32
+    x = workload.activations(M, K, "robust-np", p_ppm, R, sigma=2.0)
+    _, s = orc.daq_robust(x, R, p_ppm=p_ppm, a_bits=8)
+    mag = np.abs(x.astype(np.float64)).reshape(M // R, R * K)
+    n = R * K
+    k = -(-n * p_ppm // 1000000)            # ceil in integers
+    # numpy's inverted_cdf is the nearest-rank definition; ask for a probability safely inside rank k's interval
+    prob = (k - 0.5) / n
+    tau = np.quantile(mag, prob, axis=1, method="inverted_cdf")
+    want = np.where(tau == 0, np.float32(1), tau.astype(np.float32) / np.float32(127)).astype(np.float32)
+    assert np.array_equal(s.view(np.uint32), want.view(np.uint32))
+
+
+def test_tau_has_the_defining_property_of_the_kth_order_statistic(orc):
+    # brute force on a block with many ties: at least k magnitudes are <= tau, fewer than k are < tau
+    g = np.random.default_rng(251111446)
+    x = f16(g.integers(-6, 7, size=(6, 50)) * 0.25)
+    for p_ppm in (999000, 800000, 333333, 20000):
+        _, s = orc.daq_robust(x, 2, p_ppm=p_ppm, a_bits=8)
+        for b in range(3):
+            mag = np.abs(x[2 * b:2 * b + 2].astype(np.float64)).ravel()
+            n = mag.size
+            k = -(-n * p_ppm // 1000000)
+            tau = float(s[b]) * 127 if not (mag <= 0).sum() >= k else 0.0
+            if tau == 0.0:
+                assert s[b] == 1.0
+                continue
+            cands = np.unique(mag)
+            tau_v = cands[np.argmin(np.abs(cands - tau))]     # alpha*127 carries one rounding; snap to the data
+            assert (mag <= tau_v).sum() >= k and (mag < tau_v).sum() < k
+
+
+def test_clipped_elements_get_full_scale_codes_and_the_rest_obey_the_error_bound(orc):
+    x = workload.activations(64, 1152, "robust-bound", sigma=1.0)
+    for a_bits in (8, 6, 4, 2):
+        qmax = (1 << (a_bits - 1)) - 1
+        q, s = orc.daq_robust(x, 1, p_ppm=990000, a_bits=a_bits)
+        xf = x.astype(np.float64)
+        alpha = s.astype(np.float64)[:, None]
+        tau = alpha * qmax
+        assert np.abs(q).max() <= qmax
+        over = np.abs(xf) > tau * (1 + 1e-6)
+        # at most 1 % of each row lies above the 99th percentile
+        assert (over.sum(axis=1) <= 1152 - (-(-1152 * 990000 // 1000000))).all()
+        assert np.array_equal(q[over], (np.sign(xf[over]) * qmax).astype(np.int8))
+        inside = ~over
+        err = np.abs(np.clip(xf, -tau, tau) - alpha * q)
+        assert (err[inside] <= (alpha * (0.5 + 2.0 ** -16) * np.ones_like(xf))[inside]).all()
+
+
+def test_invariants_zero_block_sign_and_power_of_two(orc):
+    x = workload.activations(8, 128, "robust-inv", sigma=0.7)
+    x[2] = 0
+    q, s = orc.daq_robust(x, 1, p_ppm=950000, a_bits=5)
+    assert s[2] == 1.0 and not q[2].any()
+    qn, sn = orc.daq_robust(-x, 1, p_ppm=950000, a_bits=5)
+    assert np.array_equal(qn, -q) and np.array_equal(sn, s)
+    q4, s4 = orc.daq_robust(f16(x.astype(np.float32) * 4), 1, p_ppm=950000, a_bits=5)
+    assert np.array_equal(q4, q)
+    nz = np.arange(8) != 2
+    assert np.array_equal(s4[nz], s[nz] * np.float32(4))
+    # more than p of the block is zero -> tau = 0 -> alpha = 1, all codes 0 (the non-zero few are clipped to 0)
+    z = np.zeros((1, 100), np.float16)
+    z[0, :5] = 3.0
+    qz, sz = orc.daq_robust(z, 1, p_ppm=900000, a_bits=8)
+    assert sz[0] == 1.0 and not qz.any()
+
+
+def test_bad_arguments_are_refused(orc):
+    x = np.zeros((4, 8), np.float16)
+    for kw in (dict(p_ppm=0), dict(p_ppm=1000001), dict(a_bits=1), dict(a_bits=9)):
+        with pytest.raises(ValueError):
+            orc.daq_robust(x, 1, **kw)
