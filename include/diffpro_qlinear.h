@@ -182,6 +182,36 @@ int qlinear_plan_run(const ql_plan *plan, const void *const *x_in, void *const *
                      void *workspace, size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------
+ * Percentile-clipped DAQ with a selectable activation width: eq. (4) as
+ * printed (Step 3), b set per time bin (Step 6, Algorithm 2 Phase B).
+ *   tau   = Percentile(|v|, p) over each scale block of R rows, nearest rank:
+ *           the k-th smallest magnitude, k = ceil(n * p_ppm / 10^6), n = R*K
+ *   alpha = tau / (2^(a_bits-1) - 1)      (1 if tau = 0)
+ *   code  = round_half_even(clip(v, -tau, tau) / alpha), stored as int8
+ * p_ppm in [1, 10^6] (999000 = the paper's p = 99.9), a_bits in [2, 8], else
+ * QL_ERR_UNSUPPORTED; {1000000, 8} gives daq_quantize()'s result.  All other
+ * arguments, the workspace (daq_workspace_bytes / ql_plan_workspace_bytes)
+ * and the error behaviour are those of daq_quantize / qlinear_plan_run.
+ * params: host memory, read during the call.
+ * ---------------------------------------------------------------------- */
+typedef struct ql_daq_params {
+    int32_t p_ppm;
+    int32_t a_bits;
+} ql_daq_params;
+
+int daq_quantize_robust(const void *x, int64_t M, int64_t K, int64_t R, const ql_daq_params *params,
+                        void *q, void *scales, void *workspace, size_t workspace_bytes, void *stream);
+
+int qlinear_plan_run_robust(const ql_plan *plan, const void *const *x_in, void *const *y_out,
+                            int64_t M, int64_t R, const ql_daq_params *params,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/* Host helper for the time-bin policy of Step 6: bin of step `step` (0-based, in
+ * sampling order) out of num_steps, equal thirds: 0 early, 1 mid, 2 late;
+ * -1 for arguments out of range.  The caller maps the bin to a_bits. */
+int ql_time_bin(int64_t step, int64_t num_steps);
+
+/* ------------------------------------------------------------------------
  * Tuning hooks (benchmark sweeps).  ql_set_gemm_variant(v) forces GEMM tile
  * variant v for later calls from this process (-1 = choose by shape;
  * v == ql_num_gemm_variants() = the generic one-thread-per-element kernel);

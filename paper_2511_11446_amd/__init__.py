@@ -21,7 +21,7 @@ EXPORTS = ("ql_status_string", "ql_last_device_error", "ql_version", "daq_worksp
            "qlinear_workspace_bytes", "qlinear_w8a8", "qlinear_w4a8", "qgemm_w8a8", "qgemm_w4a8",
            "ql_pack_w4_host", "ql_plan_create", "ql_plan_destroy", "ql_plan_num_layers",
            "ql_plan_workspace_bytes", "qlinear_plan_run", "ql_set_gemm_variant", "ql_num_gemm_variants",
-           "ql_gemm_variant_name", "ql_probe_mfma_int8")
+           "ql_gemm_variant_name", "ql_probe_mfma_int8", "daq_quantize_robust", "qlinear_plan_run_robust", "ql_time_bin")
 
 
 class QlError(RuntimeError):
@@ -86,6 +86,12 @@ def lib():
     L.ql_plan_workspace_bytes.argtypes = [_vp, _i64, _i64]
     L.ql_plan_workspace_bytes.restype = _sz
     L.qlinear_plan_run.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _i64, _i64, _vp, _sz, _vp]
+    L.qlinear_plan_run_robust.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _i64, _i64, _vp, _vp, _sz, _vp]
+    L.qlinear_plan_run_robust.restype = _int
+    L.daq_quantize_robust.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
+    L.daq_quantize_robust.restype = _int
+    L.ql_time_bin.argtypes = [_i64, _i64]
+    L.ql_time_bin.restype = _int
     L.ql_set_gemm_variant.argtypes = [_int]
     _lib = L
     return L
@@ -145,6 +151,32 @@ def daq_quantize(x, R, q=None, scales=None, ws=None, stream=None):
                             _stream(stream))
     _check(rc, "daq_quantize")
     return q, scales
+
+
+class _DaqParams(ctypes.Structure):
+    _fields_ = [("p_ppm", ctypes.c_int32), ("a_bits", ctypes.c_int32)]
+
+
+def daq_quantize_robust(x, R, p_ppm=999000, a_bits=8, q=None, scales=None, ws=None, stream=None):
+    """Percentile-clipped DAQ: x fp16 [M,K] -> (q int8 [M,K] with |q| <= 2^(a_bits-1)-1, scales fp32 [M/R])."""
+    import torch
+    _need(x, torch.float16, name="x")
+    M, K = x.shape
+    if q is None:
+        q = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    if scales is None:
+        scales = torch.empty((max(M // max(R, 1), 1),), dtype=torch.float32, device=x.device)
+    if ws is None and R > 1:
+        ws = workspace(daq_workspace_bytes(M, K, R), x.device)
+    prm = _DaqParams(p_ppm, a_bits)
+    rc = lib().daq_quantize_robust(_ptr(x), M, K, R, ctypes.byref(prm), _ptr(q), _ptr(scales), _ptr(ws),
+                                   0 if ws is None else ws.numel(), _stream(stream))
+    _check(rc, "daq_quantize_robust")
+    return q, scales
+
+
+def time_bin(step, num_steps):
+    return int(lib().ql_time_bin(step, num_steps))
 
 
 def _qlinear(fn_name, x, R, w, w_scale, bias, N, y, debug, ws, stream):
@@ -255,6 +287,11 @@ class Plan:
     def run_ptrs(self, xs, ys, M, R, ws, stream_ptr):
         """Same with pre-marshalled pointer arrays (keeps Python out of a timed loop)."""
         _check(lib().qlinear_plan_run(self.handle, xs, ys, M, R, _ptr(ws), ws.numel(), stream_ptr), "qlinear_plan_run")
+
+    def run_ptrs_robust(self, xs, ys, M, R, p_ppm, a_bits, ws, stream_ptr):
+        prm = _DaqParams(p_ppm, a_bits)
+        _check(lib().qlinear_plan_run_robust(self.handle, xs, ys, M, R, ctypes.byref(prm), _ptr(ws), ws.numel(), stream_ptr),
+               "qlinear_plan_run_robust")
 
     def close(self):
         if self.handle:

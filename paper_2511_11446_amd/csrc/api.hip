@@ -36,12 +36,29 @@ int check_shape(int64_t M, int64_t K, int64_t R, int64_t N)
 
 inline bool misaligned(const void *p, size_t a) { return p && ((uintptr_t)p % a) != 0; }
 
-// DAQ scratch for R > 1: [block maxima M/R][partial maxima (M/R) * parts]
+// DAQ scratch for R > 1.  Absmax: [block maxima M/R][partial maxima (M/R) * parts]; percentile: [tau patterns M/R]
+// [selection histograms (M/R) * DAQ_ROBUST_WORDS].  One size covers both, so a workspace serves either mode.
 size_t daq_scratch_bytes(int64_t M, int64_t K, int64_t R)
 {
     if (M < 1 || R <= 1 || M % R != 0) return 0;
     const size_t nblk = (size_t)(M / R);
-    return align_up(nblk * 4, 256) + align_up(nblk * ql::daq_parts_per_block(K, R) * 4, 256);
+    const size_t plain = align_up(nblk * ql::daq_parts_per_block(K, R) * 4, 256);
+    const size_t robust = align_up(nblk * ql::DAQ_ROBUST_WORDS * 4, 256);
+    return align_up(nblk * 4, 256) + (plain > robust ? plain : robust);
+}
+
+// eq. (4): rank from the top of the nearest-rank percentile, c = n - ceil(n p) + 1 with n = R*K values per scale block
+int robust_args(const ql_daq_params *dp, int64_t K, int64_t R, ql::DaqArgs &d)
+{
+    if (dp->p_ppm < 1 || dp->p_ppm > 1000000 || dp->a_bits < 2 || dp->a_bits > 8) return QL_ERR_UNSUPPORTED;
+    const int64_t n = R * K;
+    if (n > (int64_t)1 << 31) return QL_ERR_SHAPE;
+    int64_t k = (n * (int64_t)dp->p_ppm + 999999) / 1000000;
+    if (k < 1) k = 1;
+    if (k > n) k = n;
+    d.top_rank = (unsigned)(n - k + 1);
+    d.qmax = (1 << (dp->a_bits - 1)) - 1;
+    return QL_OK;
 }
 
 // workspace layout of one layer: [codes M*K][scales M/R][DAQ scratch (R > 1)]
@@ -69,20 +86,29 @@ int check_workspace(void *ws, size_t have, size_t need)
 
 // DAQ then GEMM for one layer; all arguments already validated
 int run_layer(const void *x, int64_t M, int64_t K, int64_t R, int w_bits, const void *w, const void *w_scale,
-              const void *bias, int64_t N, void *y, const ql_debug *dbg, void *workspace, hipStream_t stream)
+              const void *bias, int64_t N, void *y, const ql_debug *dbg, void *workspace, hipStream_t stream,
+              const ql_daq_params *dp = nullptr)
 {
     const LayerWs lw = layer_ws(M, K, R);
     unsigned char *base = static_cast<unsigned char *>(workspace);
-    ql::DaqArgs d;
+    ql::DaqArgs d{};
     d.x = x;
     d.q = (dbg && dbg->q) ? static_cast<int8_t *>(dbg->q) : reinterpret_cast<int8_t *>(base + lw.q_off);
     d.scales = (dbg && dbg->a_scales) ? static_cast<float *>(dbg->a_scales) : reinterpret_cast<float *>(base + lw.s_off);
     d.blockmax = R > 1 ? reinterpret_cast<unsigned *>(base + lw.bm_off) : nullptr;
     d.partmax = R > 1 ? reinterpret_cast<unsigned *>(base + lw.bm_off + align_up((size_t)(M / R) * 4, 256)) : nullptr;
+    d.hist = d.partmax;
     d.M = (int)M;
     d.K = (int)K;
     d.R = (int)R;
-    int rc = device_status(ql::launch_daq(d, stream));
+    int rc;
+    if (dp) {
+        rc = robust_args(dp, K, R, d);
+        if (rc) return rc;
+        rc = device_status(ql::launch_daq_robust(d, stream));
+    } else {
+        rc = device_status(ql::launch_daq(d, stream));
+    }
     if (rc) return rc;
     ql::GemmArgs g;
     g.q = d.q;
@@ -185,26 +211,51 @@ size_t daq_workspace_bytes(int64_t M, int64_t K, int64_t R)
     return daq_scratch_bytes(M, K, R);
 }
 
-int daq_quantize(const void *x, int64_t M, int64_t K, int64_t R, void *q, void *scales, void *workspace,
-                 size_t workspace_bytes, void *stream)
+static int daq_any(const void *x, int64_t M, int64_t K, int64_t R, const ql_daq_params *dp, void *q, void *scales,
+                   void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!x || !q || !scales) return QL_ERR_NULL;
     if (misaligned(x, 2) || misaligned(scales, 4)) return QL_ERR_ALIGN;
     int rc = check_shape(M, K, R, 1);
     if (rc) return rc;
+    ql::DaqArgs d{};
+    if (dp) {
+        rc = robust_args(dp, K, R, d);
+        if (rc) return rc;
+    }
     rc = check_workspace(workspace, workspace_bytes, daq_workspace_bytes(M, K, R));
     if (rc) return rc;
-    ql::DaqArgs d;
     d.x = x;
     d.q = static_cast<int8_t *>(q);
     d.scales = static_cast<float *>(scales);
     d.blockmax = R > 1 ? static_cast<unsigned *>(workspace) : nullptr;
     d.partmax = R > 1 ? reinterpret_cast<unsigned *>(static_cast<unsigned char *>(workspace) + align_up((size_t)(M / R) * 4, 256))
                       : nullptr;
+    d.hist = d.partmax;
     d.M = (int)M;
     d.K = (int)K;
     d.R = (int)R;
-    return device_status(ql::launch_daq(d, static_cast<hipStream_t>(stream)));
+    return device_status(dp ? ql::launch_daq_robust(d, static_cast<hipStream_t>(stream))
+                            : ql::launch_daq(d, static_cast<hipStream_t>(stream)));
+}
+
+int daq_quantize(const void *x, int64_t M, int64_t K, int64_t R, void *q, void *scales, void *workspace,
+                 size_t workspace_bytes, void *stream)
+{
+    return daq_any(x, M, K, R, nullptr, q, scales, workspace, workspace_bytes, stream);
+}
+
+int daq_quantize_robust(const void *x, int64_t M, int64_t K, int64_t R, const ql_daq_params *params, void *q, void *scales,
+                        void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!params) return QL_ERR_NULL;
+    return daq_any(x, M, K, R, params, q, scales, workspace, workspace_bytes, stream);
+}
+
+int ql_time_bin(int64_t step, int64_t num_steps)
+{
+    if (num_steps < 1 || step < 0 || step >= num_steps) return -1;
+    return (int)(step * 3 / num_steps);
 }
 
 size_t qlinear_workspace_bytes(int64_t M, int64_t K, int64_t R)
@@ -292,11 +343,12 @@ size_t ql_plan_workspace_bytes(const ql_plan *plan, int64_t M, int64_t R)
     return layer_ws(M, plan->K_widest, R).total;
 }
 
-int qlinear_plan_run(const ql_plan *plan, const void *const *x_in, void *const *y_out, int64_t M, int64_t R,
-                     void *workspace, size_t workspace_bytes, void *stream)
+static int plan_run_any(const ql_plan *plan, const void *const *x_in, void *const *y_out, int64_t M, int64_t R,
+                        const ql_daq_params *dp, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!plan || !x_in || !y_out) return QL_ERR_NULL;
     if (M < 1 || R < 1 || M % R != 0 || M > plan->M_max) return QL_ERR_SHAPE;
+    if (dp && (dp->p_ppm < 1 || dp->p_ppm > 1000000 || dp->a_bits < 2 || dp->a_bits > 8)) return QL_ERR_UNSUPPORTED;
     for (size_t l = 0; l < plan->layers.size(); ++l) {
         if (!x_in[l] || !y_out[l]) return QL_ERR_NULL;
         if (misaligned(x_in[l], 2) || misaligned(y_out[l], 2)) return QL_ERR_ALIGN;
@@ -306,10 +358,23 @@ int qlinear_plan_run(const ql_plan *plan, const void *const *x_in, void *const *
     hipStream_t s = static_cast<hipStream_t>(stream);
     for (size_t l = 0; l < plan->layers.size(); ++l) {
         const ql_layer_desc &d = plan->layers[l];
-        rc = run_layer(x_in[l], M, d.K, R, d.w_bits, d.w, d.w_scale, d.bias, d.N, y_out[l], nullptr, workspace, s);
+        rc = run_layer(x_in[l], M, d.K, R, d.w_bits, d.w, d.w_scale, d.bias, d.N, y_out[l], nullptr, workspace, s, dp);
         if (rc) return rc;
     }
     return QL_OK;
+}
+
+int qlinear_plan_run(const ql_plan *plan, const void *const *x_in, void *const *y_out, int64_t M, int64_t R,
+                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    return plan_run_any(plan, x_in, y_out, M, R, nullptr, workspace, workspace_bytes, stream);
+}
+
+int qlinear_plan_run_robust(const ql_plan *plan, const void *const *x_in, void *const *y_out, int64_t M, int64_t R,
+                            const ql_daq_params *params, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!params) return QL_ERR_NULL;
+    return plan_run_any(plan, x_in, y_out, M, R, params, workspace, workspace_bytes, stream);
 }
 
 int ql_set_gemm_variant(int variant)

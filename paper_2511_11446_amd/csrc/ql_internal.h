@@ -21,7 +21,12 @@ struct DaqArgs {
     unsigned *blockmax;  // [M/R] fp16 bit patterns of block maxima (workspace), R > 1 only
     unsigned *partmax;   // [M/R][daq_parts_per_block] partial maxima (workspace), R > 1 only
     int M, K, R;
+    // percentile-clipped variant only (launch_daq_robust)
+    int qmax;            // 2^(b-1) - 1 for b-bit activation codes
+    unsigned top_rank;   // tau = the top_rank-th largest magnitude of a scale block (1 = the maximum)
+    unsigned *hist;      // [M/R][DAQ_ROBUST_WORDS] selection scratch (workspace), R > 1 only
 };
+constexpr int DAQ_ROBUST_WORDS = 256 + 2 + 128;
 
 // R > 1: the first pass cuts every scale block (R*K contiguous values) into this many parts and leaves one partial
 // maximum per part; 0 when the shape takes the row kernels instead (no partials needed).
@@ -35,6 +40,8 @@ inline size_t daq_parts_per_block(int64_t K, int64_t R)
 }
 
 hipError_t launch_daq(const DaqArgs &a, hipStream_t stream);
+// eq. (4) with tau = a percentile of the magnitudes and a selectable code width
+hipError_t launch_daq_robust(const DaqArgs &a, hipStream_t stream);
 
 // ---- GEMM + dequantization -------------------------------------------------
 struct GemmArgs {

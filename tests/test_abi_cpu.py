@@ -156,3 +156,23 @@ def test_daq_division_free_codes_exhaustive(tmp_path):
     r = subprocess.run([exe], capture_output=True, text=True, timeout=600)
     assert r.returncode == 0, r.stdout + r.stderr
     assert "mismatches 0 out-of-range 0" in r.stdout
+
+
+class _Prm(ctypes.Structure):
+    _fields_ = [("p_ppm", ctypes.c_int32), ("a_bits", ctypes.c_int32)]
+
+
+def test_robust_daq_argument_checks_and_time_bins():
+    L = ql.lib()
+    ok = _Prm(999000, 8)
+    assert L.daq_quantize_robust(FAKE, 4, 8, 1, None, FAKE, FAKE, None, 0, None) == 1
+    assert L.daq_quantize_robust(None, 4, 8, 1, ctypes.byref(ok), FAKE, FAKE, None, 0, None) == 1
+    assert L.daq_quantize_robust(FAKE, 6, 8, 4, ctypes.byref(ok), FAKE, FAKE, None, 0, None) == 2
+    for bad in (_Prm(0, 8), _Prm(1000001, 8), _Prm(999000, 1), _Prm(999000, 9)):
+        assert L.daq_quantize_robust(FAKE, 4, 8, 1, ctypes.byref(bad), FAKE, FAKE, None, 0, None) == 4
+    assert L.daq_quantize_robust(FAKE, 8, 8, 4, ctypes.byref(ok), FAKE, FAKE, None, 0, None) == 5
+    assert L.qlinear_plan_run_robust(None, None, None, 4, 1, ctypes.byref(ok), None, 0, None) == 1
+    # equal thirds of the schedule, in sampling order
+    assert [ql.time_bin(i, 6) for i in range(6)] == [0, 0, 1, 1, 2, 2]
+    assert [ql.time_bin(i, 25) for i in (0, 8, 9, 16, 17, 24)] == [0, 0, 1, 1, 2, 2]
+    assert ql.time_bin(-1, 5) == -1 and ql.time_bin(5, 5) == -1 and ql.time_bin(0, 0) == -1

@@ -360,6 +360,100 @@ def test_c4_per_sample_scales_m16384(gpu, orc):
     _sampled_layer_check(gpu, orc, "proj", 1152, 1152, 8, M, R, rows, "c4ps", 2.0)
 
 
+# ------------------------------------------------------------------ percentile-clipped DAQ (eq. (4) as printed)
+
+ROBUST_CASES = [
+    # M, K, R, p_ppm, a_bits
+    (64, 1152, 1, 999000, 8),      # the paper's p = 99.9: second largest of 1152
+    (16, 4608, 1, 999000, 8),      # fifth largest of 4608
+    (37, 1152, 1, 990000, 6),
+    (8, 8192, 1, 900000, 4),       # largest register-cached row
+    (3, 16384, 1, 999000, 8),      # re-read path
+    (5, 100, 1, 950000, 5), (7, 1151, 1, 999000, 8), (9, 3, 3, 500000, 8),   # K % 8 != 0
+    (8, 64, 1, 1000000, 8), (8, 8, 1, 1, 2),
+    (256, 1152, 256, 999000, 8),   # one image per scale: histogram selection
+    (512, 1152, 256, 990000, 4), (48, 256, 4, 750000, 7), (48, 256, 48, 999000, 8),
+    (1024, 384, 1024, 999900, 8), (40, 100, 8, 900000, 8),
+]
+
+
+@pytest.mark.parametrize("M,K,R,p_ppm,a_bits", ROBUST_CASES)
+def test_daq_robust_parity(gpu, orc, M, K, R, p_ppm, a_bits):
+    say("daq robust", M, K, R, p_ppm, a_bits)
+    x = workload.activations(M, K, "daq-robust", R, p_ppm, sigma=float(workload.rng("rsig", M, K).uniform(0.05, 6.0)))
+    q_ref, s_ref = orc.daq_robust(x, R, p_ppm=p_ppm, a_bits=a_bits, nthreads=8)
+    q, s = gpu.daq_quantize_robust(dev(x), R, p_ppm=p_ppm, a_bits=a_bits)
+    assert np.array_equal(host(s).view(np.uint32), s_ref.view(np.uint32))
+    assert np.array_equal(host(q), q_ref)
+
+
+def test_daq_robust_ties_zero_blocks_and_absmax_special_case(gpu, orc):
+    say("daq robust ties / zero blocks")
+    g = workload.rng("robust-ties")
+    x = (g.integers(-5, 6, size=(24, 1152)) * 0.5).astype(np.float16)    # few distinct magnitudes: heavy ties
+    x[3] = 0
+    x[5, 7:] = 0                                                          # more than p of the row is zero -> tau = 0
+    for R in (1, 8):
+        for p_ppm, a_bits in ((999000, 8), (600000, 3), (1000000, 8)):
+            q_ref, s_ref = orc.daq_robust(x, R, p_ppm=p_ppm, a_bits=a_bits)
+            q, s = gpu.daq_quantize_robust(dev(x), R, p_ppm=p_ppm, a_bits=a_bits)
+            assert np.array_equal(host(s).view(np.uint32), s_ref.view(np.uint32)), (R, p_ppm)
+            assert np.array_equal(host(q), q_ref), (R, p_ppm)
+    # p = 100 %, 8 bits: the absmax entry point's result
+    x2 = workload.activations(64, 1152, "robust-absmax")
+    q0, s0 = gpu.daq_quantize(dev(x2), 1)
+    q1, s1 = gpu.daq_quantize_robust(dev(x2), 1, p_ppm=1000000, a_bits=8)
+    assert np.array_equal(host(q0), host(q1)) and np.array_equal(host(s0), host(s1))
+
+
+def test_daq_robust_full_size_rows_sampled(gpu, orc):
+    """M = 16384 per token at the paper's p; the oracle checks a seeded sample of the rows (rows are independent)."""
+    M, K = 16384, 1152
+    say("daq robust full size", M, K)
+    x = workload.activations(M, K, "robust-full", sigma=2.0)
+    q, s = gpu.daq_quantize_robust(dev(x), 1, p_ppm=999000, a_bits=8)
+    rows = np.sort(workload.rng("robust-rows").choice(M, size=512, replace=False))
+    q_ref, s_ref = orc.daq_robust(x[rows], 1, p_ppm=999000, a_bits=8, nthreads=8)
+    assert np.array_equal(host(q)[rows], q_ref)
+    assert np.array_equal(host(s)[rows].view(np.uint32), s_ref.view(np.uint32))
+
+
+def test_plan_runner_robust_time_bins(gpu, orc):
+    """Algorithm 2 Phase B: the same plan run with the activation width of each time bin."""
+    import ctypes
+    import torch
+    M, R = 256, 64
+    shapes = [("a", 256, 384, 8), ("b", 384, 256, 4)]
+    layers, xs = [], []
+    for name, K, N, bits in shapes:
+        lw = workload.layer_weights(name, K, N, bits, "plan-robust")
+        w = dev(lw["w"]) if bits == 8 else dev(gpu.ql_pack_w4_host(lw["w"]))
+        layers.append(dict(K=K, N=N, bits=bits, w=w, w_scale=dev(lw["s_w"]), bias=dev(lw["bias"]), host=lw))
+        xs.append(workload.activations(M, K, "plan-robust", name))
+    plan = gpu.Plan([{k: v for k, v in l.items() if k != "host"} for l in layers], M_max=M)
+    ys = [torch.zeros((M, l["N"]), dtype=torch.float16, device="cuda") for l in layers]
+    xd = [dev(x) for x in xs]
+    ws = gpu.workspace(plan.workspace_bytes(M, R))
+    xp = (ctypes.c_void_p * 2)(*[t.data_ptr() for t in xd])
+    yp = (ctypes.c_void_p * 2)(*[t.data_ptr() for t in ys])
+    sptr = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    policy = {0: 8, 1: 6, 2: 4}          # activation bits per bin (early, mid, late)
+    for step in (0, 4, 8):
+        a_bits = policy[gpu.time_bin(step, 9)]
+        say("plan robust step", step, "a_bits", a_bits)
+        plan.run_ptrs_robust(xp, yp, M, R, 999000, a_bits, ws, sptr)
+        torch.cuda.synchronize()
+        for l, x, y in zip(layers, xs, ys):
+            lw = l["host"]
+            q, s = orc.daq_robust(x, R, p_ppm=999000, a_bits=a_bits)
+            if l["bits"] == 8:
+                ref = orc.epilogue_w8(orc.gemm_i8(q, lw["w"]), s, R, lw["s_w"], lw["bias"])
+            else:
+                ref = orc.epilogue_w4(orc.gemm_w4g128(q, orc.pack_w4(lw["w"])), s, R, lw["s_w"], lw["bias"])
+            assert assert_y_close(host(y), ref) == 0
+    plan.close()
+
+
 # ------------------------------------------------------------------ plan runner
 
 def test_plan_runner_small_mixed_plan(gpu, orc):
