@@ -122,6 +122,9 @@ def main():
     ap.add_argument("--variant", type=int, default=-1, help="force a GEMM tile variant (sweeps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
+    ap.add_argument("--daq-p-ppm", type=int, default=None,
+                    help="percentile-clipped DAQ (eq. (4) as printed): p in parts per million, e.g. 999000; default: absmax")
+    ap.add_argument("--a-bits", type=int, default=8, help="activation code width for --daq-p-ppm (Step 6 time-bin policy)")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: a few steps of the workload plus a device copy of known size, no timing")
     args = ap.parse_args()
@@ -174,14 +177,28 @@ def main():
                           "copy_bytes_written": src.numel() * 2, "steps": 3}))
         return
 
+    robust = args.daq_p_ppm is not None
+
+    def run_step(i):
+        if robust:
+            plan.run_ptrs_robust(xs_pool[i % len(pool)], ys, M, R, args.daq_p_ppm, args.a_bits, ws, sptr)
+        else:
+            plan.run_ptrs(xs_pool[i % len(pool)], ys, M, R, ws, sptr)
+
+    def run_daq(x, q, sa, dws):
+        if robust:
+            ql.daq_quantize_robust(x, R, args.daq_p_ppm, args.a_bits, q, sa, dws)
+        else:
+            ql.daq_quantize(x, R, q, sa, dws)
+
     for i in range(warmup):
-        plan.run_ptrs(xs_pool[i % len(pool)], ys, M, R, ws, sptr)
+        run_step(i)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t_wall0 = time.perf_counter()
     e0.record(stream)
     for i in range(steps):
-        plan.run_ptrs(xs_pool[i % len(pool)], ys, M, R, ws, sptr)
+        run_step(i)
     e1.record(stream)
     torch.cuda.synchronize()
     t_wall = time.perf_counter() - t_wall0
@@ -227,11 +244,11 @@ def main():
             y = torch.empty((M, l["N"]), dtype=torch.float16, device="cuda")
             gfn = ql.qgemm_w8a8 if l["bits"] == 8 else ql.qgemm_w4a8
             # eager once (also the comparison for the graph replays below)
-            ql.daq_quantize(x, R, q, sa, dws)
+            run_daq(x, q, sa, dws)
             gfn(q, sa, R, l["w"], l["w_scale"], l["bias"], y=y)
             torch.cuda.synchronize()
             q_ref, y_ref = q.clone(), y.clone()
-            td = timed_graph(lambda: ql.daq_quantize(x, R, q, sa, dws))
+            td = timed_graph(lambda: run_daq(x, q, sa, dws))
             tg = timed_graph(lambda: gfn(q, sa, R, l["w"], l["w_scale"], l["bias"], y=y))
             if not (torch.equal(q, q_ref) and torch.equal(y, y_ref)):
                 raise RuntimeError("graph replay of %s/w%d differs from the eager launch" % key)
@@ -289,7 +306,8 @@ def main():
         "pct_measured_mfma_only": (100.0 * tops / mfma_ceiling) if mfma_ceiling else None,
         "config": {"workload": args.workload, "M": M, "rows_per_scale": R, "layers": L,
                    "w4_layers": sum(l["bits"] == 4 for l in layers), "activation_sets_rotated": len(pool),
-                   "sigmas": sigmas, "gemm_variant": args.variant},
+                   "sigmas": sigmas, "gemm_variant": args.variant,
+                   "daq": ("percentile p_ppm=%d a_bits=%d" % (args.daq_p_ppm, args.a_bits)) if robust else "absmax a_bits=8"},
         "host_wall_ms_per_step": t_wall / steps * 1e3,
         "roofline": roofline,
         "cpu_baseline": cpu,
