@@ -399,6 +399,13 @@ def test_daq_robust_ties_zero_blocks_and_absmax_special_case(gpu, orc):
             q, s = gpu.daq_quantize_robust(dev(x), R, p_ppm=p_ppm, a_bits=a_bits)
             assert np.array_equal(host(s).view(np.uint32), s_ref.view(np.uint32)), (R, p_ppm)
             assert np.array_equal(host(q), q_ref), (R, p_ppm)
+    # magnitudes in the fp16 subnormal range
+    x3 = (workload.activations(16, 1152, "robust-subnormal").astype(np.float32) * np.float32(2.0 ** -18)).astype(np.float16)
+    assert (np.abs(x3.astype(np.float32)) < 2.0 ** -14).mean() > 0.5
+    for R in (1, 16):
+        q_ref, s_ref = orc.daq_robust(x3, R, p_ppm=990000, a_bits=8)
+        q, s = gpu.daq_quantize_robust(dev(x3), R, p_ppm=990000, a_bits=8)
+        assert np.array_equal(host(s).view(np.uint32), s_ref.view(np.uint32)) and np.array_equal(host(q), q_ref)
     # p = 100 %, 8 bits: the absmax entry point's result
     x2 = workload.activations(64, 1152, "robust-absmax")
     q0, s0 = gpu.daq_quantize(dev(x2), 1)
