@@ -238,7 +238,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
                             u = bias ? __builtin_fmaf(t, sw, b) : t * sw;
                             if (a.acc_out) a.acc_out[off] = acc[i][j][r];
                         }
-                        y[off] = (_Float16)u;
+                        __builtin_nontemporal_store((_Float16)u, &y[off]);
                     }
                 }
         }
@@ -302,7 +302,8 @@ __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane
                 const int id = lane + 64 * t;
                 const int row = id / CH, ch = id % CH;
                 const v4i v = *reinterpret_cast<const v4i_alias *>(strip + row * PITCH + ch * 16);
-                *reinterpret_cast<v4i_alias *>(y + (unsigned)((m_base + i * 32 + row) * N + n_base + ch * 8)) = v;
+                // the output is written once and not read again by this kernel: keep it from displacing the operand panels in L2
+                __builtin_nontemporal_store(v, reinterpret_cast<v4i_alias *>(y + (unsigned)((m_base + i * 32 + row) * N + n_base + ch * 8)));
             }
             asm volatile("" ::: "memory");
         }
