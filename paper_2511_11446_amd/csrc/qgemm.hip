@@ -19,6 +19,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 // LDS staging is written as fp16 scalars and read back as 16-byte vectors: tell the compiler these may alias
 typedef _Float16 half_alias __attribute__((may_alias));
 typedef int v4i_alias __attribute__((ext_vector_type(4), may_alias));
+typedef float v4f __attribute__((ext_vector_type(4)));
 
 // Timing hook for kernel phase studies; expands to nothing in the library build.
 #ifndef QL_PHASE
@@ -287,7 +288,8 @@ __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane
                 typedef _Float16 h2 __attribute__((ext_vector_type(2)));
                 const h2 pr = {(_Float16)u0, (_Float16)u1};
                 const unsigned own = __builtin_bit_cast(unsigned, pr);
-                const unsigned nbr = (unsigned)__builtin_amdgcn_update_dpp(0, (int)own, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, false);
+                // every lane has a valid source, so no fill value is needed (the update form would first clear the destination)
+                const unsigned nbr = (unsigned)__builtin_amdgcn_mov_dpp((int)own, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true);
                 const unsigned word = __builtin_amdgcn_perm(nbr, own, sel);
                 const int row = 8 * (r / 4) + (r % 4);  // + 4*frag_half + odd, already in the lane's base
                 if (STAGED)
@@ -641,22 +643,36 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     const bool full = (m0 + BM <= M) && (n0 + BN <= N);
     if (full && (N % 8) == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0 && (W4 || !a.acc_out)) {
         unsigned char *strip = smem + T::STRIP_OFF + wave * T::STRIP_BYTES;
-        const float *sr = sRow + wm * TM * 32 + 4 * frag_half;
+        // the 16 row scales of each 32-row block of this lane (rows 8g + 4*frag_half + 0..3), read once as 4 x 16 bytes
+        float sr[TM * 16];
+        {
+            const float *srow = sRow + wm * TM * 32 + 4 * frag_half;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const v4f t = *reinterpret_cast<const v4f *>(srow + i * 32 + 8 * g);
+                    sr[i * 16 + 4 * g + 0] = t[0];
+                    sr[i * 16 + 4 * g + 1] = t[1];
+                    sr[i * 16 + 4 * g + 2] = t[2];
+                    sr[i * 16 + 4 * g + 3] = t[3];
+                }
+        }
         if (W4 && bias)
             store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, m0 + wm * TM * 32, n0 + wn * TN * 32, [&](int i, int j, int r) {
-                return __builtin_fmaf(fsum[W4 ? i : 0][W4 ? j : 0][r], sr[i * 32 + 8 * (r / 4) + (r % 4)], bj[j]);
+                return __builtin_fmaf(fsum[W4 ? i : 0][W4 ? j : 0][r], sr[i * 16 + r], bj[j]);
             });
         else if (W4)
             store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, m0 + wm * TM * 32, n0 + wn * TN * 32, [&](int i, int j, int r) {
-                return fsum[W4 ? i : 0][W4 ? j : 0][r] * sr[i * 32 + 8 * (r / 4) + (r % 4)];
+                return fsum[W4 ? i : 0][W4 ? j : 0][r] * sr[i * 16 + r];
             });
         else if (bias)
             store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, m0 + wm * TM * 32, n0 + wn * TN * 32, [&](int i, int j, int r) {
-                return __builtin_fmaf((float)acc[i][j][r] * sr[i * 32 + 8 * (r / 4) + (r % 4)], swt[j], bj[j]);
+                return __builtin_fmaf((float)acc[i][j][r] * sr[i * 16 + r], swt[j], bj[j]);
             });
         else
             store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, m0 + wm * TM * 32, n0 + wn * TN * 32, [&](int i, int j, int r) {
-                return (float)acc[i][j][r] * sr[i * 32 + 8 * (r / 4) + (r % 4)] * swt[j];
+                return (float)acc[i][j][r] * sr[i * 16 + r] * swt[j];
             });
     } else {
         auto emit = [&](auto edge) {
