@@ -72,15 +72,22 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
     float *sS = reinterpret_cast<float *>(sB + 2 * T::B_BYTES);
 
     // ---- which tile: spread consecutive logical tiles inside one XCD, walk GROUP_M tile rows at a time
+    // Workgroup ids go round-robin over the XCDs; each XCD owns per_xcd consecutive logical tiles and its resident
+    // workgroups take them in order, gridDim.x / XCDS at a time (all of them at once unless the launch is persistent).
     const int per_xcd = nblk_padded / XCDS;
-    const int logical = (blockIdx.x % XCDS) * per_xcd + blockIdx.x / XCDS;
-    if (logical >= tiles_m * tiles_n) return;
-    const int group_sz = group_m * tiles_n;
-    const int first_m = (logical / group_sz) * group_m;
-    const int gm = min(tiles_m - first_m, group_m);
-    const int tile_m = first_m + (logical % group_sz) % gm;
-    const int tile_n = (logical % group_sz) / gm;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int slots_per_xcd = gridDim.x / XCDS;
+    const int xcd_first = (blockIdx.x % XCDS) * per_xcd;
+    int in_xcd = blockIdx.x / XCDS;
+    if (in_xcd >= per_xcd || xcd_first + in_xcd >= tiles_m * tiles_n) return;
+    int m0, n0;
+    auto set_tile = [&](int logical) {
+        const int group_sz = group_m * tiles_n;
+        const int first_m = (logical / group_sz) * group_m;
+        const int gm = min(tiles_m - first_m, group_m);
+        m0 = (first_m + (logical % group_sz) % gm) * BM;
+        n0 = ((logical % group_sz) / gm) * BN;
+    };
+    set_tile(xcd_first + in_xcd);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / T::WGN, wn = wave % T::WGN;
@@ -323,7 +330,7 @@ __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane
 // the next quarter, the hand-over barrier and the next DMA issue all sit behind an MFMA that is
 // already executing.
 // ---------------------------------------------------------------------------------------------
-template <int TM_, int TN_, int WGM_, int WGN_, int S_, int WPS_, bool STG_ = true, int EV_ = 0, bool W4_ = false, int SB_ = S_>
+template <int TM_, int TN_, int WGM_, int WGN_, int S_, int WPS_, bool STG_ = true, int EV_ = 0, bool W4_ = false, int SB_ = S_, bool PERSIST_ = false>
 struct TileD {
     static constexpr int TM = TM_, TN = TN_, WGM = WGM_, WGN = WGN_, WPS = WPS_;
     // ring depth of the activation tile and of the weight tile (K steps resident or in flight); they may differ by one
@@ -346,6 +353,12 @@ struct TileD {
     static constexpr int SCALE_BYTES = W4 ? BN * MAX_GROUPS_K * 2 : 0;
     static constexpr int LDS_BYTES = RING_BYTES + SCALE_BYTES;
     static constexpr int SMAX = SA > SB ? SA : SB;
+    // Persistent launch: a workgroup walks several tiles and requests the first K step of the next tile before it
+    // starts the epilogue of the current one, into stage 0 of both rings; the epilogue's scratch then lives in the
+    // later stages of the activation ring.
+    static constexpr bool PERSIST = PERSIST_;
+    static constexpr int EPI_OFF = PERSIST ? A_BYTES : 0;
+    static_assert(!PERSIST || (!W4 && (SA - 1) * A_BYTES >= STRIP_OFF + NW * STRIP_BYTES), "epilogue scratch beside stage 0");
     // loads that may still be in flight when K step 0 is first read, and at the hand-over from step kt to kt+1
     static constexpr int WAIT_START = (SA - 1) * NA + (SB - 1) * NB;
     static constexpr int WAIT_HAND = SA > SB ? NA + (SB - 2) * (NA + NB) : SA < SB ? NB + (SA - 2) * (NA + NB) : (SA - 2) * (NA + NB);
@@ -365,15 +378,22 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     constexpr bool W4 = T::W4;
     extern __shared__ __align__(1024) unsigned char smem[];
 
+    // Workgroup ids go round-robin over the XCDs; each XCD owns per_xcd consecutive logical tiles and its resident
+    // workgroups take them in order, gridDim.x / XCDS at a time (all of them at once unless the launch is persistent).
     const int per_xcd = nblk_padded / XCDS;
-    const int logical = (blockIdx.x % XCDS) * per_xcd + blockIdx.x / XCDS;
-    if (logical >= tiles_m * tiles_n) return;
-    const int group_sz = group_m * tiles_n;
-    const int first_m = (logical / group_sz) * group_m;
-    const int gm = min(tiles_m - first_m, group_m);
-    const int tile_m = first_m + (logical % group_sz) % gm;
-    const int tile_n = (logical % group_sz) / gm;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int slots_per_xcd = gridDim.x / XCDS;
+    const int xcd_first = (blockIdx.x % XCDS) * per_xcd;
+    int in_xcd = blockIdx.x / XCDS;
+    if (in_xcd >= per_xcd || xcd_first + in_xcd >= tiles_m * tiles_n) return;
+    int m0, n0;
+    auto set_tile = [&](int logical) {
+        const int group_sz = group_m * tiles_n;
+        const int first_m = (logical / group_sz) * group_m;
+        const int gm = min(tiles_m - first_m, group_m);
+        m0 = (first_m + (logical % group_sz) % gm) * BM;
+        n0 = ((logical % group_sz) / gm) * BN;
+    };
+    set_tile(xcd_first + in_xcd);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it in a scalar register
@@ -386,9 +406,9 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     // return first, so the vmcnt bookkeeping of the ring is unaffected): the activation scale of one tile row per
     // thread, and the weight scale and bias of this lane's columns.
     static_assert(BM <= NT, "one row scale per thread");
-    const float sa_pre = tid < BM ? a.s_a[min(m0 + tid, M - 1) / a.R] : 0.0f;
-    float swt[TN], bj[TN];
-    {
+    float sa_pre, swt[TN], bj[TN];
+    auto load_scales = [&]() {
+        sa_pre = tid < BM ? a.s_a[min(m0 + tid, M - 1) / a.R] : 0.0f;
         const unsigned short *bias_h = static_cast<const unsigned short *>(a.bias);
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
@@ -396,7 +416,8 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
             swt[j] = W4 ? 1.0f : static_cast<const float *>(a.s_w)[n];
             bj[j] = bias_h ? half_to_float_dev(bias_h[n]) : 0.0f;
         }
-    }
+    };
+    if (!T::PERSIST) load_scales();
 
     // 4-bit weights: the fp16 group scales of this tile's columns, [BN][nk], copied once (the first barrier of the
     // pipeline below orders the copy before their first use at the end of K step 0)
@@ -411,25 +432,28 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     // Group g covers tile rows [8 g, 8 g + 8) of its operand.  Wavefront w takes groups w, w+NW, ... of both operands.
     constexpr int SA = T::SA, SB = T::SB, NA = T::NA, NB = T::NB;
     unsigned goffA[NA], goffB[NB];
+    auto set_goff = [&]() {
 #pragma unroll
-    for (int i = 0; i < NA; ++i) {
-        const int row = 8 * (wave + i * NW) + (lane >> 3);
-        const int c = (lane & 7) ^ ((row >> 1) & 7);
-        goffA[i] = (unsigned)(min(m0 + row, M - 1) * K + 16 * c);
-    }
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-        if (!W4) {
+        for (int i = 0; i < NA; ++i) {
             const int row = 8 * (wave + i * NW) + (lane >> 3);
             const int c = (lane & 7) ^ ((row >> 1) & 7);
-            goffB[i] = (unsigned)(min(n0 + row, N - 1) * K + 16 * c);
-        } else {
-            // packed 4-bit rows are 64 bytes per K step: 16 rows per group, chunk c of row r at slot c ^ ((r >> 2) & 3)
-            const int row = 16 * (wave + i * NW) + (lane >> 2);
-            const int c = (lane & 3) ^ ((row >> 2) & 3);
-            goffB[i] = (unsigned)(min(n0 + row, N - 1) * (K / 2) + 16 * c);
+            goffA[i] = (unsigned)(min(m0 + row, M - 1) * K + 16 * c);
         }
-    }
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            if (!W4) {
+                const int row = 8 * (wave + i * NW) + (lane >> 3);
+                const int c = (lane & 7) ^ ((row >> 1) & 7);
+                goffB[i] = (unsigned)(min(n0 + row, N - 1) * K + 16 * c);
+            } else {
+                // packed 4-bit rows are 64 bytes per K step: 16 rows per group, chunk c of row r at slot c ^ ((r >> 2) & 3)
+                const int row = 16 * (wave + i * NW) + (lane >> 2);
+                const int c = (lane & 3) ^ ((row >> 2) & 3);
+                goffB[i] = (unsigned)(min(n0 + row, N - 1) * (K / 2) + 16 * c);
+            }
+        }
+    };
+    set_goff();
     auto issue_a = [&](int kt, int slot, int i) {
         __builtin_amdgcn_global_load_lds((global_void *)(a.q + (size_t)kt * 128 + goffA[i]),
                                          (lds_void *)(smem + slot * T::A_BYTES + (wave + i * NW) * 1024), 16, 0, 0);
@@ -456,22 +480,19 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     };
 
     v16i acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
     // 4-bit weights: fp32 sum over the weight groups, f = sum_g fma(float(P_g), s_w[n,g], f)
     float fsum[W4 ? TM : 1][W4 ? TN : 1][16];
-    if (W4) {
+    auto clear_sums = [&]() {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) fsum[i][j][r] = 0.0f;
-    }
+                for (int r = 0; r < 16; ++r) {
+                    acc[i][j][r] = 0;
+                    if (W4) fsum[W4 ? i : 0][W4 ? j : 0][r] = 0.0f;
+                }
+    };
 
     // fragment of a lane: row (lane & 31) of a 32-row tile, 16 k starting at 32 * quarter + 16 * (lane >> 5)
     const int frag_row = lane & 31, frag_half = lane >> 5;
@@ -559,9 +580,24 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     constexpr int N_Q = (NMMA - 1) / EVERY;    // loads that fit behind the MFMAs of one quarter
     static_assert(!SPREAD || 3 * N_Q >= NA + NB, "the loads of a refill window must be issued within three quarters");
 
-    // prologue: the first SA activation tiles and SB weight tiles, in K-step order
+    // prologue: the first SA activation tiles and SB weight tiles, in K-step order.  A persistent workgroup requests
+    // step 0 ahead of everything else (for its first tile here, for later tiles before the previous epilogue).
+    auto issue_step0 = [&]() {
+        if (0 < nk) {
 #pragma unroll
-    for (int st = 0; st < T::SMAX; ++st) {
+            for (int i = 0; i < NA; ++i) issue_a(0, 0, i);
+#pragma unroll
+            for (int i = 0; i < NB; ++i) issue_b(0, 0, i);
+        }
+    };
+    if (T::PERSIST) issue_step0();
+    for (;;) {   // one pass per tile; a single pass unless the launch is persistent
+    if (T::PERSIST) load_scales();
+    clear_sums();
+    flush_group = -1;
+    if (!T::PERSIST) issue_step0();
+#pragma unroll
+    for (int st = 1; st < T::SMAX; ++st) {
         if (st < SA && st < nk) {
 #pragma unroll
             for (int i = 0; i < NA; ++i) issue_a(st, st, i);
@@ -634,15 +670,28 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     QL_PHASE(2)
     __syncthreads();
 
-    float *sRow = reinterpret_cast<float *>(smem);
+    // the tile being written out; a persistent workgroup moves on to its next tile first and requests that tile's
+    // first K step, so that it travels while the epilogue runs
+    const int em0 = m0, en0 = n0;
+    bool has_next = false;
+    if (T::PERSIST) {
+        in_xcd += slots_per_xcd;
+        has_next = in_xcd < per_xcd && xcd_first + in_xcd < tiles_m * tiles_n;
+        if (has_next) {
+            set_tile(xcd_first + in_xcd);
+            set_goff();
+            issue_step0();
+        }
+    }
+    float *sRow = reinterpret_cast<float *>(smem + T::EPI_OFF);
     if (tid < BM) sRow[tid] = sa_pre;
     __syncthreads();
     QL_PHASE(3)
     _Float16 *y = static_cast<_Float16 *>(a.y);
     const unsigned short *bias = static_cast<const unsigned short *>(a.bias);
-    const bool full = (m0 + BM <= M) && (n0 + BN <= N);
+    const bool full = (em0 + BM <= M) && (en0 + BN <= N);
     if (full && (N % 8) == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0 && (W4 || !a.acc_out)) {
-        unsigned char *strip = smem + T::STRIP_OFF + wave * T::STRIP_BYTES;
+        unsigned char *strip = smem + T::EPI_OFF + T::STRIP_OFF + wave * T::STRIP_BYTES;
         // the 16 row scales of each 32-row block of this lane (rows 8g + 4*frag_half + 0..3), read once as 4 x 16 bytes
         float sr[TM * 16];
         {
@@ -659,19 +708,19 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
                 }
         }
         if (W4 && bias)
-            store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, m0 + wm * TM * 32, n0 + wn * TN * 32, [&](int i, int j, int r) {
+            store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
                 return __builtin_fmaf(fsum[W4 ? i : 0][W4 ? j : 0][r], sr[i * 16 + r], bj[j]);
             });
         else if (W4)
-            store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, m0 + wm * TM * 32, n0 + wn * TN * 32, [&](int i, int j, int r) {
+            store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
                 return fsum[W4 ? i : 0][W4 ? j : 0][r] * sr[i * 16 + r];
             });
         else if (bias)
-            store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, m0 + wm * TM * 32, n0 + wn * TN * 32, [&](int i, int j, int r) {
+            store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
                 return __builtin_fmaf((float)acc[i][j][r] * sr[i * 16 + r], swt[j], bj[j]);
             });
         else
-            store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, m0 + wm * TM * 32, n0 + wn * TN * 32, [&](int i, int j, int r) {
+            store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
                 return (float)acc[i][j][r] * sr[i * 16 + r] * swt[j];
             });
     } else {
@@ -679,7 +728,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
             constexpr bool EDGE = decltype(edge)::value;
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                const int n = n0 + wn * TN * 32 + j * 32 + frag_row;
+                const int n = en0 + wn * TN * 32 + j * 32 + frag_row;
                 const bool n_ok = !EDGE || n < N;
                 const float b = bj[j];
 #pragma unroll
@@ -687,7 +736,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int row = wm * TM * 32 + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
-                        const int m = m0 + row;
+                        const int m = em0 + row;
                         if (!EDGE || (m < M && n_ok)) {
                             const unsigned off = (unsigned)(m * N + n);
                             float u;
@@ -709,6 +758,9 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
         else emit(std::true_type{});
     }
     QL_PHASE(4)
+    if (!has_next) break;
+    __syncthreads();   // the epilogue's scratch is free again: the rest of the next prologue may overwrite it
+    }
 }
 
 template <class T>
@@ -726,7 +778,22 @@ static hipError_t run_dma(const GemmArgs &a, hipStream_t s)
     const int tiles_m = (a.M + T::BM - 1) / T::BM, tiles_n = (a.N + T::BN - 1) / T::BN;
     const int nblk = tiles_m * tiles_n;
     const int padded = (nblk + XCDS - 1) / XCDS * XCDS;
-    hipLaunchKernelGGL(qgemm_dma<T>, dim3(padded), dim3(T::NT), T::LDS_BYTES, s, a, tiles_m, tiles_n, padded, pick_group_m(tiles_m, tiles_n));
+    int grid = padded;
+    if (T::PERSIST) {
+        // as many workgroups as the chip holds at once (LDS decides), a multiple of the XCD count
+        static int resident = 0;
+        if (!resident) {
+            int dev = 0, cus = 0;
+            hipError_t e = hipGetDevice(&dev);
+            if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+            if (e != hipSuccess) return e;
+            const int per_cu = 160 * 1024 / T::LDS_BYTES > 0 ? 160 * 1024 / T::LDS_BYTES : 1;
+            resident = cus / XCDS * XCDS * per_cu;
+            if (resident < XCDS) resident = XCDS;
+        }
+        if (grid > resident) grid = resident;
+    }
+    hipLaunchKernelGGL(qgemm_dma<T>, dim3(grid), dim3(T::NT), T::LDS_BYTES, s, a, tiles_m, tiles_n, padded, pick_group_m(tiles_m, tiles_n));
     return hipGetLastError();
 }
 
@@ -834,6 +901,10 @@ using D8_256x256_8w_a3b2 = TileD<4, 2, 2, 4, 3, 2, true, 1, false, 2>;
 using D8_128x128_a3b2 = TileD<2, 2, 2, 2, 3, 2, true, 0, false, 2>;
 using D8_128x128_a3b2_e1 = TileD<2, 2, 2, 2, 3, 2, true, 1, false, 2>;
 using D8_128x128_s2_e1 = TileD<2, 2, 2, 2, 2, 2, true, 1>;
+//                                                                               persistent
+using P8_256x192_a3b2 = TileD<2, 3, 4, 2, 3, 2, true, 1, false, 2, true>;
+using P8_256x256_a3b2 = TileD<4, 2, 2, 4, 3, 2, true, 1, false, 2, true>;
+using P8_128x128_a3b2 = TileD<2, 2, 2, 2, 3, 2, true, 1, false, 2, true>;
 
 static const Variant VARIANTS[] = {
     {"w8 dma 128x128 s3 4w", 8, 128, 128, 128, run_dma<D8_128x128_s3>},
@@ -857,6 +928,9 @@ static const Variant VARIANTS[] = {
     {"w8 dma 128x128 a3b2 4w", 8, 128, 128, 128, run_dma<D8_128x128_a3b2>},
     {"w8 dma 128x128 a3b2 4w spread1", 8, 128, 128, 128, run_dma<D8_128x128_a3b2_e1>},
     {"w8 dma 128x128 s2 4w spread1", 8, 128, 128, 128, run_dma<D8_128x128_s2_e1>},
+    {"w8 dma 256x192 a3b2 8w spread1 persistent", 8, 256, 192, 128, run_dma<P8_256x192_a3b2>},
+    {"w8 dma 256x256 a3b2 8w spread1 persistent", 8, 256, 256, 128, run_dma<P8_256x256_a3b2>},
+    {"w8 dma 128x128 a3b2 4w spread1 persistent", 8, 128, 128, 128, run_dma<P8_128x128_a3b2>},
     {"w8 128x128 bk64 4w occ2", 8, 128, 128, 64, run_variant<W8_128x128_k64>},
     {"w8 128x128 bk128 4w occ2", 8, 128, 128, 128, run_variant<W8_128x128_k128>},
     {"w8 256x128 bk64 4w occ2", 8, 256, 128, 64, run_variant<W8_256x128_k64>},
@@ -889,7 +963,8 @@ static int choose_variant(const GemmArgs &a)
     static const int w8_small = find_variant("w8 dma 64x64 s4 4w"),
                      w8_mid = find_variant("w8 dma 128x128 a3b2 4w spread1"),
                      w8_mid_deep = find_variant("w8 dma 128x128 a3b2 4w"),
-                     w8_big = find_variant("w8 dma 256x192 s2 8w spread1"),
+                     w8_mid_persist = find_variant("w8 dma 128x128 a3b2 4w spread1 persistent"),
+                     w8_big = find_variant("w8 dma 256x192 a3b2 8w spread1"),
                      w8_big_b3 = find_variant("w8 dma 256x192 a2b3 8w spread1"),
                      w8_wide = find_variant("w8 dma 256x256 s2 8w spread2"),
                      w8_k64 = find_variant("w8 128x128 bk64 4w occ3"), w4_any = find_variant("w4 128x64 bk128 4w occ3");
@@ -898,8 +973,11 @@ static int choose_variant(const GemmArgs &a)
     if (a.M <= 512) return w8_small;
     const long tiles_big = (long)((a.M + 255) / 256) * ((a.N + 191) / 192);
     if (tiles_big >= 192) {                                   // at least 3/4 of the CUs get a 256x192 tile
-        if (a.N <= 1536 || a.K >= 2304) return w8_big_b3;     // few tile columns or a long K loop: a third weight stage pays
+        if (a.K >= 2304) return w8_big_b3;                    // a long K loop: a third weight stage pays
         if (a.N % 256 == 0 && a.N >= 4096 && a.M >= 8192) return w8_wide;
+        // several tiles per CU: two resident 128x128 workgroups per CU that walk their tiles and fetch the next
+        // tile's first K step under the epilogue
+        if (a.M >= 4096) return w8_mid_persist;
         return w8_big;
     }
     return a.K >= 2304 ? w8_mid_deep : w8_mid;
