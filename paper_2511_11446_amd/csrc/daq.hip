@@ -21,8 +21,8 @@ __device__ __forceinline__ void publish_block_max(unsigned *slot, unsigned bits)
 
 constexpr int ROWS_PER_BLOCK = 4;  // 4 wavefronts, one row each (loop kernels)
 
-// Rows held in registers: CH 16-byte chunks per lane and row (K/8 <= 64*CH), RW rows per wavefront.  All loads of
-// the RW rows are issued before the first reduction, so that enough bytes are in flight to cover the HBM latency.
+// Rows held in registers: CH 16-byte chunks per lane and row (K/8 <= 64*CH), RW rows per wavefront (all loads of the
+// RW rows are issued before the first reduction).  The dispatcher uses RW = 1: see run_rows().
 template <int CH, int RW>
 __global__ __launch_bounds__(256) void daq_rows_cached(DaqArgs a, int mode)
 {
@@ -203,14 +203,15 @@ static void run_rows(const DaqArgs &a, int mode, hipStream_t s)
         hipLaunchKernelGGL(daq_rows_loop<1>, grid, dim3(256), 0, s, a, mode);
         return;
     }
+    // one row per wavefront at every size: with the division-free codes the kernel is no longer VALU-bound, and more,
+    // shorter wavefronts beat several rows per wavefront (measured 4.5 against 3.4 TB/s at M = 16384, K = 1152)
     const int per_lane = (a.K / 8 + 63) / 64;
-    const bool many = a.M >= 8192;   // enough rows to give every wavefront several
-    if (per_lane <= 1) many ? run_cached<1, 4>(a, mode, s) : run_cached<1, 1>(a, mode, s);
-    else if (per_lane <= 2) many ? run_cached<2, 4>(a, mode, s) : run_cached<2, 1>(a, mode, s);
-    else if (per_lane <= 3) many ? run_cached<3, 4>(a, mode, s) : run_cached<3, 1>(a, mode, s);
-    else if (per_lane <= 4) many ? run_cached<4, 2>(a, mode, s) : run_cached<4, 1>(a, mode, s);
-    else if (per_lane <= 6) many ? run_cached<6, 2>(a, mode, s) : run_cached<6, 1>(a, mode, s);
-    else if (per_lane <= 9) many ? run_cached<9, 2>(a, mode, s) : run_cached<9, 1>(a, mode, s);
+    if (per_lane <= 1) run_cached<1, 1>(a, mode, s);
+    else if (per_lane <= 2) run_cached<2, 1>(a, mode, s);
+    else if (per_lane <= 3) run_cached<3, 1>(a, mode, s);
+    else if (per_lane <= 4) run_cached<4, 1>(a, mode, s);
+    else if (per_lane <= 6) run_cached<6, 1>(a, mode, s);
+    else if (per_lane <= 9) run_cached<9, 1>(a, mode, s);
     else if (per_lane <= 12) run_cached<12, 1>(a, mode, s);
     else if (per_lane <= 16) run_cached<16, 1>(a, mode, s);
     else hipLaunchKernelGGL(daq_rows_loop<8>, grid, dim3(256), 0, s, a, mode);
