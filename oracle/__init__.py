@@ -175,6 +175,21 @@ def gemm_w4g128(q, w4, nthreads=1):
     return P
 
 
+def gemm_w4g(q, w4, group, nthreads=1):
+    """q [M,K] int8, w4 packed [N,K/2] -> P int32 [M,K/group,N] (weight groups of `group` consecutive k)."""
+    q = _c(q, np.int8)
+    w4 = _c(w4, np.uint8)
+    M, K = q.shape
+    N = w4.shape[0]
+    assert w4.shape[1] * 2 == K and K % group == 0
+    P = np.empty((M, K // group, N), np.int32)
+    rc = lib().orc_gemm_w4g(_p(q), _p(w4), ctypes.c_int64(M), ctypes.c_int64(N), ctypes.c_int64(K), ctypes.c_int64(group),
+                            _p(P), ctypes.c_int(nthreads))
+    if rc:
+        raise ValueError("orc_gemm_w4g rc=%d" % rc)
+    return P
+
+
 def epilogue_w8(acc, s_a, R, s_w, bias):
     """-> y float16 [M,N]."""
     acc = _c(acc, np.int32)

@@ -281,6 +281,37 @@ int orc_gemm_w4g128(const int8_t *q, const uint8_t *w4, int64_t M, int64_t N, in
 }
 
 /* ------------------------------------------------------------------ */
+/* The same with weight groups of `group` consecutive k (Step 2 and    */
+/* Algorithm 1 choose the group size per layer; the final plan of      */
+/* Section 6 uses 64, 128, 192 and 288):                               */
+/*   P[m,g,n] = sum_{k in [group*g, group*g+group)} q[m,k] * w4[n,k]   */
+/*   P is [M, K/group, N];  K % group == 0                             */
+/* ------------------------------------------------------------------ */
+int orc_gemm_w4g(const int8_t *q, const uint8_t *w4, int64_t M, int64_t N, int64_t K, int64_t group,
+                 int32_t *P, int nthreads)
+{
+    if (M < 0 || N < 0 || K < 0 || group <= 0 || (K % group) != 0 || (K % 8) != 0) return 1;
+    int64_t G = K / group;
+    (void)nthreads;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) num_threads(nthreads > 1 ? nthreads : 1)
+#endif
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n)
+            for (int64_t g = 0; g < G; ++g) {
+                int32_t s = 0;
+                for (int64_t k = group * g; k < group * g + group; ++k) {
+                    uint8_t byte = w4[n * (K / 2) + w4_byte_of(k)];
+                    int v = w4_is_high(k) ? (byte >> 4) : (byte & 0xF);
+                    if (v >= 8) v -= 16;
+                    s += (int32_t)q[m * K + k] * v;
+                }
+                P[(m * G + g) * N + n] = s;
+            }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
 /* Dequantization epilogues (Section 6: "dequantization"; Step 5:      */
 /* per-output-channel weight scales).  binary32, one rounding per      */
 /* operation, in the order written; fma = fused multiply-add.          */

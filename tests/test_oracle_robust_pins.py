@@ -115,3 +115,51 @@ def test_bad_arguments_are_refused(orc):
     for kw in (dict(p_ppm=0), dict(p_ppm=1000001), dict(a_bits=1), dict(a_bits=9)):
         with pytest.raises(ValueError):
             orc.daq_robust(x, 1, **kw)
+
+
+# ---------------------------------------------------------------- weight groups of other sizes (Step 2, Algorithm 1)
+
+def _w4_case(M, K, N, seed):
+    g = workload.rng("w4g-pin", seed)
+    q = g.integers(-127, 128, size=(M, K), dtype=np.int8)
+    w = g.integers(-8, 8, size=(N, K), dtype=np.int8)
+    return q, w
+
+
+@pytest.mark.parametrize("group", [32, 64, 96, 128, 192, 288])
+def test_grouped_partials_against_numpy_block_sums(orc, group):
+    M, K, N = 5, 576, 7
+    q, w = _w4_case(M, K, N, group)
+    P = orc.gemm_w4g(q, orc.pack_w4(w), group)
+    G = K // group
+    want = np.einsum("mgk,ngk->mgn", q.reshape(M, G, group).astype(np.int64), w.reshape(N, G, group).astype(np.int64))
+    assert np.array_equal(P, want.astype(np.int32))
+    # the groups partition K: their sum is the plain int8 product of the same codes
+    assert np.array_equal(P.sum(axis=1), orc.gemm_i8(q, w))
+
+
+def test_group128_is_the_fixed_group_function_and_one_hot_group_membership(orc):
+    q, w = _w4_case(4, 256, 6, "g128")
+    assert np.array_equal(orc.gemm_w4g(q, orc.pack_w4(w), 128), orc.gemm_w4g128(q, orc.pack_w4(w)))
+    # a single non-zero weight at k lands in group k // group only
+    for group, k in ((32, 95), (64, 64), (192, 191), (288, 288)):
+        K = 576
+        w1 = np.zeros((1, K), np.int8)
+        w1[0, k] = -8
+        q1 = np.full((1, K), 3, np.int8)
+        P = orc.gemm_w4g(q1, orc.pack_w4(w1), group)
+        want = np.zeros((1, K // group, 1), np.int32)
+        want[0, k // group, 0] = -24
+        assert np.array_equal(P, want)
+
+
+def test_grouped_epilogue_with_equal_power_of_two_scales_equals_the_per_channel_path(orc):
+    M, K, N, group = 6, 576, 5, 192
+    q, w = _w4_case(M, K, N, "epi")
+    s_a = np.full((M,), 0.5, np.float32)
+    P = orc.gemm_w4g(q, orc.pack_w4(w), group)
+    sw = np.full((N, K // group), 0.25, np.float16)
+    bias = np.zeros((N,), np.float16)
+    y4 = orc.epilogue_w4(P, s_a, 1, sw, bias)
+    y8 = orc.epilogue_w8(orc.gemm_i8(q, w), s_a, 1, np.full((N,), 0.25, np.float32), bias)
+    assert np.array_equal(y4.view(np.uint16), y8.view(np.uint16))
