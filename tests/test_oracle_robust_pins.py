@@ -128,7 +128,7 @@ def _w4_case(M, K, N, seed):
 
 @pytest.mark.parametrize("group", [32, 64, 96, 128, 192, 288])
 def test_grouped_partials_against_numpy_block_sums(orc, group):
-    M, K, N = 5, 576, 7
+    M, K, N = 5, 1152, 7
     q, w = _w4_case(M, K, N, group)
     P = orc.gemm_w4g(q, orc.pack_w4(w), group)
     G = K // group
