@@ -22,7 +22,8 @@
  *     (so that K * 127 * 127 fits an int32); M % R == 0.
  *     The fast (MFMA) kernels need K % 16 == 0 and 16-byte aligned x, q, w;
  *     other shapes or alignments are served by slower generic kernels with the
- *     same results.  4-bit weights need K % 128 == 0.
+ *     same results.  4-bit weights need K % group == 0 (group = 128 unless the
+ *     call takes one) and K % 8 == 0.
  */
 #ifndef DIFFPRO_QLINEAR_H
 #define DIFFPRO_QLINEAR_H
@@ -39,7 +40,7 @@ typedef enum ql_status {
     QL_ERR_NULL = 1,        /* a required pointer is NULL */
     QL_ERR_SHAPE = 2,       /* a size is out of the limits above */
     QL_ERR_ALIGN = 3,       /* workspace not 256-byte aligned, or a 2/4-byte typed pointer misaligned */
-    QL_ERR_UNSUPPORTED = 4, /* w_bits not in {4,8} or group not in {0,128} */
+    QL_ERR_UNSUPPORTED = 4, /* w_bits not in {4,8}, group not 0 (8-bit) / not a multiple of 32 (4-bit), DAQ parameters out of range */
     QL_ERR_WORKSPACE = 5,   /* workspace missing or too small */
     QL_ERR_DEVICE = 6       /* a HIP call failed; see ql_last_device_error() */
 } ql_status;
@@ -96,8 +97,9 @@ size_t qlinear_workspace_bytes(int64_t M, int64_t K, int64_t R);
  * Section 6 counts DAQ, requantization and dequantization in the latency):
  *   q, alpha = DAQ(x, R)
  *   acc[m,n] = sum_k q[m,k] * w[n,k]                       (int32)
- *   y[m,n]   = fp16( float(acc) * alpha[m/R] * w_scale[n] + bias[n] )
- * evaluated in fp32, left to right, round-to-nearest-even into fp16.
+ *   t        = float(acc) * alpha[m/R]                      (fp32)
+ *   y[m,n]   = fp16( fma(t, w_scale[n], bias[n]) )          (t * w_scale[n] without a bias)
+ * one fp32 rounding per operation, then round-to-nearest-even into fp16.
  *   x        (device) [M,K] fp16
  *   w        (device) [N,K] int8 codes in [-127,127], K contiguous
  *   w_scale  (device) [N] fp32
@@ -113,8 +115,8 @@ int qlinear_w8a8(const void *x, int64_t M, int64_t K, int64_t R,
  * Quantized linear with 4-bit group-128 weights (Step 2: integer weights with
  * per-group scales; symmetric, zero-point 0, as in the ablation section):
  *   P[m,g,n] = sum_{k in group g} q[m,k] * w4[n,k]          (int32, g = k/128)
- *   f        = sum_g float(P[m,g,n]) * w_scale[n,g]         (fp32, g ascending)
- *   y[m,n]   = fp16( f * alpha[m/R] + bias[n] )
+ *   f        = fma(float(P[m,g,n]), w_scale[n,g], f)        (fp32, g ascending, f starts at 0)
+ *   y[m,n]   = fp16( fma(f, alpha[m/R], bias[n]) )          (f * alpha[m/R] without a bias)
  *   w4       (device) [N, K/2] bytes, two's-complement nibbles in [-8,7].
  *            Storage order: inside every run of 8 consecutive k (4 bytes),
  *            byte j (0..3) holds k = 8b+j in its low nibble and k = 8b+4+j in
@@ -141,6 +143,21 @@ int qgemm_w4a8(const void *q, const void *a_scales, int64_t M, int64_t K, int64_
                const void *w4, const void *w_scale, const void *bias, int64_t N,
                void *y, void *acc, void *stream);
 
+/* The 4-bit layer with weight groups of `group` consecutive k per scale instead
+ * of 128 (Step 2 and Algorithm 1 choose the group size per layer; the final plan
+ * of Section 6 uses 64, 128, 192 and 288).  group: a multiple of 32
+ * (else QL_ERR_UNSUPPORTED) that divides K (else QL_ERR_SHAPE).
+ *   w_scale (device) fp16 [N, K/group];  dbg->acc, acc: int32 [M, K/group, N]
+ *   f = sum over groups g ascending of fma(float(P[m,g,n]), w_scale[n,g], f)
+ * Everything else as qlinear_w4a8 / qgemm_w4a8 (group = 128 gives their result). */
+int qlinear_w4a8_g(const void *x, int64_t M, int64_t K, int64_t R,
+                   const void *w4, const void *w_scale, int64_t group, const void *bias, int64_t N,
+                   void *y, const ql_debug *dbg,
+                   void *workspace, size_t workspace_bytes, void *stream);
+int qgemm_w4a8_g(const void *q, const void *a_scales, int64_t M, int64_t K, int64_t R,
+                 const void *w4, const void *w_scale, int64_t group, const void *bias, int64_t N,
+                 void *y, void *acc, void *stream);
+
 /* Host helper: pack int8 codes in [-8,7], [N,K] row-major (host), into the
  * 4-bit storage order described at qlinear_w4a8 ([N,K/2] bytes, host).
  * K % 8 == 0.  Returns QL_ERR_SHAPE for a code outside [-8,7]. */
@@ -157,9 +174,9 @@ typedef struct ql_layer_desc {
     int64_t K;            /* input features */
     int64_t N;            /* output features */
     int32_t w_bits;       /* 8 or 4 */
-    int32_t group;        /* 0 = one scale per output channel (8-bit); 128 (4-bit) */
+    int32_t group;        /* 0 = one scale per output channel (8-bit); 4-bit: k per scale, a multiple of 32 dividing K */
     const void *w;        /* (device) int8 [N,K] or packed 4-bit [N,K/2] */
-    const void *w_scale;  /* (device) fp32 [N] (8-bit) or fp16 [N,K/128] (4-bit) */
+    const void *w_scale;  /* (device) fp32 [N] (8-bit) or fp16 [N,K/group] (4-bit) */
     const void *bias;     /* (device) fp16 [N] or NULL */
 } ql_layer_desc;
 

@@ -21,7 +21,8 @@ EXPORTS = ("ql_status_string", "ql_last_device_error", "ql_version", "daq_worksp
            "qlinear_workspace_bytes", "qlinear_w8a8", "qlinear_w4a8", "qgemm_w8a8", "qgemm_w4a8",
            "ql_pack_w4_host", "ql_plan_create", "ql_plan_destroy", "ql_plan_num_layers",
            "ql_plan_workspace_bytes", "qlinear_plan_run", "ql_set_gemm_variant", "ql_num_gemm_variants",
-           "ql_gemm_variant_name", "ql_probe_mfma_int8", "daq_quantize_robust", "qlinear_plan_run_robust", "ql_time_bin")
+           "ql_gemm_variant_name", "ql_probe_mfma_int8", "daq_quantize_robust", "qlinear_plan_run_robust", "ql_time_bin",
+           "qlinear_w4a8_g", "qgemm_w4a8_g")
 
 
 class QlError(RuntimeError):
@@ -86,6 +87,10 @@ def lib():
     L.ql_plan_workspace_bytes.argtypes = [_vp, _i64, _i64]
     L.ql_plan_workspace_bytes.restype = _sz
     L.qlinear_plan_run.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _i64, _i64, _vp, _sz, _vp]
+    L.qlinear_w4a8_g.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp, ctypes.POINTER(ql_debug), _vp, _sz, _vp]
+    L.qlinear_w4a8_g.restype = _int
+    L.qgemm_w4a8_g.argtypes = [_vp, _vp, _i64, _i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp, _vp, _vp]
+    L.qgemm_w4a8_g.restype = _int
     L.qlinear_plan_run_robust.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _i64, _i64, _vp, _vp, _sz, _vp]
     L.qlinear_plan_run_robust.restype = _int
     L.daq_quantize_robust.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -179,7 +184,7 @@ def time_bin(step, num_steps):
     return int(lib().ql_time_bin(step, num_steps))
 
 
-def _qlinear(fn_name, x, R, w, w_scale, bias, N, y, debug, ws, stream):
+def _qlinear(fn_name, x, R, w, w_scale, bias, N, y, debug, ws, stream, group=128):
     import torch
     _need(x, torch.float16, name="x")
     M, K = x.shape
@@ -190,14 +195,19 @@ def _qlinear(fn_name, x, R, w, w_scale, bias, N, y, debug, ws, stream):
     dbg = None
     out = {"y": y}
     if debug:
-        G = K // 128
+        G = K // group
         out["q"] = torch.empty((M, K), dtype=torch.int8, device=x.device)
         out["s_a"] = torch.empty((M // R,), dtype=torch.float32, device=x.device)
         shape = (M, N) if fn_name == "qlinear_w8a8" else (M, G, N)
         out["acc" if fn_name == "qlinear_w8a8" else "P"] = acc = torch.empty(shape, dtype=torch.int32, device=x.device)
         dbg = ctypes.pointer(ql_debug(out["q"].data_ptr(), out["s_a"].data_ptr(), acc.data_ptr()))
-    rc = getattr(lib(), fn_name)(_ptr(x), M, K, R, _ptr(w), _ptr(w_scale), _ptr(bias), N, _ptr(y), dbg, _ptr(ws),
-                                 ws.numel(), _stream(stream))
+    if fn_name == "qlinear_w4a8" and group != 128:
+        fn_name = "qlinear_w4a8_g"
+        rc = lib().qlinear_w4a8_g(_ptr(x), M, K, R, _ptr(w), _ptr(w_scale), group, _ptr(bias), N, _ptr(y), dbg, _ptr(ws),
+                                  ws.numel(), _stream(stream))
+    else:
+        rc = getattr(lib(), fn_name)(_ptr(x), M, K, R, _ptr(w), _ptr(w_scale), _ptr(bias), N, _ptr(y), dbg, _ptr(ws),
+                                     ws.numel(), _stream(stream))
     _check(rc, fn_name)
     return out if debug else y
 
@@ -214,17 +224,17 @@ def qlinear_w8a8(x, R, w, w_scale, bias=None, y=None, debug=False, ws=None, stre
     return _qlinear("qlinear_w8a8", x, R, w, w_scale, bias, w.shape[0], y, debug, ws, stream)
 
 
-def qlinear_w4a8(x, R, w4, w_scale, bias=None, y=None, debug=False, ws=None, stream=None):
-    """Same with packed 4-bit weights: w4 uint8 [N,K/2], w_scale fp16 [N,K/128]."""
+def qlinear_w4a8(x, R, w4, w_scale, bias=None, y=None, debug=False, ws=None, stream=None, group=128):
+    """Same with packed 4-bit weights: w4 uint8 [N,K/2], w_scale fp16 [N,K/group]."""
     import torch
     _need(w4, torch.uint8, name="w4")
     K = x.shape[1]
     if w4.shape[1] * 2 != K:
         raise ValueError("w4 must be [N,K/2]")
-    _need(w_scale, torch.float16, (w4.shape[0], K // 128), "w_scale")
+    _need(w_scale, torch.float16, (w4.shape[0], K // group), "w_scale")
     if bias is not None:
         _need(bias, torch.float16, (w4.shape[0],), "bias")
-    return _qlinear("qlinear_w4a8", x, R, w4, w_scale, bias, w4.shape[0], y, debug, ws, stream)
+    return _qlinear("qlinear_w4a8", x, R, w4, w_scale, bias, w4.shape[0], y, debug, ws, stream, group)
 
 
 def _qgemm(fn_name, q, a_scales, R, w, w_scale, bias, N, y, acc, stream):
@@ -244,8 +254,18 @@ def qgemm_w8a8(q, a_scales, R, w, w_scale, bias=None, y=None, acc=None, stream=N
     return _qgemm("qgemm_w8a8", q, a_scales, R, w, w_scale, bias, w.shape[0], y, acc, stream)
 
 
-def qgemm_w4a8(q, a_scales, R, w4, w_scale, bias=None, y=None, acc=None, stream=None):
-    return _qgemm("qgemm_w4a8", q, a_scales, R, w4, w_scale, bias, w4.shape[0], y, acc, stream)
+def qgemm_w4a8(q, a_scales, R, w4, w_scale, bias=None, y=None, acc=None, stream=None, group=128):
+    if group == 128:
+        return _qgemm("qgemm_w4a8", q, a_scales, R, w4, w_scale, bias, w4.shape[0], y, acc, stream)
+    import torch
+    M, K = q.shape
+    N = w4.shape[0]
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=q.device)
+    rc = lib().qgemm_w4a8_g(_ptr(q), _ptr(a_scales), M, K, R, _ptr(w4), _ptr(w_scale), group, _ptr(bias), N, _ptr(y),
+                            _ptr(acc), _stream(stream))
+    _check(rc, "qgemm_w4a8_g")
+    return y
 
 
 def ql_pack_w4_host(codes):
@@ -260,13 +280,14 @@ def ql_pack_w4_host(codes):
 
 
 class Plan:
-    """A per-layer weight-bit plan (Algorithm 2, Phase B): list of dicts(K, N, bits, w, w_scale, bias) of CUDA tensors."""
+    """A per-layer weight-bit plan (Algorithm 2, Phase B): list of dicts(K, N, bits, w, w_scale, bias[, group]) of CUDA
+    tensors; group = k per weight scale of a 4-bit layer (default 128)."""
 
     def __init__(self, layers, M_max):
         self._keep = layers  # the plan stores raw pointers: keep the tensors alive
         arr = (ql_layer_desc * len(layers))()
         for i, l in enumerate(layers):
-            arr[i] = ql_layer_desc(l["K"], l["N"], l["bits"], 128 if l["bits"] == 4 else 0, l["w"].data_ptr(),
+            arr[i] = ql_layer_desc(l["K"], l["N"], l["bits"], l.get("group", 128) if l["bits"] == 4 else 0, l["w"].data_ptr(),
                                    l["w_scale"].data_ptr(), 0 if l.get("bias") is None else l["bias"].data_ptr())
         h = _vp()
         _check(lib().ql_plan_create(arr, len(layers), M_max, ctypes.byref(h)), "ql_plan_create")

@@ -84,10 +84,18 @@ int check_workspace(void *ws, size_t have, size_t need)
     return QL_OK;
 }
 
+// 4-bit weight groups: a multiple of 32 that divides K (Step 2 / Algorithm 1 choose the size per layer)
+int check_group(int64_t K, int64_t group)
+{
+    if (group < 32 || group % 32 != 0) return QL_ERR_UNSUPPORTED;
+    if (K % group != 0 || K % 8 != 0) return QL_ERR_SHAPE;
+    return QL_OK;
+}
+
 // DAQ then GEMM for one layer; all arguments already validated
 int run_layer(const void *x, int64_t M, int64_t K, int64_t R, int w_bits, const void *w, const void *w_scale,
               const void *bias, int64_t N, void *y, const ql_debug *dbg, void *workspace, hipStream_t stream,
-              const ql_daq_params *dp = nullptr)
+              const ql_daq_params *dp = nullptr, int64_t group = 128)
 {
     const LayerWs lw = layer_ws(M, K, R);
     unsigned char *base = static_cast<unsigned char *>(workspace);
@@ -123,6 +131,7 @@ int run_layer(const void *x, int64_t M, int64_t K, int64_t R, int w_bits, const 
     g.K = (int)K;
     g.R = (int)R;
     g.w_bits = w_bits;
+    g.group = (int)group;
     return device_status(ql::launch_qgemm(g, g_gemm_variant.load(), stream));
 }
 
@@ -138,21 +147,25 @@ int check_layer_ptrs(const void *x, const void *w, const void *w_scale, const vo
 
 int qlinear_any(int w_bits, const void *x, int64_t M, int64_t K, int64_t R, const void *w, const void *w_scale,
                 const void *bias, int64_t N, void *y, const ql_debug *dbg, void *workspace, size_t workspace_bytes,
-                void *stream)
+                void *stream, int64_t group = 128)
 {
     int rc = check_layer_ptrs(x, w, w_scale, bias, y, dbg, w_bits);
     if (rc) return rc;
     rc = check_shape(M, K, R, N);
     if (rc) return rc;
-    if (w_bits == 4 && K % 128 != 0) return QL_ERR_SHAPE;
-    if (w_bits == 4 && M > ELEMS_MAX / N / (K / 128) && dbg && dbg->acc) return QL_ERR_SHAPE;
+    if (w_bits == 4) {
+        rc = check_group(K, group);
+        if (rc) return rc;
+        if (M > ELEMS_MAX / N / (K / group) && dbg && dbg->acc) return QL_ERR_SHAPE;
+    }
     rc = check_workspace(workspace, workspace_bytes, layer_ws(M, K, R).total);
     if (rc) return rc;
-    return run_layer(x, M, K, R, w_bits, w, w_scale, bias, N, y, dbg, workspace, static_cast<hipStream_t>(stream));
+    return run_layer(x, M, K, R, w_bits, w, w_scale, bias, N, y, dbg, workspace, static_cast<hipStream_t>(stream), nullptr,
+                     group);
 }
 
 int qgemm_any(int w_bits, const void *q, const void *a_scales, int64_t M, int64_t K, int64_t R, const void *w,
-              const void *w_scale, const void *bias, int64_t N, void *y, void *acc, void *stream)
+              const void *w_scale, const void *bias, int64_t N, void *y, void *acc, void *stream, int64_t group = 128)
 {
     if (!q || !a_scales || !w || !w_scale || !y) return QL_ERR_NULL;
     if (misaligned(a_scales, 4) || misaligned(y, 2) || misaligned(bias, 2) || misaligned(acc, 4) ||
@@ -160,8 +173,11 @@ int qgemm_any(int w_bits, const void *q, const void *a_scales, int64_t M, int64_
         return QL_ERR_ALIGN;
     int rc = check_shape(M, K, R, N);
     if (rc) return rc;
-    if (w_bits == 4 && K % 128 != 0) return QL_ERR_SHAPE;
-    if (w_bits == 4 && acc && M > ELEMS_MAX / N / (K / 128)) return QL_ERR_SHAPE;
+    if (w_bits == 4) {
+        rc = check_group(K, group);
+        if (rc) return rc;
+        if (acc && M > ELEMS_MAX / N / (K / group)) return QL_ERR_SHAPE;
+    }
     ql::GemmArgs g;
     g.q = static_cast<const int8_t *>(q);
     g.s_a = static_cast<const float *>(a_scales);
@@ -175,6 +191,7 @@ int qgemm_any(int w_bits, const void *q, const void *a_scales, int64_t M, int64_
     g.K = (int)K;
     g.R = (int)R;
     g.w_bits = w_bits;
+    g.group = (int)group;
     return device_status(ql::launch_qgemm(g, g_gemm_variant.load(), static_cast<hipStream_t>(stream)));
 }
 
@@ -278,6 +295,19 @@ int qlinear_w4a8(const void *x, int64_t M, int64_t K, int64_t R, const void *w4,
     return qlinear_any(4, x, M, K, R, w4, w_scale, bias, N, y, dbg, workspace, workspace_bytes, stream);
 }
 
+int qlinear_w4a8_g(const void *x, int64_t M, int64_t K, int64_t R, const void *w4, const void *w_scale, int64_t group,
+                   const void *bias, int64_t N, void *y, const ql_debug *dbg, void *workspace, size_t workspace_bytes,
+                   void *stream)
+{
+    return qlinear_any(4, x, M, K, R, w4, w_scale, bias, N, y, dbg, workspace, workspace_bytes, stream, group);
+}
+
+int qgemm_w4a8_g(const void *q, const void *a_scales, int64_t M, int64_t K, int64_t R, const void *w4,
+                 const void *w_scale, int64_t group, const void *bias, int64_t N, void *y, void *acc, void *stream)
+{
+    return qgemm_any(4, q, a_scales, M, K, R, w4, w_scale, bias, N, y, acc, stream, group);
+}
+
 int qgemm_w8a8(const void *q, const void *a_scales, int64_t M, int64_t K, int64_t R, const void *w,
                const void *w_scale, const void *bias, int64_t N, void *y, void *acc, void *stream)
 {
@@ -316,11 +346,14 @@ int ql_plan_create(const ql_layer_desc *layers, int32_t n_layers, int64_t M_max,
     for (int32_t l = 0; l < n_layers; ++l) {
         const ql_layer_desc &d = layers[l];
         if (d.w_bits != 8 && d.w_bits != 4) return QL_ERR_UNSUPPORTED;
-        if ((d.w_bits == 8 && d.group != 0) || (d.w_bits == 4 && d.group != 128)) return QL_ERR_UNSUPPORTED;
+        if (d.w_bits == 8 && d.group != 0) return QL_ERR_UNSUPPORTED;
         if (!d.w || !d.w_scale) return QL_ERR_NULL;
         int rc = check_shape(M_max, d.K, 1, d.N);
         if (rc) return rc;
-        if (d.w_bits == 4 && d.K % 128 != 0) return QL_ERR_SHAPE;
+        if (d.w_bits == 4) {
+            rc = check_group(d.K, d.group);
+            if (rc) return rc;
+        }
         if (misaligned(d.w_scale, d.w_bits == 8 ? 4 : 2) || misaligned(d.bias, 2)) return QL_ERR_ALIGN;
         widest = d.K > widest ? d.K : widest;
     }
@@ -358,7 +391,8 @@ static int plan_run_any(const ql_plan *plan, const void *const *x_in, void *cons
     hipStream_t s = static_cast<hipStream_t>(stream);
     for (size_t l = 0; l < plan->layers.size(); ++l) {
         const ql_layer_desc &d = plan->layers[l];
-        rc = run_layer(x_in[l], M, d.K, R, d.w_bits, d.w, d.w_scale, d.bias, d.N, y_out[l], nullptr, workspace, s, dp);
+        rc = run_layer(x_in[l], M, d.K, R, d.w_bits, d.w, d.w_scale, d.bias, d.N, y_out[l], nullptr, workspace, s, dp,
+                       d.w_bits == 4 ? d.group : 128);
         if (rc) return rc;
     }
     return QL_OK;

@@ -39,10 +39,12 @@ __device__ __forceinline__ float half_to_float_dev(unsigned short h)
 // Tile shape: a workgroup of WGM x WGN wavefronts, each owning TM x TN MFMA
 // tiles of 32x32, walks K in steps of BK int8.
 // WPS = wavefronts per SIMD the register budget must allow (512 / WPS registers per lane).
-template <int TM_, int TN_, int WGM_, int WGN_, int BK_, bool W4_, int WPS_>
+template <int TM_, int TN_, int WGM_, int WGN_, int BK_, bool W4_, int WPS_, bool GG_ = false>
 struct Tile {
     static constexpr int TM = TM_, TN = TN_, WGM = WGM_, WGN = WGN_, BK = BK_, WPS = WPS_;
     static constexpr bool W4 = W4_;
+    // 4-bit weights with a group size other than 128: any multiple of 32 that divides K (groups end at 32-wide K slices)
+    static constexpr bool GG = GG_;
     static constexpr int NT = WGM * WGN * 64;
     static constexpr int BM = WGM * TM * 32;
     static constexpr int BN = WGN * TN * 32;
@@ -57,6 +59,7 @@ struct Tile {
     static constexpr int LDS_BYTES = 2 * A_BYTES + 2 * B_BYTES + S_BYTES;
     static_assert(BM * BK / 16 % NT == 0 && BN * BKB / 16 % NT == 0, "tile loads must divide over the threads");
     static_assert(!W4 || BK == 128, "one K step is one 128-wide weight group");
+    static_assert(!GG || W4, "group sizes apply to 4-bit weights");
     static_assert(BM * 4 <= 2 * A_BYTES, "row-scale staging reuses the A buffers");
 };
 
@@ -93,7 +96,8 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
     const int wm = wave / T::WGN, wn = wave % T::WGN;
     const int M = a.M, N = a.N, K = a.K;
     const int KB = W4 ? K / 2 : K;  // bytes per weight row
-    const int G = K / 128;
+    const int G = T::GG ? K / a.group : K / 128;   // weight groups along K
+    const int QG = T::GG ? a.group / 32 : 4;         // 32-wide K slices per weight group
     const int nk = K / BK;  // the dispatcher only sends K % BK == 0 here
 
     // ---- global -> register staging of one K step
@@ -116,7 +120,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
             const int gr = min(n0 + row, N - 1);
             gb[i] = *reinterpret_cast<const v4i *>(static_cast<const unsigned char *>(a.w) + (size_t)gr * KB + (kb0 + cc * 16));
         }
-        if (W4 && (k0 % 128) == 0 && tid < BN) {
+        if (W4 && !T::GG && (k0 % 128) == 0 && tid < BN) {
             const int gr = min(n0 + tid, N - 1);
             // the nibbles are used as value*16, so the group scale carries the 1/16 (exact: a power of two)
             gs = half_to_float_dev(static_cast<const unsigned short *>(a.s_w)[(size_t)gr * G + k0 / 128]) * 0.0625f;
@@ -135,7 +139,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
             const int c = tid + i * NT;
             *reinterpret_cast<v4i *>(dB + (c / (BKB / 16)) * LDB + (c % (BKB / 16)) * 16) = gb[i];
         }
-        if (W4 && ((kt * BK) % 128) == 0 && tid < BN) sS[(((kt * BK) / 128) & 1) * BN + tid] = gs;
+        if (W4 && !T::GG && ((kt * BK) % 128) == 0 && tid < BN) sS[(((kt * BK) / 128) & 1) * BN + tid] = gs;
     };
 
     v16i acc[TM][TN];
@@ -157,6 +161,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
     const int a_off = (wm * TM * 32 + frag_row) * LDA + frag_half * 16;
     const int b_off = (wn * TN * 32 + frag_row) * LDB + frag_half * (W4 ? 8 : 16);
 
+    int qs = 0, grp = 0;   // generic group size: slice inside the current weight group, and the group's number
     load_tile(0);
     store_tile(0);
     __syncthreads();
@@ -181,6 +186,43 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
                     bf[j] = *reinterpret_cast<const v4i *>(pb + j * 32 * LDB + ks * 32);
                 }
             }
+            if (T::GG) {
+                // slice number qs of the current group: the group starts from a zero accumulator at qs == 0 and is
+                // folded into the fp32 sum after slice QG-1 (both tests are wavefront-uniform)
+                const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                if (qs == 0) {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], zero, 0, 0, 0);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+                }
+                if (++qs == QG) {
+                    qs = 0;
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        const int n = n0 + wn * TN * 32 + j * 32 + frag_row;
+                        // the nibbles are used as value*16, so the group scale carries the 1/16 (exact: a power of two)
+                        const float s16 = half_to_float_dev(static_cast<const unsigned short *>(a.s_w)[(size_t)min(n, N - 1) * G + grp]) * 0.0625f;
+#pragma unroll
+                        for (int i = 0; i < TM; ++i)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                if (a.acc_out) {
+                                    const int m = m0 + wm * TM * 32 + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
+                                    if (m < M && n < N) a.acc_out[(size_t)((size_t)m * G + grp) * N + n] = acc[i][j][r] >> 4;
+                                }
+                                fsum[W4 ? i : 0][W4 ? j : 0][r] = __builtin_fmaf((float)acc[i][j][r], s16, fsum[W4 ? i : 0][W4 ? j : 0][r]);
+                            }
+                    }
+                    ++grp;
+                }
+                continue;
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -190,7 +232,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], (W4 && ks == 0) ? zero : acc[i][j], 0, 0, 0);
                 }
         }
-        if (W4) {
+        if (W4 && !T::GG) {
             // the weight group ends here: fold its int32 partial sums into the fp32 sum with the group scale
             const int g = kt;
             const float *sc = sS + (g & 1) * BN + wn * TN * 32 + frag_row;
@@ -819,11 +861,12 @@ __global__ __launch_bounds__(256) void qgemm_naive(GemmArgs a)
         u = bias ? __builtin_fmaf(t, sw, b) : t * sw;
     } else {
         const unsigned char *w = static_cast<const unsigned char *>(a.w) + (size_t)n * (K / 2);
-        const int G = K / 128;
+        const int gsz = a.group;
+        const int G = K / gsz;
         float f = 0.0f;
         for (int g = 0; g < G; ++g) {
             int s = 0;
-            for (int k = 128 * g; k < 128 * g + 128; ++k) {
+            for (int k = gsz * g; k < gsz * g + gsz; ++k) {
                 const unsigned byte = w[4 * (k / 8) + (k % 4)];
                 int v = (k % 8) >= 4 ? (int)(byte >> 4) : (int)(byte & 0xf);
                 v = v >= 8 ? v - 16 : v;
@@ -877,6 +920,8 @@ using W4_128x128_k128 = Tile<2, 2, 2, 2, 128, true, 2>;
 using W4_64x128_k128 = Tile<1, 2, 2, 2, 128, true, 2>;
 using W4_256x128_8w = Tile<2, 2, 4, 2, 128, true, 2>;
 using W4_128x64_k128 = Tile<2, 1, 2, 2, 128, true, 3>;
+using W4G_128x64_k128 = Tile<2, 1, 2, 2, 128, true, 3, true>;   // any group size that is a multiple of 32
+using W4G_128x128_k128 = Tile<2, 2, 2, 2, 128, true, 2, true>;
 
 //                          TM TN WGM WGN S WPS
 using D8_128x128_s3 = TileD<2, 2, 2, 2, 3, 2>;
@@ -944,6 +989,8 @@ static const Variant VARIANTS[] = {
     {"w4 64x128 bk128 4w occ2", 4, 64, 128, 128, run_variant<W4_64x128_k128>},
     {"w4 256x128 bk128 8w occ2", 4, 256, 128, 128, run_variant<W4_256x128_8w>},
     {"w4 128x64 bk128 4w occ3", 4, 128, 64, 128, run_variant<W4_128x64_k128>},
+    {"w4 any-group 128x64 bk128 4w occ3", 4, 128, 64, 128, run_variant<W4G_128x64_k128>},
+    {"w4 any-group 128x128 bk128 4w occ2", 4, 128, 128, 128, run_variant<W4G_128x128_k128>},
 };
 constexpr int NUM_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);
 
@@ -983,20 +1030,27 @@ static int choose_variant(const GemmArgs &a)
     return a.K >= 2304 ? w8_mid_deep : w8_mid;
 }
 
+static bool is_any_group(int v) { return __builtin_strncmp(VARIANTS[v].name, "w4 any-group", 12) == 0; }
+
 hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream)
 {
     // MFMA tiles need 16-byte loads along K and a whole number of K steps
     const bool fast = (a.K % 64 == 0) && ((uintptr_t)a.q % 16 == 0) && ((uintptr_t)a.w % 16 == 0) &&
-                      (a.w_bits == 8 || a.K % 128 == 0);
+                      (a.w_bits == 8 || (a.K % 128 == 0 && a.group % 32 == 0));
     if (!fast || variant >= NUM_VARIANTS) {
         hipLaunchKernelGGL(qgemm_naive, dim3((a.M + 3) / 4, (a.N + 63) / 64), dim3(256), 0, stream, a);
         return hipGetLastError();
     }
     int v = variant;
     if (v < 0 || VARIANTS[v].w_bits != a.w_bits || a.K % VARIANTS[v].BK != 0) v = choose_variant(a);
-    // the pipelined 4-bit kernel keeps the group scales of a tile in LDS: at most 40 groups (K <= 5120)
-    if (a.w_bits == 4 && a.K > 128 * 40 && __builtin_strncmp(VARIANTS[v].name, "w4 dma", 6) == 0)
-        v = find_variant("w4 128x64 bk128 4w occ3");
+    if (a.w_bits == 4) {
+        // group sizes other than 128 run on the variants that end a group at any 32-wide K slice
+        static const int any_group = find_variant("w4 any-group 128x64 bk128 4w occ3");
+        if (a.group != 128 && !is_any_group(v)) v = any_group;
+        // the pipelined 4-bit kernel keeps the group scales of a tile in LDS: at most 40 groups (K <= 5120)
+        if (a.K > 128 * 40 && __builtin_strncmp(VARIANTS[v].name, "w4 dma", 6) == 0)
+            v = find_variant("w4 128x64 bk128 4w occ3");
+    }
     return VARIANTS[v].run(a, stream);
 }
 

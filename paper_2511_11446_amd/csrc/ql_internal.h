@@ -48,12 +48,13 @@ struct GemmArgs {
     const int8_t *q;      // [M,K] activation codes
     const float *s_a;     // [M/R]
     const void *w;        // int8 [N,K] or packed 4-bit [N,K/2]
-    const void *s_w;      // fp32 [N] (W8) or fp16 [N,K/128] (W4)
+    const void *s_w;      // fp32 [N] (W8) or fp16 [N,K/group] (W4)
     const void *bias;     // fp16 [N] or null
     void *y;              // fp16 [M,N]
-    int32_t *acc_out;     // optional export: [M,N] (W8) or [M,K/128,N] (W4)
+    int32_t *acc_out;     // optional export: [M,N] (W8) or [M,K/group,N] (W4)
     int M, N, K, R;
     int w_bits;           // 8 or 4
+    int group;            // 4-bit weights: k per weight scale (a multiple of 32 dividing K); 128 unless stated
 };
 
 int num_gemm_variants();

@@ -97,7 +97,7 @@ def test_plan_argument_checks():
     assert L.qlinear_plan_run(h, xs, ys, 256, 1, FAKE, 64, None) == 5
     assert L.qlinear_plan_run(None, xs, ys, 256, 1, FAKE, 1 << 30, None) == 1
     L.ql_plan_destroy(h)
-    bad = [(desc(bits=6), 4), (desc(bits=8, group=128), 4), (desc(bits=4, group=0), 4), (desc(bits=4, group=64), 4),
+    bad = [(desc(bits=6), 4), (desc(bits=8, group=128), 4), (desc(bits=4, group=0), 4), (desc(bits=4, group=48), 4),
            (desc(K=1100, bits=4, group=128), 2), (desc(w=0), 1), (desc(s=0), 1), (desc(N=0), 2), (desc(s=0x2001), 3)]
     for d, want in bad:
         arr = (ql.ql_layer_desc * 1)(d)
@@ -176,3 +176,16 @@ def test_robust_daq_argument_checks_and_time_bins():
     assert [ql.time_bin(i, 6) for i in range(6)] == [0, 0, 1, 1, 2, 2]
     assert [ql.time_bin(i, 25) for i in (0, 8, 9, 16, 17, 24)] == [0, 0, 1, 1, 2, 2]
     assert ql.time_bin(-1, 5) == -1 and ql.time_bin(5, 5) == -1 and ql.time_bin(0, 0) == -1
+
+
+def test_group_size_argument_checks():
+    L = ql.lib()
+    ws = ctypes.c_void_p(0x10000)
+    big = 1 << 30
+    args = lambda K, g: (FAKE, 4, K, 1, FAKE, FAKE, g, None, 8, FAKE, None, ws, big, None)
+    assert L.qlinear_w4a8_g(*args(1152, 48)) == 4       # not a multiple of 32
+    assert L.qlinear_w4a8_g(*args(1152, 0)) == 4
+    assert L.qlinear_w4a8_g(*args(1152, 320)) == 2      # does not divide K
+    assert L.qlinear_w4a8_g(*args(100, 100)) == 4
+    assert L.qgemm_w4a8_g(FAKE, FAKE, 4, 1152, 1, FAKE, FAKE, 48, None, 8, FAKE, None, None) == 4
+    assert L.qgemm_w4a8_g(FAKE, FAKE, 4, 1152, 1, FAKE, FAKE, 256, None, 8, FAKE, None, None) == 2

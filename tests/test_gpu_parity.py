@@ -461,6 +461,92 @@ def test_plan_runner_robust_time_bins(gpu, orc):
     plan.close()
 
 
+# ------------------------------------------------------------------ 4-bit weights with other group sizes
+
+W4G_CASES = [
+    # M, K, N, R, group
+    (192, 1152, 192, 1, 288),     # the paper's most used group size: 2.25 K steps per group
+    (160, 1152, 200, 1, 192),     # ragged M and N
+    (128, 1152, 128, 1, 64),
+    (96, 1152, 64, 1, 32),        # one group per 32-wide K slice
+    (256, 4608, 256, 64, 288),
+    (64, 1152, 96, 1, 1152),      # one group for the whole row
+    (64, 1152, 96, 1, 384),
+    (48, 576, 80, 1, 288),        # K % 128 != 0: generic kernel
+    (40, 96, 24, 1, 96),
+]
+
+
+@pytest.mark.parametrize("M,K,N,R,group", W4G_CASES)
+def test_w4a8_group_sizes(gpu, orc, M, K, N, R, group):
+    say("w4 group", M, K, N, R, group)
+    x = workload.activations(M, K, "w4g", group)
+    lw = workload.layer_weights("w4g", K, N, 4, group)
+    sw = workload.w4_scales_group(N, K, group, "w4g")
+    q_ref, s_ref = orc.daq(x, R)
+    P_ref = orc.gemm_w4g(q_ref, orc.pack_w4(lw["w"]), group, nthreads=8)
+    y_ref = orc.epilogue_w4(P_ref, s_ref, R, sw, lw["bias"])
+    out = gpu.qlinear_w4a8(dev(x), R, dev(gpu.ql_pack_w4_host(lw["w"])), dev(sw), dev(lw["bias"]), debug=True, group=group)
+    assert np.array_equal(host(out["q"]), q_ref)
+    assert np.array_equal(host(out["P"]), P_ref)
+    assert assert_y_close(host(out["y"]), y_ref) == 0
+    # the same without the debug exports (the path a plan takes)
+    y = gpu.qlinear_w4a8(dev(x), R, dev(gpu.ql_pack_w4_host(lw["w"])), dev(sw), dev(lw["bias"]), group=group)
+    assert assert_y_close(host(y), y_ref) == 0
+
+
+def test_w4a8_group128_through_the_group_entry_point_and_both_any_group_variants(gpu, orc):
+    M, K, N = 256, 1152, 256
+    x = workload.activations(M, K, "w4g128")
+    lw = workload.layer_weights("w4g128", K, N, 4)
+    ref = orc.qlinear_w4a8(x, 1, orc.pack_w4(lw["w"]), lw["s_w"], lw["bias"], want_debug=False)["y"]
+    w4 = dev(gpu.ql_pack_w4_host(lw["w"]))
+    names = gpu.gemm_variants()
+    sw288 = workload.w4_scales_group(N, K, 288, "v")
+    q_ref, s_ref = orc.daq(x, 1)
+    ref288 = orc.epilogue_w4(orc.gemm_w4g(q_ref, orc.pack_w4(lw["w"]), 288), s_ref, 1, sw288, lw["bias"])
+    try:
+        for v, nm in enumerate(names):
+            if not nm.startswith("w4 any-group"):
+                continue
+            say("variant", nm)
+            gpu.set_gemm_variant(v)
+            y = gpu.qlinear_w4a8(dev(x), 1, w4, dev(lw["s_w"]), dev(lw["bias"]))            # group 128 on the generic-group kernel
+            assert assert_y_close(host(y), ref) == 0
+            y = gpu.qlinear_w4a8(dev(x), 1, w4, dev(sw288), dev(lw["bias"]), group=288)
+            assert assert_y_close(host(y), ref288) == 0
+    finally:
+        gpu.set_gemm_variant(-1)
+
+
+def test_plan_with_mixed_group_sizes(gpu, orc):
+    import torch
+    M, R = 256, 1
+    shapes = [("a", 1152, 192, 4, 288), ("b", 1152, 128, 4, 128), ("c", 1152, 160, 8, 0), ("d", 1152, 96, 4, 64)]
+    layers, xs, refs = [], [], []
+    for name, K, N, bits, group in shapes:
+        lw = workload.layer_weights(name, K, N, bits, "plan-groups")
+        x = workload.activations(M, K, "plan-groups", name)
+        if bits == 8:
+            refs.append(orc.qlinear_w8a8(x, R, lw["w"], lw["s_w"], lw["bias"], want_debug=False)["y"])
+            layers.append(dict(K=K, N=N, bits=8, w=dev(lw["w"]), w_scale=dev(lw["s_w"]), bias=dev(lw["bias"])))
+        else:
+            sw = workload.w4_scales_group(N, K, group, name)
+            q, s = orc.daq(x, R)
+            refs.append(orc.epilogue_w4(orc.gemm_w4g(q, orc.pack_w4(lw["w"]), group), s, R, sw, lw["bias"]))
+            layers.append(dict(K=K, N=N, bits=4, group=group, w=dev(gpu.ql_pack_w4_host(lw["w"])), w_scale=dev(sw),
+                               bias=dev(lw["bias"])))
+        xs.append(dev(x))
+    plan = gpu.Plan(layers, M_max=M)
+    ys = [torch.zeros((M, l["N"]), dtype=torch.float16, device="cuda") for l in layers]
+    ws = gpu.workspace(plan.workspace_bytes(M, R))
+    plan.run(xs, ys, M, R, ws)
+    torch.cuda.synchronize()
+    for y, ref in zip(ys, refs):
+        assert assert_y_close(host(y), ref) == 0
+    plan.close()
+
+
 # ------------------------------------------------------------------ plan runner
 
 def test_plan_runner_small_mixed_plan(gpu, orc):

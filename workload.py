@@ -76,6 +76,11 @@ def w4_scales(N, K, *key):
     return rng("w4s", N, K, *key).uniform(1e-2, 1e-1, size=(N, K // 128)).astype(np.float16)
 
 
+def w4_scales_group(N, K, group, *key):
+    """fp16 [N, K/group] ~ U(1e-2, 1e-1) for weight groups of `group` inputs (the plan's other group sizes)."""
+    return rng("w4sg", N, K, group, *key).uniform(1e-2, 1e-1, size=(N, K // group)).astype(np.float16)
+
+
 def bias(N, *key):
     """fp16 [N] ~ N(0, 0.02^2)."""
     return (rng("bias", N, *key).standard_normal((N,), dtype=np.float32) * np.float32(0.02)).astype(np.float16)
