@@ -35,7 +35,7 @@ TRAFFIC_BYTES_PER_LAUNCH = {
 }
 
 
-def build_layers(ql, torch, wl_name):
+def build_layers(ql, torch, wl_name, w4_group=128):
     wl = workload.WORKLOADS[wl_name]
     if wl["layers"] == "bit_plan":
         descs = [(p["name"], p["K"], p["N"], p["bits"], p["block"]) for p in workload.bit_plan()]
@@ -45,7 +45,9 @@ def build_layers(ql, torch, wl_name):
     for name, K, N, bits, blk in descs:
         lw = workload.layer_weights(name, K, N, bits, wl_name, blk)
         w = lw["w"] if bits == 8 else ql.ql_pack_w4_host(lw["w"])
-        layers.append(dict(name=name, K=K, N=N, bits=bits, w=torch.from_numpy(w).cuda(),
+        if bits == 4 and w4_group != 128:
+            lw = dict(lw, s_w=workload.w4_scales_group(N, K, w4_group, wl_name, name, blk))
+        layers.append(dict(name=name, K=K, N=N, bits=bits, group=w4_group, w=torch.from_numpy(w).cuda(),
                            w_scale=torch.from_numpy(lw["s_w"]).cuda(), bias=torch.from_numpy(lw["bias"]).cuda(),
                            host=lw))
     return wl, layers
@@ -73,7 +75,7 @@ def build_inputs(ql, torch, wl_name, wl, layers):
             if fc1["bits"] == 8:
                 y1 = ql.qlinear_w8a8(x["fc1"], R, fc1["w"], fc1["w_scale"], fc1["bias"])
             else:
-                y1 = ql.qlinear_w4a8(x["fc1"], R, fc1["w"], fc1["w_scale"], fc1["bias"])
+                y1 = ql.qlinear_w4a8(x["fc1"], R, fc1["w"], fc1["w_scale"], fc1["bias"], group=fc1["group"])
             x["fc2"] = torch.nn.functional.gelu(y1.float(), approximate="tanh").half()   # input preparation only
             del y1
         elif "fc2" in types:
@@ -109,7 +111,12 @@ def cpu_baseline(wl_name, wl, layers, budget_rows=16384, min_seconds=10.0, max_p
             if l["bits"] == 8:
                 oracle.qlinear_w8a8(x, Rs, w, lw["s_w"], lw["bias"], nthreads=threads, want_debug=False)
             else:
-                oracle.qlinear_w4a8(x, Rs, w, lw["s_w"], lw["bias"], nthreads=threads, want_debug=False)
+                if l["group"] == 128:
+                    oracle.qlinear_w4a8(x, Rs, w, lw["s_w"], lw["bias"], nthreads=threads, want_debug=False)
+                else:
+                    qc, sc = oracle.daq(x, Rs, nthreads=threads)
+                    oracle.epilogue_w4(oracle.gemm_w4g(qc, w, l["group"], nthreads=threads), sc, Rs, l["w_scale"].cpu().numpy(),
+                                       lw["bias"])
             t_total += time.perf_counter() - t0
             macs += rows * l["K"] * l["N"]
         passes += 1
@@ -131,6 +138,8 @@ def main():
     ap.add_argument("--daq-p-ppm", type=int, default=None,
                     help="percentile-clipped DAQ (eq. (4) as printed): p in parts per million, e.g. 999000; default: absmax")
     ap.add_argument("--a-bits", type=int, default=8, help="activation code width for --daq-p-ppm (Step 6 time-bin policy)")
+    ap.add_argument("--w4-group", type=int, default=128,
+                    help="k per weight scale of the 4-bit layers (the plan's other group sizes: 64, 192, 288 ...)")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: a few steps of the workload plus a device copy of known size, no timing")
     args = ap.parse_args()
@@ -148,13 +157,13 @@ def main():
     torch.cuda.set_device(0)
     ql.set_gemm_variant(args.variant)
 
-    wl, layers = build_layers(ql, torch, args.workload)
+    wl, layers = build_layers(ql, torch, args.workload, args.w4_group)
     M, R = wl["M"], wl["R"]
     big = M >= 8192
     steps = args.steps if args.steps is not None else (wl["steps"] if wl["steps"] > 1 else (100 if not big else 20))
     warmup = args.warmup if args.warmup is not None else (10 if not big else 3)
     pool, sigmas = build_inputs(ql, torch, args.workload, wl, layers)
-    plan = ql.Plan([dict(K=l["K"], N=l["N"], bits=l["bits"], w=l["w"], w_scale=l["w_scale"], bias=l["bias"])
+    plan = ql.Plan([dict(K=l["K"], N=l["N"], bits=l["bits"], group=l["group"], w=l["w"], w_scale=l["w_scale"], bias=l["bias"])
                     for l in layers], M_max=M)
     ws = ql.workspace(plan.workspace_bytes(M, R))
     y_by_type = {}
@@ -248,7 +257,10 @@ def main():
             sa = torch.empty((M // R,), dtype=torch.float32, device="cuda")
             dws = ql.workspace(ql.daq_workspace_bytes(M, l["K"], R))
             y = torch.empty((M, l["N"]), dtype=torch.float16, device="cuda")
-            gfn = ql.qgemm_w8a8 if l["bits"] == 8 else ql.qgemm_w4a8
+            if l["bits"] == 8:
+                gfn = ql.qgemm_w8a8
+            else:
+                gfn = (lambda *a, _g=l["group"], **kw: ql.qgemm_w4a8(*a, group=_g, **kw))
             # eager once (also the comparison for the graph replays below)
             run_daq(x, q, sa, dws)
             gfn(q, sa, R, l["w"], l["w_scale"], l["bias"], y=y)
@@ -313,6 +325,7 @@ def main():
         "config": {"workload": args.workload, "M": M, "rows_per_scale": R, "layers": L,
                    "w4_layers": sum(l["bits"] == 4 for l in layers), "activation_sets_rotated": len(pool),
                    "sigmas": sigmas, "gemm_variant": args.variant,
+                   "w4_group": args.w4_group,
                    "daq": ("percentile p_ppm=%d a_bits=%d" % (args.daq_p_ppm, args.a_bits)) if robust else "absmax a_bits=8"},
         "host_wall_ms_per_step": t_wall / steps * 1e3,
         "roofline": roofline,

@@ -162,6 +162,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
     const int b_off = (wn * TN * 32 + frag_row) * LDB + frag_half * (W4 ? 8 : 16);
 
     int qs = 0, grp = 0;   // generic group size: slice inside the current weight group, and the group's number
+    unsigned short sgrp[TN] = {};
     load_tile(0);
     store_tile(0);
     __syncthreads();
@@ -170,7 +171,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
         if (kt + 1 < nk) load_tile(kt + 1);
         const unsigned char *pa = sA + (kt & 1) * T::A_BYTES + a_off;
         const unsigned char *pb = sB + (kt & 1) * T::B_BYTES + b_off;
-#pragma unroll
+#pragma unroll(T::GG ? 1 : BK / 32)   // with run-time group ends the four slices share one copy of the code
         for (int ks = 0; ks < BK / 32; ++ks) {
             v4i af[TM], bf[TN];
 #pragma unroll
@@ -187,36 +188,35 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
                 }
             }
             if (T::GG) {
-                // slice number qs of the current group: the group starts from a zero accumulator at qs == 0 and is
-                // folded into the fp32 sum after slice QG-1 (both tests are wavefront-uniform)
-                const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                // slice number qs of the current group (wavefront-uniform): the group's scales are requested at its
+                // first slice; after its last slice the partial sums are folded into the fp32 sum and the accumulators
+                // cleared (one code path for the MFMAs: a second one with a zero C operand doubled the register need)
                 if (qs == 0) {
 #pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], zero, 0, 0, 0);
-                } else {
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+                    for (int j = 0; j < TN; ++j)
+                        sgrp[j] = static_cast<const unsigned short *>(a.s_w)[(size_t)min(n0 + wn * TN * 32 + j * 32 + frag_row, N - 1) * G + grp];
                 }
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
                 if (++qs == QG) {
                     qs = 0;
 #pragma unroll
                     for (int j = 0; j < TN; ++j) {
                         const int n = n0 + wn * TN * 32 + j * 32 + frag_row;
                         // the nibbles are used as value*16, so the group scale carries the 1/16 (exact: a power of two)
-                        const float s16 = half_to_float_dev(static_cast<const unsigned short *>(a.s_w)[(size_t)min(n, N - 1) * G + grp]) * 0.0625f;
+                        const float s16 = half_to_float_dev(sgrp[j]) * 0.0625f;
 #pragma unroll
                         for (int i = 0; i < TM; ++i)
 #pragma unroll
                             for (int r = 0; r < 16; ++r) {
                                 if (a.acc_out) {
                                     const int m = m0 + wm * TM * 32 + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
-                                    if (m < M && n < N) a.acc_out[(size_t)((size_t)m * G + grp) * N + n] = acc[i][j][r] >> 4;
+                                    if (m < M && n < N) a.acc_out[(unsigned)((m * G + grp) * N + n)] = acc[i][j][r] >> 4;
                                 }
                                 fsum[W4 ? i : 0][W4 ? j : 0][r] = __builtin_fmaf((float)acc[i][j][r], s16, fsum[W4 ? i : 0][W4 ? j : 0][r]);
+                                acc[i][j][r] = 0;
                             }
                     }
                     ++grp;
@@ -1014,8 +1014,10 @@ static int choose_variant(const GemmArgs &a)
                      w8_big = find_variant("w8 dma 256x192 a3b2 8w spread1"),
                      w8_big_b3 = find_variant("w8 dma 256x192 a2b3 8w spread1"),
                      w8_wide = find_variant("w8 dma 256x256 s2 8w spread2"),
-                     w8_k64 = find_variant("w8 128x128 bk64 4w occ3"), w4_any = find_variant("w4 128x64 bk128 4w occ3");
-    if (a.w_bits == 4) return w4_any;   // the register-staged kernel at 3 wavefronts per SIMD hides the per-group VALU work best
+                     w8_k64 = find_variant("w8 128x128 bk64 4w occ3"), w4_any = find_variant("w4 any-group 128x64 bk128 4w occ3");
+    // the register-staged kernel at 3 wavefronts per SIMD hides the per-group VALU work best; its any-group form, whose
+    // four K slices share one copy of the loop body, is also the fastest at group 128 (108 against 127 us, fc1 at M = 8192)
+    if (a.w_bits == 4) return w4_any;
     if (a.K % 128 != 0) return w8_k64;
     if (a.M <= 512) return w8_small;
     const long tiles_big = (long)((a.M + 255) / 256) * ((a.N + 191) / 192);
