@@ -311,7 +311,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
 // leaves the lane as half of a 4-byte word instead of a 2-byte store.
 //   STAGED: the words go to the LDS strip and are read back as 16-byte pieces (whole row segments per store);
 //   otherwise they are stored to global memory directly (64-byte row segments per half wavefront).
-template <int TM, int TN, bool STAGED, class ValueFn>
+template <int TM, int TN, bool STAGED, int ROWS = 32, class ValueFn>
 __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane, _Float16 *y, int N, int m_base, int n_base,
                                                   ValueFn value)
 {
@@ -324,39 +324,44 @@ __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane
     const unsigned sel = odd ? 0x03020706u : 0x05040100u;
     unsigned char *wr = strip + (4 * frag_half + odd) * PITCH + (frag_row - odd) * 2;
     const unsigned g_off = (unsigned)((m_base + 4 * frag_half + odd) * N + n_base + frag_row - odd);
+    static_assert(ROWS == 32 || ROWS == 16, "the strip holds a whole 32-row block or one half of it");
+    constexpr int HALVES = 32 / ROWS;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int h = 0; h < HALVES; ++h) {
 #pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-                float u0 = value(i, j, r), u1 = value(i, j, r + 1);
-                // keep the fp32 rounding of the fused multiply-add: without this the compiler may select a
-                // mixed-precision fma that rounds straight to fp16 (one rounding instead of the defined two)
-                asm volatile("" : "+v"(u0), "+v"(u1));
-                typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-                const h2 pr = {(_Float16)u0, (_Float16)u1};
-                const unsigned own = __builtin_bit_cast(unsigned, pr);
-                // every lane has a valid source, so no fill value is needed (the update form would first clear the destination)
-                const unsigned nbr = (unsigned)__builtin_amdgcn_mov_dpp((int)own, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true);
-                const unsigned word = __builtin_amdgcn_perm(nbr, own, sel);
-                const int row = 8 * (r / 4) + (r % 4);  // + 4*frag_half + odd, already in the lane's base
-                if (STAGED)
-                    *reinterpret_cast<unsigned __attribute__((may_alias)) *>(wr + row * PITCH + j * 64) = word;
-                else
-                    *reinterpret_cast<unsigned __attribute__((may_alias)) *>(y + (g_off + (unsigned)((i * 32 + row) * N + j * 32))) = word;
-            }
-        if (STAGED) {
-            asm volatile("" ::: "memory");  // the strip reads below see other lanes' writes: keep program order
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int t = 0; t < 32 * CH / 64; ++t) {
-                const int id = lane + 64 * t;
-                const int row = id / CH, ch = id % CH;
-                const v4i v = *reinterpret_cast<const v4i_alias *>(strip + row * PITCH + ch * 16);
-                // the output is written once and not read again by this kernel: keep it from displacing the operand panels in L2
-                __builtin_nontemporal_store(v, reinterpret_cast<v4i_alias *>(y + (unsigned)((m_base + i * 32 + row) * N + n_base + ch * 8)));
+                for (int r = h * (16 / HALVES); r < (h + 1) * (16 / HALVES); r += 2) {
+                    float u0 = value(i, j, r), u1 = value(i, j, r + 1);
+                    // keep the fp32 rounding of the fused multiply-add: without this the compiler may select a
+                    // mixed-precision fma that rounds straight to fp16 (one rounding instead of the defined two)
+                    asm volatile("" : "+v"(u0), "+v"(u1));
+                    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+                    const h2 pr = {(_Float16)u0, (_Float16)u1};
+                    const unsigned own = __builtin_bit_cast(unsigned, pr);
+                    // every lane has a valid source, so no fill value is needed (the update form would first clear the destination)
+                    const unsigned nbr = (unsigned)__builtin_amdgcn_mov_dpp((int)own, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true);
+                    const unsigned word = __builtin_amdgcn_perm(nbr, own, sel);
+                    const int row = 8 * (r / 4) + (r % 4);  // + 4*frag_half + odd, already in the lane's base
+                    if (STAGED)
+                        *reinterpret_cast<unsigned __attribute__((may_alias)) *>(wr + (row - h * ROWS) * PITCH + j * 64) = word;
+                    else
+                        *reinterpret_cast<unsigned __attribute__((may_alias)) *>(y + (g_off + (unsigned)((i * 32 + row) * N + j * 32))) = word;
+                }
+            if (STAGED) {
+                asm volatile("" ::: "memory");  // the strip reads below see other lanes' writes: keep program order
+#pragma unroll
+                for (int t = 0; t < ROWS * CH / 64; ++t) {
+                    const int id = lane + 64 * t;
+                    const int row = id / CH, ch = id % CH;
+                    const v4i v = *reinterpret_cast<const v4i_alias *>(strip + row * PITCH + ch * 16);
+                    // the output is written once and not read again by this kernel: keep it from displacing the operand panels in L2
+                    __builtin_nontemporal_store(v, reinterpret_cast<v4i_alias *>(y + (unsigned)((m_base + i * 32 + h * ROWS + row) * N + n_base + ch * 8)));
+                }
+                asm volatile("" ::: "memory");
             }
-            asm volatile("" ::: "memory");
         }
     }
 }
@@ -388,7 +393,10 @@ struct TileD {
     static constexpr bool STAGED_STORE = STG_;
     static constexpr int DMA_EVERY = EV_;                 // one DMA instruction behind every EV_-th MFMA; 0: all at the hand-over
     static constexpr int STRIP_OFF = (BM * 4 + 255) / 256 * 256;   // epilogue: row scales first, then one strip per wavefront
-    static constexpr int STRIP_BYTES = 32 * (TN * 64 + 16);
+    // a persistent workgroup parks its epilogue beside stage 0; where a 32-row strip per wavefront does not fit there,
+    // the strip holds 16 rows
+    static constexpr int STRIP_ROWS = (PERSIST_ && (SA - 1) * A_BYTES < STRIP_OFF + NW * 32 * (TN * 64 + 16)) ? 16 : 32;
+    static constexpr int STRIP_BYTES = STRIP_ROWS * (TN * 64 + 16);
     static constexpr int RINGS = SA * A_BYTES + SB * B_BYTES;
     static constexpr int RING_BYTES = RINGS > STRIP_OFF + NW * STRIP_BYTES ? RINGS : STRIP_OFF + NW * STRIP_BYTES;
     static constexpr int MAX_GROUPS_K = 40;               // 4-bit: group scales of the tile's columns live in LDS (K <= 5120)
@@ -750,19 +758,19 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
                 }
         }
         if (W4 && bias)
-            store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
+            store_tile_staged<TM, TN, T::STAGED_STORE, T::STRIP_ROWS>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
                 return __builtin_fmaf(fsum[W4 ? i : 0][W4 ? j : 0][r], sr[i * 16 + r], bj[j]);
             });
         else if (W4)
-            store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
+            store_tile_staged<TM, TN, T::STAGED_STORE, T::STRIP_ROWS>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
                 return fsum[W4 ? i : 0][W4 ? j : 0][r] * sr[i * 16 + r];
             });
         else if (bias)
-            store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
+            store_tile_staged<TM, TN, T::STAGED_STORE, T::STRIP_ROWS>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
                 return __builtin_fmaf((float)acc[i][j][r] * sr[i * 16 + r], swt[j], bj[j]);
             });
         else
-            store_tile_staged<TM, TN, T::STAGED_STORE>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
+            store_tile_staged<TM, TN, T::STAGED_STORE, T::STRIP_ROWS>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
                 return (float)acc[i][j][r] * sr[i * 16 + r] * swt[j];
             });
     } else {
@@ -950,6 +958,7 @@ using D8_128x128_s2_e1 = TileD<2, 2, 2, 2, 2, 2, true, 1>;
 using P8_256x192_a3b2 = TileD<2, 3, 4, 2, 3, 2, true, 1, false, 2, true>;
 using P8_256x256_a3b2 = TileD<4, 2, 2, 4, 3, 2, true, 1, false, 2, true>;
 using P8_128x128_a3b2 = TileD<2, 2, 2, 2, 3, 2, true, 1, false, 2, true>;
+using P8_128x192_s2 = TileD<2, 3, 2, 2, 2, 2, true, 1, false, 2, true>;
 
 static const Variant VARIANTS[] = {
     {"w8 dma 128x128 s3 4w", 8, 128, 128, 128, run_dma<D8_128x128_s3>},
@@ -976,6 +985,7 @@ static const Variant VARIANTS[] = {
     {"w8 dma 256x192 a3b2 8w spread1 persistent", 8, 256, 192, 128, run_dma<P8_256x192_a3b2>},
     {"w8 dma 256x256 a3b2 8w spread1 persistent", 8, 256, 256, 128, run_dma<P8_256x256_a3b2>},
     {"w8 dma 128x128 a3b2 4w spread1 persistent", 8, 128, 128, 128, run_dma<P8_128x128_a3b2>},
+    {"w8 dma 128x192 s2 4w spread1 persistent", 8, 128, 192, 128, run_dma<P8_128x192_s2>},
     {"w8 128x128 bk64 4w occ2", 8, 128, 128, 64, run_variant<W8_128x128_k64>},
     {"w8 128x128 bk128 4w occ2", 8, 128, 128, 128, run_variant<W8_128x128_k128>},
     {"w8 256x128 bk64 4w occ2", 8, 256, 128, 64, run_variant<W8_256x128_k64>},
@@ -1010,10 +1020,9 @@ static int choose_variant(const GemmArgs &a)
     static const int w8_small = find_variant("w8 dma 64x64 s4 4w"),
                      w8_mid = find_variant("w8 dma 128x128 a3b2 4w spread1"),
                      w8_mid_deep = find_variant("w8 dma 128x128 a3b2 4w"),
-                     w8_mid_persist = find_variant("w8 dma 128x128 a3b2 4w spread1 persistent"),
+                     w8_p128 = find_variant("w8 dma 128x128 a3b2 4w spread1 persistent"),
+                     w8_p192 = find_variant("w8 dma 128x192 s2 4w spread1 persistent"),
                      w8_big = find_variant("w8 dma 256x192 a3b2 8w spread1"),
-                     w8_big_b3 = find_variant("w8 dma 256x192 a2b3 8w spread1"),
-                     w8_wide = find_variant("w8 dma 256x256 s2 8w spread2"),
                      w8_k64 = find_variant("w8 128x128 bk64 4w occ3"), w4_any = find_variant("w4 any-group 128x64 bk128 4w occ3");
     // the register-staged kernel at 3 wavefronts per SIMD hides the per-group VALU work best; its any-group form, whose
     // four K slices share one copy of the loop body, is also the fastest at group 128 (108 against 127 us, fc1 at M = 8192)
@@ -1021,12 +1030,11 @@ static int choose_variant(const GemmArgs &a)
     if (a.K % 128 != 0) return w8_k64;
     if (a.M <= 512) return w8_small;
     const long tiles_big = (long)((a.M + 255) / 256) * ((a.N + 191) / 192);
-    if (tiles_big >= 192) {                                   // at least 3/4 of the CUs get a 256x192 tile
-        if (a.K >= 2304) return w8_big_b3;                    // a long K loop: a third weight stage pays
-        if (a.N % 256 == 0 && a.N >= 4096 && a.M >= 8192) return w8_wide;
-        // several tiles per CU: two resident 128x128 workgroups per CU that walk their tiles and fetch the next
-        // tile's first K step under the epilogue
-        if (a.M >= 4096) return w8_mid_persist;
+    if (tiles_big >= 192) {                                   // enough work for every CU
+        // Several tiles per CU: two resident 4-wavefront workgroups per CU that walk their tiles and fetch the next
+        // tile's first K step under the epilogue.  128x192 tiles move less data per MAC; 128x128 tiles balance better
+        // when the tiles per CU are few and N is wide.
+        if (a.M >= 4096) return (a.K >= 2304 || a.N <= 1536 || a.M >= 12288) ? w8_p192 : w8_p128;
         return w8_big;
     }
     return a.K >= 2304 ? w8_mid_deep : w8_mid;
