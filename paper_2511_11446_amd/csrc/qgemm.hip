@@ -69,6 +69,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
     constexpr int TM = T::TM, TN = T::TN, BK = T::BK, BM = T::BM, BN = T::BN, NT = T::NT;
     constexpr int LDA = T::LDA, LDB = T::LDB, BKB = T::BKB;
     constexpr bool W4 = T::W4;
+    constexpr int SLICE_UNROLL = T::GG ? 1 : BK / 32;
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char *sA = smem;
     unsigned char *sB = smem + 2 * T::A_BYTES;
@@ -171,7 +172,8 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
         if (kt + 1 < nk) load_tile(kt + 1);
         const unsigned char *pa = sA + (kt & 1) * T::A_BYTES + a_off;
         const unsigned char *pb = sB + (kt & 1) * T::B_BYTES + b_off;
-#pragma unroll(T::GG ? 1 : BK / 32)   // with run-time group ends the four slices share one copy of the code
+        // with run-time group ends the four slices share one copy of the code
+#pragma unroll SLICE_UNROLL
         for (int ks = 0; ks < BK / 32; ++ks) {
             v4i af[TM], bf[TN];
 #pragma unroll

@@ -192,6 +192,24 @@ def test_w8a8_extreme_fill_and_zero_input(gpu, orc):
     assert np.array_equal(host(y), np.repeat(lw["bias"][None], 40, 0))
 
 
+def test_w8a8_longest_k_fills_int32(gpu, orc):
+    """K at the ABI's limit (the largest multiple of 128 below 133143), every product +-127*127: the accumulator ends
+    400 000 below 2^31 and must not wrap; also the longest row the DAQ kernels see (re-read path)."""
+    M, K, N = 8, 133120, 32
+    say("w8a8 longest K", M, K, N)
+    x = np.full((M, K), 5.0, np.float16)
+    x[1::2] = np.float16(-5.0)
+    w = np.full((N, K), 127, np.int8)
+    w[1::2] = -127
+    s_w = np.full((N,), 2.0 ** -20, np.float32)
+    ref = orc.qlinear_w8a8(x, 1, w, s_w, None, nthreads=8)
+    assert np.abs(ref["acc"]).max() == 127 * 127 * K and 127 * 127 * K < 2 ** 31
+    out = gpu.qlinear_w8a8(dev(x), 1, dev(w), dev(s_w), None, debug=True)
+    assert np.array_equal(host(out["q"]), ref["q"])
+    assert np.array_equal(host(out["acc"]), ref["acc"])
+    assert assert_y_close(host(out["y"]), ref["y"]) == 0
+
+
 # ------------------------------------------------------------------ W4A8 layer
 
 def run_w4(gpu, orc, M, K, N, R, key, use_bias=True, check_exact=False):
