@@ -222,6 +222,48 @@ def epilogue_w4(P, s_a, R, s_w, bias):
     return y.view(np.float16)
 
 
+def dequant_w8(acc, s_a, R, s_w, bias):
+    """The layer's fp32 values before the fp16 rounding, float32 [M,N]."""
+    acc = _c(acc, np.int32)
+    s_a = _c(s_a, np.float32)
+    s_w = _c(s_w, np.float32)
+    M, N = acc.shape
+    b = None if bias is None else _f16bits(bias)
+    u = np.empty((M, N), np.float32)
+    rc = lib().orc_dequant_w8(_p(acc), _p(s_a), ctypes.c_int64(R), _p(s_w), _p(b), ctypes.c_int64(M), ctypes.c_int64(N), _p(u))
+    if rc:
+        raise ValueError("orc_dequant_w8 rc=%d" % rc)
+    return u
+
+
+def dequant_w4(P, s_a, R, s_w, bias):
+    P = _c(P, np.int32)
+    s_a = _c(s_a, np.float32)
+    sw = _f16bits(s_w)
+    M, G, N = P.shape
+    b = None if bias is None else _f16bits(bias)
+    u = np.empty((M, N), np.float32)
+    rc = lib().orc_dequant_w4(_p(P), _p(s_a), ctypes.c_int64(R), _p(sw), _p(b), ctypes.c_int64(M), ctypes.c_int64(N),
+                              ctypes.c_int64(G), _p(u))
+    if rc:
+        raise ValueError("orc_dequant_w4 rc=%d" % rc)
+    return u
+
+
+def block_glue(u, act=0, residual=None, gate=None, gate_rows=1):
+    """u float32 [M,N] -> y float16 [M,N]: activation, gate and residual folded into the epilogue."""
+    u = _c(u, np.float32)
+    M, N = u.shape
+    r = None if residual is None else _f16bits(residual)
+    g = None if gate is None else _f16bits(gate)
+    y = np.empty((M, N), np.uint16)
+    rc = lib().orc_block_glue(_p(u), ctypes.c_int64(M), ctypes.c_int64(N), ctypes.c_int(act), _p(r), _p(g),
+                              ctypes.c_int64(gate_rows), _p(y))
+    if rc:
+        raise ValueError("orc_block_glue rc=%d" % rc)
+    return y.view(np.float16)
+
+
 def qlinear_w8a8(x, R, w, s_w, bias, nthreads=1, want_debug=True):
     """Whole layer.  Returns dict(y, q, s_a, acc)."""
     xb = _f16bits(x)

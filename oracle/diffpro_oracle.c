@@ -350,6 +350,70 @@ int orc_epilogue_w4(const int32_t *P, const float *s_a, int64_t R, const uint16_
 }
 
 /* ------------------------------------------------------------------ */
+/* Block glue folded into the layer's epilogue (Section 6 counts the   */
+/* residual additions in the latency; Step 3 keeps residual adds in    */
+/* higher precision; the MLP's activation sits between its two         */
+/* quantized linears).                                                  */
+/*   u  = the dequantized binary32 value of the layer, as above, before */
+/*        its rounding to binary16 (orc_dequant_w8 / _w4)               */
+/*   h  = f16( act(u) )     act = identity, or GELU in its tanh form    */
+/*        gelu(u) = u * sigmoid(2 z), z = sqrt(2/pi) (u + 0.044715 u^3) */
+/*        (= 0.5 u (1 + tanh z)), evaluated in binary64, rounded to     */
+/*        binary32 and then to binary16                                 */
+/*   y  = h                                   without gate and residual */
+/*   y  = f16( fma(g, float(h), r) )          g = gate[m / gate_rows, n] (1 if none), r = residual[m, n] (0 if none) */
+/* ------------------------------------------------------------------ */
+int orc_dequant_w8(const int32_t *acc, const float *s_a, int64_t R, const float *s_w,
+                   const uint16_t *bias, int64_t M, int64_t N, float *u)
+{
+    if (M < 0 || N < 0 || R <= 0 || (M % R) != 0) return 1;
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            float t = (float)acc[m * N + n] * s_a[m / R];
+            u[m * N + n] = bias ? fmaf(t, s_w[n], orc_half_to_float(bias[n])) : t * s_w[n];
+        }
+    return 0;
+}
+
+int orc_dequant_w4(const int32_t *P, const float *s_a, int64_t R, const uint16_t *s_w,
+                   const uint16_t *bias, int64_t M, int64_t N, int64_t G, float *u)
+{
+    if (M < 0 || N < 0 || G < 0 || R <= 0 || (M % R) != 0) return 1;
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            float f = 0.0f;
+            for (int64_t g = 0; g < G; ++g)
+                f = fmaf((float)P[(m * G + g) * N + n], orc_half_to_float(s_w[n * G + g]), f);
+            u[m * N + n] = bias ? fmaf(f, s_a[m / R], orc_half_to_float(bias[n])) : f * s_a[m / R];
+        }
+    return 0;
+}
+
+int orc_block_glue(const float *u, int64_t M, int64_t N, int act, const uint16_t *residual,
+                   const uint16_t *gate, int64_t gate_rows, uint16_t *y)
+{
+    if (M < 0 || N < 0 || (act != 0 && act != 1)) return 1;
+    if (gate && (gate_rows <= 0 || (M % gate_rows) != 0)) return 1;
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            float v = u[m * N + n];
+            if (act == 1) {
+                double x = (double)v;
+                double z = 0.7978845608028654 * (x + 0.044715 * x * x * x);   /* sqrt(2/pi) */
+                v = (float)(x / (1.0 + exp(-2.0 * z)));
+            }
+            uint16_t h = orc_float_to_half(v);
+            if (gate || residual) {
+                float g = gate ? orc_half_to_float(gate[(m / gate_rows) * N + n]) : 1.0f;
+                float r = residual ? orc_half_to_float(residual[m * N + n]) : 0.0f;
+                h = orc_float_to_half(fmaf(g, orc_half_to_float(h), r));
+            }
+            y[m * N + n] = h;
+        }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
 /* The whole layer: DAQ -> GEMM -> epilogue.  Optional outputs         */
 /* (q, s_a, acc / P) may be NULL; scratch is then taken from the heap. */
 /* ------------------------------------------------------------------ */

@@ -163,3 +163,58 @@ def test_grouped_epilogue_with_equal_power_of_two_scales_equals_the_per_channel_
     y4 = orc.epilogue_w4(P, s_a, 1, sw, bias)
     y8 = orc.epilogue_w8(orc.gemm_i8(q, w), s_a, 1, np.full((N,), 0.25, np.float32), bias)
     assert np.array_equal(y4.view(np.uint16), y8.view(np.uint16))
+
+
+# ---------------------------------------------------------------- block glue folded into the epilogue
+
+def test_dequant_values_round_to_the_plain_epilogues(orc):
+    g = workload.rng("glue-dq")
+    M, K, N = 6, 256, 10
+    q = g.integers(-127, 128, size=(M, K), dtype=np.int8)
+    w8 = g.integers(-127, 128, size=(N, K), dtype=np.int8)
+    w4 = g.integers(-8, 8, size=(N, K), dtype=np.int8)
+    s_a = g.uniform(0.01, 0.1, M).astype(np.float32)
+    bias = workload.bias(N, "glue")
+    acc = orc.gemm_i8(q, w8)
+    sw8 = workload.w8_scales(N, "glue")
+    assert np.array_equal(orc.float_to_half(orc.dequant_w8(acc, s_a, 1, sw8, bias)), orc.epilogue_w8(acc, s_a, 1, sw8, bias).view(np.uint16))
+    P = orc.gemm_w4g128(q, orc.pack_w4(w4))
+    sw4 = workload.w4_scales(N, K, "glue")
+    assert np.array_equal(orc.float_to_half(orc.dequant_w4(P, s_a, 1, sw4, None)), orc.epilogue_w4(P, s_a, 1, sw4, None).view(np.uint16))
+    # no activation, gate or residual: the glue is the rounding alone
+    u = orc.dequant_w8(acc, s_a, 1, sw8, bias)
+    assert np.array_equal(orc.block_glue(u).view(np.uint16), orc.float_to_half(u))
+
+
+def test_gelu_against_the_tanh_formula_and_its_closed_form_values(orc):
+    import math
+    u = np.array([[0.0, 1.0, -1.0, 3.0, -3.0, 0.5, -8.0, 10.0, -0.0, 1e-4]], np.float32)
+    y = orc.block_glue(u, act=1).astype(np.float64)
+    want = np.array([0.5 * x * (1.0 + math.tanh(math.sqrt(2.0 / math.pi) * (x + 0.044715 * x ** 3))) for x in u[0].astype(np.float64)])
+    assert np.allclose(y[0], want, rtol=2.0 ** -10, atol=2.0 ** -24)
+    # published values of the tanh form: gelu(1) = 0.841192, gelu(-1) = -0.158808, gelu(3) = 2.996363
+    assert abs(y[0, 1] - 0.841192) < 5e-4 and abs(y[0, 2] + 0.158808) < 2e-4 and abs(y[0, 3] - 2.996363) < 2e-3
+    assert y[0, 0] == 0.0 and y[0, 7] == 10.0 and abs(y[0, 6]) < 1e-6
+    # gelu(x) - gelu(-x) = x for every x (sigmoid(t) + sigmoid(-t) = 1)
+    xs = workload.rng("gelu-sym").uniform(-6, 6, size=(1, 4096)).astype(np.float32)
+    a = orc.block_glue(xs, act=1).astype(np.float64)
+    b = orc.block_glue(-xs, act=1).astype(np.float64)
+    assert np.allclose(a - b, xs, rtol=2e-3, atol=2e-3)
+
+
+def test_gate_and_residual_hand_worked_and_broadcast(orc):
+    u = np.array([[1.0, 2.0, -4.0], [0.5, 0.25, 8.0], [1.0, 1.0, 1.0], [3.0, -3.0, 0.0]], np.float32)
+    res = np.array([[10, 20, 30], [1, 1, 1], [0, 0, 0], [-1, -2, -3]], np.float16)
+    gate = np.array([[2.0, 0.5, -1.0], [0.0, 1.0, 4.0]], np.float16)      # one gate row per 2 rows
+    y = orc.block_glue(u, residual=res, gate=gate, gate_rows=2)
+    want = np.array([[12, 21, 34], [2, 1.125, -7], [0, 1, 4], [-1, -5, -3]], np.float16)
+    assert np.array_equal(y, want)
+    assert np.array_equal(orc.block_glue(u, residual=res), (u + res.astype(np.float32)).astype(np.float16))
+    assert np.array_equal(orc.block_glue(u, gate=gate, gate_rows=2), (u * np.repeat(gate.astype(np.float32), 2, 0)).astype(np.float16))
+    # the layer's value is rounded to fp16 BEFORE the gated addition: 1 + 2^-11 rounds to 1 first, so adding 2^-11 gives
+    # 1 + 2^-11 -> 1 (tie to even), not the 1 + 2^-10 a single rounding of the exact sum would give
+    u2 = np.array([[1.0 + 2.0 ** -11]], np.float32)
+    r2 = np.array([[2.0 ** -11]], np.float16)
+    assert orc.block_glue(u2, residual=r2)[0, 0] == np.float16(1.0)
+    with pytest.raises(ValueError):
+        orc.block_glue(u, gate=gate, gate_rows=3)
