@@ -158,6 +158,43 @@ int qgemm_w4a8_g(const void *q, const void *a_scales, int64_t M, int64_t K, int6
                  const void *w4, const void *w_scale, int64_t group, const void *bias, int64_t N,
                  void *y, void *acc, void *stream);
 
+/* ------------------------------------------------------------------------
+ * Block glue folded into the layer's epilogue (Section 6 counts the residual
+ * additions in the latency; Step 3 keeps them in higher precision; the MLP's
+ * activation sits between its two quantized linears).  With u the layer's
+ * fp32 value before its rounding to fp16 (formulas above):
+ *   h = fp16( act(u) )                  act: QL_ACT_NONE, or QL_ACT_GELU_TANH
+ *                                       gelu(u) = u * sigmoid(2z), z = sqrt(2/pi) (u + 0.044715 u^3)
+ *   y = h                               without gate and residual
+ *   y = fp16( fma(g, float(h), r) )     g = gate[m / gate_rows, n] (1 if gate is NULL),
+ *                                       r = residual[m, n]         (0 if residual is NULL)
+ * i.e. the result of the unfused sequence layer -> fp16 -> gated residual add.
+ *   residual  (device) [M,N] fp16 or NULL;  gate (device) [M/gate_rows, N] fp16 or NULL
+ *   gate_rows: rows sharing one gate row (tokens per image); M % gate_rows == 0
+ * The GELU is evaluated in fp32 on the GPU (relative error about 1e-6 before the
+ * fp16 rounding).  fusion == NULL or all-zero gives the plain layer.  group: as in
+ * qlinear_w4a8_g.  Errors: QL_ERR_UNSUPPORTED for an unknown act, QL_ERR_SHAPE for
+ * a bad gate_rows, QL_ERR_ALIGN for odd pointers; the rest as the plain calls.
+ * ---------------------------------------------------------------------- */
+enum { QL_ACT_NONE = 0, QL_ACT_GELU_TANH = 1 };
+
+typedef struct ql_fusion {
+    int32_t act;
+    int32_t reserved;      /* 0 */
+    const void *residual;
+    const void *gate;
+    int64_t gate_rows;
+} ql_fusion;
+
+int qlinear_w8a8_fused(const void *x, int64_t M, int64_t K, int64_t R,
+                       const void *w, const void *w_scale, const void *bias, int64_t N,
+                       const ql_fusion *fusion, void *y,
+                       void *workspace, size_t workspace_bytes, void *stream);
+int qlinear_w4a8_fused(const void *x, int64_t M, int64_t K, int64_t R,
+                       const void *w4, const void *w_scale, int64_t group, const void *bias, int64_t N,
+                       const ql_fusion *fusion, void *y,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
 /* Host helper: pack int8 codes in [-8,7], [N,K] row-major (host), into the
  * 4-bit storage order described at qlinear_w4a8 ([N,K/2] bytes, host).
  * K % 8 == 0.  Returns QL_ERR_SHAPE for a code outside [-8,7]. */

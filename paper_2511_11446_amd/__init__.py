@@ -22,7 +22,7 @@ EXPORTS = ("ql_status_string", "ql_last_device_error", "ql_version", "daq_worksp
            "ql_pack_w4_host", "ql_plan_create", "ql_plan_destroy", "ql_plan_num_layers",
            "ql_plan_workspace_bytes", "qlinear_plan_run", "ql_set_gemm_variant", "ql_num_gemm_variants",
            "ql_gemm_variant_name", "ql_probe_mfma_int8", "daq_quantize_robust", "qlinear_plan_run_robust", "ql_time_bin",
-           "qlinear_w4a8_g", "qgemm_w4a8_g")
+           "qlinear_w4a8_g", "qgemm_w4a8_g", "qlinear_w8a8_fused", "qlinear_w4a8_fused")
 
 
 class QlError(RuntimeError):
@@ -91,6 +91,10 @@ def lib():
     L.qlinear_w4a8_g.restype = _int
     L.qgemm_w4a8_g.argtypes = [_vp, _vp, _i64, _i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp, _vp, _vp]
     L.qgemm_w4a8_g.restype = _int
+    L.qlinear_w8a8_fused.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _i64, ctypes.POINTER(ql_fusion), _vp, _vp, _sz, _vp]
+    L.qlinear_w8a8_fused.restype = _int
+    L.qlinear_w4a8_fused.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _i64, _vp, _i64, ctypes.POINTER(ql_fusion), _vp, _vp, _sz, _vp]
+    L.qlinear_w4a8_fused.restype = _int
     L.qlinear_plan_run_robust.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _i64, _i64, _vp, _vp, _sz, _vp]
     L.qlinear_plan_run_robust.restype = _int
     L.daq_quantize_robust.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -156,6 +160,41 @@ def daq_quantize(x, R, q=None, scales=None, ws=None, stream=None):
                             _stream(stream))
     _check(rc, "daq_quantize")
     return q, scales
+
+
+class ql_fusion(ctypes.Structure):
+    _fields_ = [("act", ctypes.c_int32), ("reserved", ctypes.c_int32), ("residual", ctypes.c_void_p),
+                ("gate", ctypes.c_void_p), ("gate_rows", ctypes.c_int64)]
+
+
+ACT_NONE, ACT_GELU_TANH = 0, 1
+
+
+def qlinear_fused(x, R, w, w_scale, bias=None, bits=8, group=128, act=ACT_NONE, residual=None, gate=None, gate_rows=1,
+                  y=None, ws=None, stream=None):
+    """The layer with activation, gate and residual folded into its epilogue:
+    h = fp16(act(u)); y = fp16(fma(gate, h, residual)).  bits = 8 (w int8 [N,K]) or 4 (w packed [N,K/2], group)."""
+    import torch
+    _need(x, torch.float16, name="x")
+    M, K = x.shape
+    N = w.shape[0]
+    if residual is not None:
+        _need(residual, torch.float16, (M, N), "residual")
+    if gate is not None:
+        _need(gate, torch.float16, (M // gate_rows, N), "gate")
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    if ws is None:
+        ws = workspace(qlinear_workspace_bytes(M, K, R), x.device)
+    fu = ql_fusion(act, 0, None if residual is None else residual.data_ptr(), None if gate is None else gate.data_ptr(), gate_rows)
+    if bits == 8:
+        rc = lib().qlinear_w8a8_fused(_ptr(x), M, K, R, _ptr(w), _ptr(w_scale), _ptr(bias), N, ctypes.byref(fu), _ptr(y),
+                                      _ptr(ws), ws.numel(), _stream(stream))
+    else:
+        rc = lib().qlinear_w4a8_fused(_ptr(x), M, K, R, _ptr(w), _ptr(w_scale), group, _ptr(bias), N, ctypes.byref(fu),
+                                      _ptr(y), _ptr(ws), ws.numel(), _stream(stream))
+    _check(rc, "qlinear_w%da8_fused" % bits)
+    return y
 
 
 class _DaqParams(ctypes.Structure):

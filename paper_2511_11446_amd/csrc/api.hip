@@ -95,7 +95,7 @@ int check_group(int64_t K, int64_t group)
 // DAQ then GEMM for one layer; all arguments already validated
 int run_layer(const void *x, int64_t M, int64_t K, int64_t R, int w_bits, const void *w, const void *w_scale,
               const void *bias, int64_t N, void *y, const ql_debug *dbg, void *workspace, hipStream_t stream,
-              const ql_daq_params *dp = nullptr, int64_t group = 128)
+              const ql_daq_params *dp = nullptr, int64_t group = 128, const ql_fusion *fu = nullptr)
 {
     const LayerWs lw = layer_ws(M, K, R);
     unsigned char *base = static_cast<unsigned char *>(workspace);
@@ -118,7 +118,7 @@ int run_layer(const void *x, int64_t M, int64_t K, int64_t R, int w_bits, const 
         rc = device_status(ql::launch_daq(d, stream));
     }
     if (rc) return rc;
-    ql::GemmArgs g;
+    ql::GemmArgs g{};
     g.q = d.q;
     g.s_a = d.scales;
     g.w = w;
@@ -132,7 +132,22 @@ int run_layer(const void *x, int64_t M, int64_t K, int64_t R, int w_bits, const 
     g.R = (int)R;
     g.w_bits = w_bits;
     g.group = (int)group;
+    if (fu) {
+        g.act = fu->act;
+        g.residual = fu->residual;
+        g.gate = fu->gate;
+        g.gate_rows = (int)fu->gate_rows;
+    }
     return device_status(ql::launch_qgemm(g, g_gemm_variant.load(), stream));
+}
+
+int check_fusion(const ql_fusion *fu, int64_t M)
+{
+    if (!fu) return QL_OK;
+    if (fu->act != QL_ACT_NONE && fu->act != QL_ACT_GELU_TANH) return QL_ERR_UNSUPPORTED;
+    if (misaligned(fu->residual, 2) || misaligned(fu->gate, 2)) return QL_ERR_ALIGN;
+    if (fu->gate && (fu->gate_rows < 1 || M % fu->gate_rows != 0)) return QL_ERR_SHAPE;
+    return QL_OK;
 }
 
 int check_layer_ptrs(const void *x, const void *w, const void *w_scale, const void *bias, const void *y,
@@ -147,11 +162,13 @@ int check_layer_ptrs(const void *x, const void *w, const void *w_scale, const vo
 
 int qlinear_any(int w_bits, const void *x, int64_t M, int64_t K, int64_t R, const void *w, const void *w_scale,
                 const void *bias, int64_t N, void *y, const ql_debug *dbg, void *workspace, size_t workspace_bytes,
-                void *stream, int64_t group = 128)
+                void *stream, int64_t group = 128, const ql_fusion *fu = nullptr)
 {
     int rc = check_layer_ptrs(x, w, w_scale, bias, y, dbg, w_bits);
     if (rc) return rc;
     rc = check_shape(M, K, R, N);
+    if (rc) return rc;
+    rc = check_fusion(fu, M);
     if (rc) return rc;
     if (w_bits == 4) {
         rc = check_group(K, group);
@@ -161,7 +178,7 @@ int qlinear_any(int w_bits, const void *x, int64_t M, int64_t K, int64_t R, cons
     rc = check_workspace(workspace, workspace_bytes, layer_ws(M, K, R).total);
     if (rc) return rc;
     return run_layer(x, M, K, R, w_bits, w, w_scale, bias, N, y, dbg, workspace, static_cast<hipStream_t>(stream), nullptr,
-                     group);
+                     group, fu);
 }
 
 int qgemm_any(int w_bits, const void *q, const void *a_scales, int64_t M, int64_t K, int64_t R, const void *w,
@@ -178,7 +195,7 @@ int qgemm_any(int w_bits, const void *q, const void *a_scales, int64_t M, int64_
         if (rc) return rc;
         if (acc && M > ELEMS_MAX / N / (K / group)) return QL_ERR_SHAPE;
     }
-    ql::GemmArgs g;
+    ql::GemmArgs g{};
     g.q = static_cast<const int8_t *>(q);
     g.s_a = static_cast<const float *>(a_scales);
     g.w = w;
@@ -300,6 +317,19 @@ int qlinear_w4a8_g(const void *x, int64_t M, int64_t K, int64_t R, const void *w
                    void *stream)
 {
     return qlinear_any(4, x, M, K, R, w4, w_scale, bias, N, y, dbg, workspace, workspace_bytes, stream, group);
+}
+
+int qlinear_w8a8_fused(const void *x, int64_t M, int64_t K, int64_t R, const void *w, const void *w_scale, const void *bias,
+                       int64_t N, const ql_fusion *fusion, void *y, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return qlinear_any(8, x, M, K, R, w, w_scale, bias, N, y, nullptr, workspace, workspace_bytes, stream, 128, fusion);
+}
+
+int qlinear_w4a8_fused(const void *x, int64_t M, int64_t K, int64_t R, const void *w4, const void *w_scale, int64_t group,
+                       const void *bias, int64_t N, const ql_fusion *fusion, void *y, void *workspace,
+                       size_t workspace_bytes, void *stream)
+{
+    return qlinear_any(4, x, M, K, R, w4, w_scale, bias, N, y, nullptr, workspace, workspace_bytes, stream, group, fusion);
 }
 
 int qgemm_w4a8_g(const void *q, const void *a_scales, int64_t M, int64_t K, int64_t R, const void *w4,

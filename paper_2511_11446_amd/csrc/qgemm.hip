@@ -36,6 +36,50 @@ __device__ __forceinline__ float half_to_float_dev(unsigned short h)
     return (float)__builtin_bit_cast(_Float16, h);
 }
 
+// ---- block glue folded into the epilogue: h = f16(act(u)); y = f16(fma(g, h, r)) -----------------------------------
+// GELU in its tanh form, written with the logistic function: u * sigmoid(2 z), z = sqrt(2/pi) (u + 0.044715 u^3).
+// This keeps the relative accuracy in the negative tail, where 1 + tanh z cancels.
+__device__ __forceinline__ float gelu_tanh_dev(float u)
+{
+    const float z = 0.7978845608028654f * (u + 0.044715f * u * u * u);
+    return u * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * z));
+}
+
+__device__ __forceinline__ bool has_glue(const GemmArgs &a) { return a.act != 0 || a.residual != nullptr || a.gate != nullptr; }
+
+// one element: u is the layer's fp32 value
+__device__ __forceinline__ _Float16 glue_one(const GemmArgs &a, float u, int m, int n)
+{
+    if (a.act == 1) u = gelu_tanh_dev(u);
+    asm volatile("" : "+v"(u));   // keep the fp32 value: it is rounded to fp16 here and nowhere earlier
+    _Float16 h = (_Float16)u;
+    if (a.residual || a.gate) {
+        const float g = a.gate ? half_to_float_dev(static_cast<const unsigned short *>(a.gate)[(size_t)(m / a.gate_rows) * a.N + n]) : 1.0f;
+        const float r = a.residual ? half_to_float_dev(static_cast<const unsigned short *>(a.residual)[(size_t)m * a.N + n]) : 0.0f;
+        float v = __builtin_fmaf(g, (float)h, r);
+        asm volatile("" : "+v"(v));
+        h = (_Float16)v;
+    }
+    return h;
+}
+
+// eight neighbouring elements of one row at once (16-byte pieces of the staged tile)
+__device__ __forceinline__ v4i glue_piece(const GemmArgs &a, v4i hv, int m, int n)
+{
+    typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+    h8 h = __builtin_bit_cast(h8, hv);
+    h8 g, r;
+    if (a.gate) g = *reinterpret_cast<const h8 *>(static_cast<const _Float16 *>(a.gate) + (size_t)(m / a.gate_rows) * a.N + n);
+    if (a.residual) r = *reinterpret_cast<const h8 *>(static_cast<const _Float16 *>(a.residual) + (size_t)m * a.N + n);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float v = __builtin_fmaf(a.gate ? (float)g[e] : 1.0f, (float)h[e], a.residual ? (float)r[e] : 0.0f);
+        asm volatile("" : "+v"(v));
+        h[e] = (_Float16)v;
+    }
+    return __builtin_bit_cast(v4i, h);
+}
+
 // Tile shape: a workgroup of WGM x WGN wavefronts, each owning TM x TN MFMA
 // tiles of 32x32, walks K in steps of BK int8.
 // WPS = wavefronts per SIMD the register budget must allow (512 / WPS registers per lane).
@@ -63,7 +107,7 @@ struct Tile {
     static_assert(BM * 4 <= 2 * A_BYTES, "row-scale staging reuses the A buffers");
 };
 
-template <class T>
+template <class T, bool GLUE = false>
 __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tiles_m, int tiles_n, int nblk_padded, int group_m)
 {
     constexpr int TM = T::TM, TN = T::TN, BK = T::BK, BM = T::BM, BN = T::BN, NT = T::NT;
@@ -290,7 +334,8 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
                             u = bias ? __builtin_fmaf(t, sw, b) : t * sw;
                             if (a.acc_out) a.acc_out[off] = acc[i][j][r];
                         }
-                        __builtin_nontemporal_store((_Float16)u, &y[off]);
+                        if (GLUE) __builtin_nontemporal_store(glue_one(a, u, m, n), &y[off]);
+                        else __builtin_nontemporal_store((_Float16)u, &y[off]);
                     }
                 }
         }
@@ -315,7 +360,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
 //   otherwise they are stored to global memory directly (64-byte row segments per half wavefront).
 template <int TM, int TN, bool STAGED, int ROWS = 32, class ValueFn>
 __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane, _Float16 *y, int N, int m_base, int n_base,
-                                                  ValueFn value)
+                                                  ValueFn value, const GemmArgs *glue = nullptr)
 {
     constexpr int PITCH = TN * 64 + 16;
     constexpr int CH = TN * 4;  // 16-byte pieces per row
@@ -358,7 +403,9 @@ __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane
                 for (int t = 0; t < ROWS * CH / 64; ++t) {
                     const int id = lane + 64 * t;
                     const int row = id / CH, ch = id % CH;
-                    const v4i v = *reinterpret_cast<const v4i_alias *>(strip + row * PITCH + ch * 16);
+                    v4i v = *reinterpret_cast<const v4i_alias *>(strip + row * PITCH + ch * 16);
+                    // gate and residual meet the fp16 result here, eight elements of a row at a time
+                    if (glue) v = glue_piece(*glue, v, m_base + i * 32 + h * ROWS + row, n_base + ch * 8);
                     // the output is written once and not read again by this kernel: keep it from displacing the operand panels in L2
                     __builtin_nontemporal_store(v, reinterpret_cast<v4i_alias *>(y + (unsigned)((m_base + i * 32 + h * ROWS + row) * N + n_base + ch * 8)));
                 }
@@ -423,7 +470,7 @@ struct TileD {
 typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void global_void;
 
-template <class T>
+template <class T, bool GLUE = false>
 __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles_m, int tiles_n, int nblk_padded, int group_m)
 {
     constexpr int TM = T::TM, TN = T::TN, BM = T::BM, BN = T::BN, NT = T::NT, NW = T::NW;
@@ -742,7 +789,11 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     _Float16 *y = static_cast<_Float16 *>(a.y);
     const unsigned short *bias = static_cast<const unsigned short *>(a.bias);
     const bool full = (em0 + BM <= M) && (en0 + BN <= N);
-    if (full && (N % 8) == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0 && (W4 || !a.acc_out)) {
+    const bool glue_pieces = GLUE && (a.residual || a.gate);
+    const bool glue_aligned = !glue_pieces || (((reinterpret_cast<uintptr_t>(a.residual) | reinterpret_cast<uintptr_t>(a.gate)) & 15) == 0);
+    auto act_of = [&](float u) { return (GLUE && a.act == 1) ? gelu_tanh_dev(u) : u; };
+    if (full && (N % 8) == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0 && (W4 || !a.acc_out) && glue_aligned) {
+        const GemmArgs *gl = glue_pieces ? &a : nullptr;
         unsigned char *strip = smem + T::EPI_OFF + T::STRIP_OFF + wave * T::STRIP_BYTES;
         // the 16 row scales of each 32-row block of this lane (rows 8g + 4*frag_half + 0..3), read once as 4 x 16 bytes
         float sr[TM * 16];
@@ -761,20 +812,20 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
         }
         if (W4 && bias)
             store_tile_staged<TM, TN, T::STAGED_STORE, T::STRIP_ROWS>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
-                return __builtin_fmaf(fsum[W4 ? i : 0][W4 ? j : 0][r], sr[i * 16 + r], bj[j]);
-            });
+                return act_of(__builtin_fmaf(fsum[W4 ? i : 0][W4 ? j : 0][r], sr[i * 16 + r], bj[j]));
+            }, gl);
         else if (W4)
             store_tile_staged<TM, TN, T::STAGED_STORE, T::STRIP_ROWS>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
-                return fsum[W4 ? i : 0][W4 ? j : 0][r] * sr[i * 16 + r];
-            });
+                return act_of(fsum[W4 ? i : 0][W4 ? j : 0][r] * sr[i * 16 + r]);
+            }, gl);
         else if (bias)
             store_tile_staged<TM, TN, T::STAGED_STORE, T::STRIP_ROWS>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
-                return __builtin_fmaf((float)acc[i][j][r] * sr[i * 16 + r], swt[j], bj[j]);
-            });
+                return act_of(__builtin_fmaf((float)acc[i][j][r] * sr[i * 16 + r], swt[j], bj[j]));
+            }, gl);
         else
             store_tile_staged<TM, TN, T::STAGED_STORE, T::STRIP_ROWS>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
-                return (float)acc[i][j][r] * sr[i * 16 + r] * swt[j];
-            });
+                return act_of((float)acc[i][j][r] * sr[i * 16 + r] * swt[j]);
+            }, gl);
     } else {
         auto emit = [&](auto edge) {
             constexpr bool EDGE = decltype(edge)::value;
@@ -801,7 +852,8 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
                                 if (a.acc_out) a.acc_out[off] = acc[i][j][r];
                             }
                             asm volatile("" : "+v"(u));   // keep the fp32 rounding before the fp16 one
-                            y[off] = (_Float16)u;
+                            if (GLUE) y[off] = glue_one(a, u, m, n);
+                            else y[off] = (_Float16)u;
                         }
                     }
             }
@@ -815,13 +867,13 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     }
 }
 
-template <class T>
+template <class T, bool GLUE = false>
 static hipError_t run_dma(const GemmArgs &a, hipStream_t s)
 {
     static bool attr_set = false;
     if (!attr_set) {
         if (T::LDS_BYTES > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&qgemm_dma<T>),
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&qgemm_dma<T, GLUE>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
             if (e != hipSuccess) return e;
         }
@@ -845,7 +897,7 @@ static hipError_t run_dma(const GemmArgs &a, hipStream_t s)
         }
         if (grid > resident) grid = resident;
     }
-    hipLaunchKernelGGL(qgemm_dma<T>, dim3(grid), dim3(T::NT), T::LDS_BYTES, s, a, tiles_m, tiles_n, padded, pick_group_m(tiles_m, tiles_n));
+    hipLaunchKernelGGL((qgemm_dma<T, GLUE>), dim3(grid), dim3(T::NT), T::LDS_BYTES, s, a, tiles_m, tiles_n, padded, pick_group_m(tiles_m, tiles_n));
     return hipGetLastError();
 }
 
@@ -887,17 +939,17 @@ __global__ __launch_bounds__(256) void qgemm_naive(GemmArgs a)
         }
         u = bias ? __builtin_fmaf(f, sa, b) : f * sa;
     }
-    static_cast<_Float16 *>(a.y)[(size_t)m * a.N + n] = (_Float16)u;
+    static_cast<_Float16 *>(a.y)[(size_t)m * a.N + n] = has_glue(a) ? glue_one(a, u, m, n) : (_Float16)u;
 }
 
 // ---- variants -----------------------------------------------------------------
-template <class T>
+template <class T, bool GLUE = false>
 static hipError_t run_variant(const GemmArgs &a, hipStream_t s)
 {
     static bool attr_set = false;  // per variant; LDS above 64 KB needs the opt-in once
     if (!attr_set) {
         if (T::LDS_BYTES > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&qgemm_mfma<T>),
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&qgemm_mfma<T, GLUE>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
             if (e != hipSuccess) return e;
         }
@@ -906,7 +958,7 @@ static hipError_t run_variant(const GemmArgs &a, hipStream_t s)
     const int tiles_m = (a.M + T::BM - 1) / T::BM, tiles_n = (a.N + T::BN - 1) / T::BN;
     const int nblk = tiles_m * tiles_n;
     const int padded = (nblk + XCDS - 1) / XCDS * XCDS;
-    hipLaunchKernelGGL(qgemm_mfma<T>, dim3(padded), dim3(T::NT), T::LDS_BYTES, s, a, tiles_m, tiles_n, padded, pick_group_m(tiles_m, tiles_n));
+    hipLaunchKernelGGL((qgemm_mfma<T, GLUE>), dim3(padded), dim3(T::NT), T::LDS_BYTES, s, a, tiles_m, tiles_n, padded, pick_group_m(tiles_m, tiles_n));
     return hipGetLastError();
 }
 
@@ -914,6 +966,7 @@ struct Variant {
     const char *name;
     int w_bits, BM, BN, BK;   // BK: K must be a multiple of this
     hipError_t (*run)(const GemmArgs &, hipStream_t);
+    hipError_t (*run_glue)(const GemmArgs &, hipStream_t) = nullptr;   // the same tile with block glue in the epilogue (shape-chosen variants only)
 };
 
 //                         TM TN WGM WGN BK  W4  WPS
@@ -972,22 +1025,22 @@ static const Variant VARIANTS[] = {
     {"w8 dma 256x256 s2 4w", 8, 256, 256, 128, run_dma<D8_256x256_s2>},
     {"w8 dma 256x256 s2 8w", 8, 256, 256, 128, run_dma<D8_256x256_8w>},
     {"w8 dma 256x192 s2 8w", 8, 256, 192, 128, run_dma<D8_256x192_8w>},
-    {"w8 dma 64x64 s4 4w", 8, 64, 64, 128, run_dma<D8_64x64_s4>},
+    {"w8 dma 64x64 s4 4w", 8, 64, 64, 128, run_dma<D8_64x64_s4>, run_dma<D8_64x64_s4, true>},
     {"w8 dma 256x192 s2 8w spread1", 8, 256, 192, 128, run_dma<D8_256x192_8w_e1>},
     {"w8 dma 256x256 s2 8w spread1", 8, 256, 256, 128, run_dma<D8_256x256_8w_e1>},
     {"w8 dma 256x256 s2 8w spread2", 8, 256, 256, 128, run_dma<D8_256x256_8w_e2>},
     {"w8 dma 256x192 s2 4w spread2", 8, 256, 192, 128, run_dma<D8_256x192_4w_e2>},
     {"w4 dma 128x128 s2 4w", 4, 128, 128, 128, run_dma<D4_128x128_4w>},
-    {"w8 dma 256x192 a3b2 8w spread1", 8, 256, 192, 128, run_dma<D8_256x192_8w_a3b2>},
+    {"w8 dma 256x192 a3b2 8w spread1", 8, 256, 192, 128, run_dma<D8_256x192_8w_a3b2>, run_dma<D8_256x192_8w_a3b2, true>},
     {"w8 dma 256x192 a2b3 8w spread1", 8, 256, 192, 128, run_dma<D8_256x192_8w_a2b3>},
     {"w8 dma 256x256 a3b2 8w spread1", 8, 256, 256, 128, run_dma<D8_256x256_8w_a3b2>},
-    {"w8 dma 128x128 a3b2 4w", 8, 128, 128, 128, run_dma<D8_128x128_a3b2>},
-    {"w8 dma 128x128 a3b2 4w spread1", 8, 128, 128, 128, run_dma<D8_128x128_a3b2_e1>},
+    {"w8 dma 128x128 a3b2 4w", 8, 128, 128, 128, run_dma<D8_128x128_a3b2>, run_dma<D8_128x128_a3b2, true>},
+    {"w8 dma 128x128 a3b2 4w spread1", 8, 128, 128, 128, run_dma<D8_128x128_a3b2_e1>, run_dma<D8_128x128_a3b2_e1, true>},
     {"w8 dma 128x128 s2 4w spread1", 8, 128, 128, 128, run_dma<D8_128x128_s2_e1>},
     {"w8 dma 256x192 a3b2 8w spread1 persistent", 8, 256, 192, 128, run_dma<P8_256x192_a3b2>},
     {"w8 dma 256x256 a3b2 8w spread1 persistent", 8, 256, 256, 128, run_dma<P8_256x256_a3b2>},
-    {"w8 dma 128x128 a3b2 4w spread1 persistent", 8, 128, 128, 128, run_dma<P8_128x128_a3b2>},
-    {"w8 dma 128x192 s2 4w spread1 persistent", 8, 128, 192, 128, run_dma<P8_128x192_s2>},
+    {"w8 dma 128x128 a3b2 4w spread1 persistent", 8, 128, 128, 128, run_dma<P8_128x128_a3b2>, run_dma<P8_128x128_a3b2, true>},
+    {"w8 dma 128x192 s2 4w spread1 persistent", 8, 128, 192, 128, run_dma<P8_128x192_s2>, run_dma<P8_128x192_s2, true>},
     {"w8 128x128 bk64 4w occ2", 8, 128, 128, 64, run_variant<W8_128x128_k64>},
     {"w8 128x128 bk128 4w occ2", 8, 128, 128, 128, run_variant<W8_128x128_k128>},
     {"w8 256x128 bk64 4w occ2", 8, 256, 128, 64, run_variant<W8_256x128_k64>},
@@ -996,12 +1049,12 @@ static const Variant VARIANTS[] = {
     {"w8 256x192 bk64 4w occ1", 8, 256, 192, 64, run_variant<W8_256x192_k64>},
     {"w8 256x256 bk64 8w occ2", 8, 256, 256, 64, run_variant<W8_256x256_8w>},
     {"w8 64x64 bk64 4w occ4", 8, 64, 64, 64, run_variant<W8_64x64_k64>},
-    {"w8 128x128 bk64 4w occ3", 8, 128, 128, 64, run_variant<W8_128x128_k64_o3>},
+    {"w8 128x128 bk64 4w occ3", 8, 128, 128, 64, run_variant<W8_128x128_k64_o3>, run_variant<W8_128x128_k64_o3, true>},
     {"w4 128x128 bk128 4w occ2", 4, 128, 128, 128, run_variant<W4_128x128_k128>},
     {"w4 64x128 bk128 4w occ2", 4, 64, 128, 128, run_variant<W4_64x128_k128>},
     {"w4 256x128 bk128 8w occ2", 4, 256, 128, 128, run_variant<W4_256x128_8w>},
     {"w4 128x64 bk128 4w occ3", 4, 128, 64, 128, run_variant<W4_128x64_k128>},
-    {"w4 any-group 128x64 bk128 4w occ3", 4, 128, 64, 128, run_variant<W4G_128x64_k128>},
+    {"w4 any-group 128x64 bk128 4w occ3", 4, 128, 64, 128, run_variant<W4G_128x64_k128>, run_variant<W4G_128x64_k128, true>},
     {"w4 any-group 128x128 bk128 4w occ2", 4, 128, 128, 128, run_variant<W4G_128x128_k128>},
 };
 constexpr int NUM_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);
@@ -1062,6 +1115,11 @@ hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream)
         // the pipelined 4-bit kernel keeps the group scales of a tile in LDS: at most 40 groups (K <= 5120)
         if (a.K > 128 * 40 && __builtin_strncmp(VARIANTS[v].name, "w4 dma", 6) == 0)
             v = find_variant("w4 128x64 bk128 4w occ3");
+    }
+    if (a.act != 0 || a.residual != nullptr || a.gate != nullptr) {
+        // block glue in the epilogue: only the shape-chosen tiles carry it
+        if (!VARIANTS[v].run_glue) v = choose_variant(a);
+        return VARIANTS[v].run_glue(a, stream);
     }
     return VARIANTS[v].run(a, stream);
 }

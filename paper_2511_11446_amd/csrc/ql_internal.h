@@ -55,6 +55,11 @@ struct GemmArgs {
     int M, N, K, R;
     int w_bits;           // 8 or 4
     int group;            // 4-bit weights: k per weight scale (a multiple of 32 dividing K); 128 unless stated
+    // block glue folded into the epilogue (all zero = none):  h = f16(act(u));  y = f16(fma(g, h, r))
+    int act;              // 0 identity, 1 GELU (tanh form) on the fp32 value u
+    const void *residual; // fp16 [M,N] r, or null (0)
+    const void *gate;     // fp16 [M/gate_rows, N] g, or null (1)
+    int gate_rows;        // rows sharing one gate row
 };
 
 int num_gemm_variants();

@@ -189,3 +189,16 @@ def test_group_size_argument_checks():
     assert L.qlinear_w4a8_g(*args(100, 100)) == 4
     assert L.qgemm_w4a8_g(FAKE, FAKE, 4, 1152, 1, FAKE, FAKE, 48, None, 8, FAKE, None, None) == 4
     assert L.qgemm_w4a8_g(FAKE, FAKE, 4, 1152, 1, FAKE, FAKE, 256, None, 8, FAKE, None, None) == 2
+
+
+def test_fused_epilogue_argument_checks():
+    L = ql.lib()
+    ws = ctypes.c_void_p(0x10000)
+    big = 1 << 30
+    def call(fu, M=8):
+        return L.qlinear_w8a8_fused(FAKE, M, 64, 1, FAKE, FAKE, None, 8, ctypes.byref(fu) if fu else None, FAKE, ws, big, None)
+    assert call(ql.ql_fusion(7, 0, None, None, 1)) == 4                       # unknown activation
+    assert call(ql.ql_fusion(0, 0, 0x1001, None, 1)) == 3                     # odd residual pointer
+    assert call(ql.ql_fusion(0, 0, None, 0x1000, 3)) == 2                     # M % gate_rows
+    assert call(ql.ql_fusion(0, 0, None, 0x1000, 0)) == 2
+    assert L.qlinear_w4a8_fused(FAKE, 8, 1152, 1, FAKE, FAKE, 48, None, 8, None, FAKE, ws, big, None) == 4   # bad group

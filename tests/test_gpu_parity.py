@@ -565,6 +565,84 @@ def test_plan_with_mixed_group_sizes(gpu, orc):
     plan.close()
 
 
+# ------------------------------------------------------------------ block glue folded into the epilogue
+
+def _glue_reference(orc, x, R, lw, bits, group, act, residual, gate, gate_rows):
+    q, s = orc.daq(x, R, nthreads=8)
+    if bits == 8:
+        u = orc.dequant_w8(orc.gemm_i8(q, lw["w"], nthreads=8), s, R, lw["s_w"], lw["bias"])
+    else:
+        u = orc.dequant_w4(orc.gemm_w4g(q, orc.pack_w4(lw["w"]), group, nthreads=8), s, R, lw["s_w"], lw["bias"])
+    return orc.block_glue(u, act=act, residual=residual, gate=gate, gate_rows=gate_rows)
+
+
+GLUE_CASES = [
+    # M, K, N, R, bits, group, act, residual, gate_rows (0 = no gate)
+    (512, 1152, 384, 1, 8, 0, 1, False, 0),       # fc1-like: GELU only, full tiles
+    (512, 1152, 384, 1, 8, 0, 0, True, 256),      # proj-like: gated residual
+    (512, 1152, 384, 1, 8, 0, 1, True, 256),      # everything at once
+    (300, 1152, 200, 1, 8, 0, 1, True, 100),      # ragged M and N: element-wise epilogue
+    (256, 1152, 256, 1, 8, 0, 0, True, 0),        # plain residual
+    (256, 1152, 256, 1, 8, 0, 0, False, 64),      # gate alone
+    (64, 200, 48, 1, 8, 0, 1, True, 32),          # generic kernel (K % 64 != 0)
+    (256, 1152, 256, 1, 4, 128, 1, True, 256),    # 4-bit weights
+    (256, 1152, 192, 1, 4, 288, 0, True, 128),    # 4-bit, group 288
+    (4096, 1152, 1152, 1, 8, 0, 0, True, 1024),   # persistent 128x192 tiles
+    (4096, 1152, 3456, 1, 8, 0, 1, False, 0),     # persistent 128x128 tiles
+    (256, 4608, 384, 256, 8, 0, 0, True, 256),    # K = 4608, per-sample scales
+]
+
+
+@pytest.mark.parametrize("M,K,N,R,bits,group,act,use_res,gate_rows", GLUE_CASES)
+def test_fused_epilogue(gpu, orc, M, K, N, R, bits, group, act, use_res, gate_rows):
+    say("glue", M, K, N, R, bits, group, act, use_res, gate_rows)
+    x = workload.activations(M, K, "glue", N, bits)
+    lw = workload.layer_weights("glue", K, N, bits, "glue")
+    if bits == 4 and group != 128:
+        lw = dict(lw, s_w=workload.w4_scales_group(N, K, group, "glue"))
+    g = workload.rng("glue-rg", M, N)
+    residual = (g.standard_normal((M, N), dtype=np.float32) * 2).astype(np.float16) if use_res else None
+    gate = (g.standard_normal((M // gate_rows, N), dtype=np.float32)).astype(np.float16) if gate_rows else None
+    ref = _glue_reference(orc, x, R, lw, bits, group, act, residual, gate, max(gate_rows, 1))
+    w = dev(lw["w"]) if bits == 8 else dev(gpu.ql_pack_w4_host(lw["w"]))
+    y = gpu.qlinear_fused(dev(x), R, w, dev(lw["s_w"]), dev(lw["bias"]), bits=bits, group=group or 128, act=act,
+                          residual=None if residual is None else dev(residual), gate=None if gate is None else dev(gate),
+                          gate_rows=max(gate_rows, 1))
+    if act == 0:
+        assert assert_y_close(host(y), ref) == 0          # no transcendental involved: identical
+        return
+    # fp32 GELU on the GPU against the oracle's fp64 one: h = fp16(gelu(u)) may differ by one fp16 ulp in rare elements.
+    # Through the gated addition that is an ABSOLUTE error of |g| ulp(h), which a small |y| (cancellation against the
+    # residual) does not shrink: the bound below is 1e-3 relative on y plus one ulp of h carried through the gate.
+    yg = host(y).astype(np.float64)
+    h_ref = _glue_reference(orc, x, R, lw, bits, group, act, None, None, 1).astype(np.float64)
+    gabs = np.abs(np.repeat(gate.astype(np.float64), gate_rows, 0)) if gate is not None else 1.0
+    tol = 1e-3 * np.abs(ref.astype(np.float64)) + gabs * np.abs(h_ref) * 2.0 ** -10 + 2.0 ** -24
+    assert (np.abs(yg - ref.astype(np.float64)) <= tol).all()
+    ndiff = int((host(y).view(np.uint16) != ref.view(np.uint16)).sum())
+    assert ndiff <= max(4, y.numel() // 500)              # and such elements are rare
+
+
+def test_fused_epilogue_with_nothing_to_fuse_is_the_plain_layer_and_misaligned_glue_still_works(gpu, orc):
+    import torch
+    M, K, N = 256, 1152, 256
+    x = workload.activations(M, K, "glue0")
+    lw = workload.layer_weights("glue0", K, N, 8, "glue0")
+    plain = gpu.qlinear_w8a8(dev(x), 1, dev(lw["w"]), dev(lw["s_w"]), dev(lw["bias"]))
+    fused = gpu.qlinear_fused(dev(x), 1, dev(lw["w"]), dev(lw["s_w"]), dev(lw["bias"]))
+    assert torch.equal(plain, fused)
+    # a residual that starts 2 bytes off a 16-byte boundary: the 16-byte piece path must step aside
+    res = (workload.rng("glue-mis").standard_normal((M, N), dtype=np.float32)).astype(np.float16)
+    buf = torch.zeros(M * N + 8, dtype=torch.float16, device="cuda")
+    view = buf[1:1 + M * N].view(M, N)
+    view.copy_(dev(res))
+    assert view.data_ptr() % 16 == 2
+    y = gpu.qlinear_fused(dev(x), 1, dev(lw["w"]), dev(lw["s_w"]), dev(lw["bias"]), residual=view)
+    q, s = orc.daq(x, 1)
+    ref = orc.block_glue(orc.dequant_w8(orc.gemm_i8(q, lw["w"]), s, 1, lw["s_w"], lw["bias"]), residual=res)
+    assert assert_y_close(host(y), ref) == 0
+
+
 # ------------------------------------------------------------------ plan runner
 
 def test_plan_runner_small_mixed_plan(gpu, orc):
