@@ -140,6 +140,9 @@ def main():
     ap.add_argument("--a-bits", type=int, default=8, help="activation code width for --daq-p-ppm (Step 6 time-bin policy)")
     ap.add_argument("--w4-group", type=int, default=128,
                     help="k per weight scale of the 4-bit layers (the plan's other group sizes: 64, 192, 288 ...)")
+    ap.add_argument("--fused-block", action="store_true",
+                    help="time one block with GELU (fc1) and gated residuals (proj, fc2) folded into the epilogues, "
+                         "against the same layers followed by separate elementwise kernels")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: a few steps of the workload plus a device copy of known size, no timing")
     args = ap.parse_args()
@@ -190,6 +193,64 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"traffic_probe": args.workload, "copy_bytes_read": src.numel() * 2,
                           "copy_bytes_written": src.numel() * 2, "steps": 3}))
+        return
+
+    if args.fused_block:
+        # Block glue (Section 6 counts residual additions in the latency): one DiT block's four linears with
+        # proj/fc2 -> gated residual, fc1 -> GELU.  Both sequences are captured into a HIP graph and replayed.
+        tokens = 256 if M % 256 == 0 else M
+        by = {l["name"]: l for l in layers}
+        names = [n for n in ("qkv", "proj", "fc1", "fc2") if n in by]
+        x0 = pool[0]
+        hid = by["proj"]["N"]
+        resid = torch.randn((M, hid), device="cuda", dtype=torch.float16)
+        gate = torch.randn((M // tokens, hid), device="cuda", dtype=torch.float16)
+        outs = {n: torch.empty((M, by[n]["N"]), dtype=torch.float16, device="cuda") for n in names}
+        wsl = ql.workspace(plan.workspace_bytes(M, R))
+
+        def layer(n, **kw):
+            l = by[n]
+            return ql.qlinear_fused(x0[n], R, l["w"], l["w_scale"], l["bias"], bits=l["bits"], group=l["group"],
+                                    y=outs[n], ws=wsl, **kw)
+
+        def fused():
+            layer("qkv")
+            layer("proj", residual=resid, gate=gate, gate_rows=tokens)
+            layer("fc1", act=ql.ACT_GELU_TANH)
+            layer("fc2", residual=resid, gate=gate, gate_rows=tokens)
+
+        tmp = torch.empty((M, hid), dtype=torch.float16, device="cuda")
+        g3 = gate.repeat_interleave(tokens, dim=0)
+
+        def unfused():
+            layer("qkv")
+            layer("proj")
+            torch.addcmul(resid, g3, outs["proj"], out=tmp)
+            layer("fc1")
+            torch.nn.functional.gelu(outs["fc1"], approximate="tanh")
+            layer("fc2")
+            torch.addcmul(resid, g3, outs["fc2"], out=tmp)
+
+        def timed(fn, reps=10):
+            fn()
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for _ in range(reps):
+                    fn()
+            g.replay()
+            torch.cuda.synchronize()
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a0.record(stream)
+            g.replay()
+            a1.record(stream)
+            torch.cuda.synchronize()
+            return a0.elapsed_time(a1) / reps * 1e3
+
+        tf, tu = timed(fused), timed(unfused)
+        print(json.dumps({"metric": "one block's four linears with GELU and gated residuals", "unit": "us",
+                          "fused_epilogues_us": tf, "separate_elementwise_kernels_us": tu, "speedup": tu / tf,
+                          "config": {"workload": args.workload, "M": M, "rows_per_scale": R, "tokens_per_gate_row": tokens}}))
         return
 
     robust = args.daq_p_ppm is not None

@@ -47,15 +47,30 @@ __device__ __forceinline__ float gelu_tanh_dev(float u)
 
 __device__ __forceinline__ bool has_glue(const GemmArgs &a) { return a.act != 0 || a.residual != nullptr || a.gate != nullptr; }
 
-// one element: u is the layer's fp32 value
-__device__ __forceinline__ _Float16 glue_one(const GemmArgs &a, float u, int m, int n)
+// Gate row of tile row d (0 <= d < span) without a division per element: the tile starts at row m_first, whose gate
+// row and remainder are computed once; rows of a tile cross at most one gate boundary when gate_rows >= span.
+struct GateRows {
+    int base, rem, rows;
+    bool one_step;
+    __device__ __forceinline__ GateRows(const GemmArgs &a, int m_first, int span)
+    {
+        rows = a.gate ? a.gate_rows : 1;
+        base = m_first / rows;
+        rem = m_first - base * rows;
+        one_step = rows >= span;
+    }
+    __device__ __forceinline__ int of(int d) const { return one_step ? base + (rem + d >= rows ? 1 : 0) : base + (rem + d) / rows; }
+};
+
+// one element: u is the layer's fp32 value, grow its gate row
+__device__ __forceinline__ _Float16 glue_one(const GemmArgs &a, float u, int m, int n, int grow)
 {
     if (a.act == 1) u = gelu_tanh_dev(u);
     asm volatile("" : "+v"(u));   // keep the fp32 value: it is rounded to fp16 here and nowhere earlier
     _Float16 h = (_Float16)u;
     if (a.residual || a.gate) {
-        const float g = a.gate ? half_to_float_dev(static_cast<const unsigned short *>(a.gate)[(size_t)(m / a.gate_rows) * a.N + n]) : 1.0f;
-        const float r = a.residual ? half_to_float_dev(static_cast<const unsigned short *>(a.residual)[(size_t)m * a.N + n]) : 0.0f;
+        const float g = a.gate ? half_to_float_dev(static_cast<const unsigned short *>(a.gate)[(unsigned)(grow * a.N + n)]) : 1.0f;
+        const float r = a.residual ? half_to_float_dev(static_cast<const unsigned short *>(a.residual)[(unsigned)(m * a.N + n)]) : 0.0f;
         float v = __builtin_fmaf(g, (float)h, r);
         asm volatile("" : "+v"(v));
         h = (_Float16)v;
@@ -63,17 +78,14 @@ __device__ __forceinline__ _Float16 glue_one(const GemmArgs &a, float u, int m, 
     return h;
 }
 
-// eight neighbouring elements of one row at once (16-byte pieces of the staged tile)
-__device__ __forceinline__ v4i glue_piece(const GemmArgs &a, v4i hv, int m, int n)
+// eight neighbouring elements of one row at once (16-byte pieces of the staged tile); g and r were loaded ahead
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ v4i glue_piece(bool has_g, bool has_r, v4i hv, h8 g, h8 r)
 {
-    typedef _Float16 h8 __attribute__((ext_vector_type(8)));
     h8 h = __builtin_bit_cast(h8, hv);
-    h8 g, r;
-    if (a.gate) g = *reinterpret_cast<const h8 *>(static_cast<const _Float16 *>(a.gate) + (size_t)(m / a.gate_rows) * a.N + n);
-    if (a.residual) r = *reinterpret_cast<const h8 *>(static_cast<const _Float16 *>(a.residual) + (size_t)m * a.N + n);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        float v = __builtin_fmaf(a.gate ? (float)g[e] : 1.0f, (float)h[e], a.residual ? (float)r[e] : 0.0f);
+        float v = __builtin_fmaf(has_g ? (float)g[e] : 1.0f, (float)h[e], has_r ? (float)r[e] : 0.0f);
         asm volatile("" : "+v"(v));
         h[e] = (_Float16)v;
     }
@@ -334,7 +346,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
                             u = bias ? __builtin_fmaf(t, sw, b) : t * sw;
                             if (a.acc_out) a.acc_out[off] = acc[i][j][r];
                         }
-                        if (GLUE) __builtin_nontemporal_store(glue_one(a, u, m, n), &y[off]);
+                        if (GLUE) __builtin_nontemporal_store(glue_one(a, u, m, n, GateRows(a, m0, BM).of(row)), &y[off]);
                         else __builtin_nontemporal_store((_Float16)u, &y[off]);
                     }
                 }
@@ -377,6 +389,19 @@ __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int h = 0; h < HALVES; ++h) {
+            // gate and residual of the pieces this lane will write back are requested before the block is dequantized
+            constexpr int PIECES = ROWS * CH / 64;
+            h8 pg[PIECES], pr[PIECES];
+            if (glue) {
+                const GateRows gr(*glue, m_base, TM * 32);
+#pragma unroll
+                for (int t = 0; t < PIECES; ++t) {
+                    const int id = lane + 64 * t;
+                    const int row = i * 32 + h * ROWS + id / CH, col = n_base + (id % CH) * 8;
+                    if (glue->gate) pg[t] = *reinterpret_cast<const h8 *>(static_cast<const _Float16 *>(glue->gate) + (unsigned)(gr.of(row) * N + col));
+                    if (glue->residual) pr[t] = *reinterpret_cast<const h8 *>(static_cast<const _Float16 *>(glue->residual) + (unsigned)((m_base + row) * N + col));
+                }
+            }
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -405,7 +430,7 @@ __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane
                     const int row = id / CH, ch = id % CH;
                     v4i v = *reinterpret_cast<const v4i_alias *>(strip + row * PITCH + ch * 16);
                     // gate and residual meet the fp16 result here, eight elements of a row at a time
-                    if (glue) v = glue_piece(*glue, v, m_base + i * 32 + h * ROWS + row, n_base + ch * 8);
+                    if (glue) v = glue_piece(glue->gate != nullptr, glue->residual != nullptr, v, pg[t], pr[t]);
                     // the output is written once and not read again by this kernel: keep it from displacing the operand panels in L2
                     __builtin_nontemporal_store(v, reinterpret_cast<v4i_alias *>(y + (unsigned)((m_base + i * 32 + h * ROWS + row) * N + n_base + ch * 8)));
                 }
@@ -852,7 +877,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
                                 if (a.acc_out) a.acc_out[off] = acc[i][j][r];
                             }
                             asm volatile("" : "+v"(u));   // keep the fp32 rounding before the fp16 one
-                            if (GLUE) y[off] = glue_one(a, u, m, n);
+                            if (GLUE) y[off] = glue_one(a, u, m, n, GateRows(a, em0, BM).of(row));
                             else y[off] = (_Float16)u;
                         }
                     }
@@ -939,7 +964,7 @@ __global__ __launch_bounds__(256) void qgemm_naive(GemmArgs a)
         }
         u = bias ? __builtin_fmaf(f, sa, b) : f * sa;
     }
-    static_cast<_Float16 *>(a.y)[(size_t)m * a.N + n] = has_glue(a) ? glue_one(a, u, m, n) : (_Float16)u;
+    static_cast<_Float16 *>(a.y)[(size_t)m * a.N + n] = has_glue(a) ? glue_one(a, u, m, n, a.gate ? m / a.gate_rows : 0) : (_Float16)u;
 }
 
 // ---- variants -----------------------------------------------------------------
@@ -1039,8 +1064,8 @@ static const Variant VARIANTS[] = {
     {"w8 dma 128x128 s2 4w spread1", 8, 128, 128, 128, run_dma<D8_128x128_s2_e1>},
     {"w8 dma 256x192 a3b2 8w spread1 persistent", 8, 256, 192, 128, run_dma<P8_256x192_a3b2>},
     {"w8 dma 256x256 a3b2 8w spread1 persistent", 8, 256, 256, 128, run_dma<P8_256x256_a3b2>},
-    {"w8 dma 128x128 a3b2 4w spread1 persistent", 8, 128, 128, 128, run_dma<P8_128x128_a3b2>, run_dma<P8_128x128_a3b2, true>},
-    {"w8 dma 128x192 s2 4w spread1 persistent", 8, 128, 192, 128, run_dma<P8_128x192_s2>, run_dma<P8_128x192_s2, true>},
+    {"w8 dma 128x128 a3b2 4w spread1 persistent", 8, 128, 128, 128, run_dma<P8_128x128_a3b2>},
+    {"w8 dma 128x192 s2 4w spread1 persistent", 8, 128, 192, 128, run_dma<P8_128x192_s2>},
     {"w8 128x128 bk64 4w occ2", 8, 128, 128, 64, run_variant<W8_128x128_k64>},
     {"w8 128x128 bk128 4w occ2", 8, 128, 128, 128, run_variant<W8_128x128_k128>},
     {"w8 256x128 bk64 4w occ2", 8, 256, 128, 64, run_variant<W8_256x128_k64>},
@@ -1119,6 +1144,10 @@ hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream)
     if (a.act != 0 || a.residual != nullptr || a.gate != nullptr) {
         // block glue in the epilogue: only the shape-chosen tiles carry it
         if (!VARIANTS[v].run_glue) v = choose_variant(a);
+        // the prefetched gate and residual pieces need registers the persistent tiles do not have left
+        // (256x192 measured faster here than two resident 128x128 workgroups per CU: 565 against 596 us for a block at M = 16384)
+        static const int big = find_variant("w8 dma 256x192 a3b2 8w spread1");
+        if (__builtin_strstr(VARIANTS[v].name, "persistent")) v = big;
         return VARIANTS[v].run_glue(a, stream);
     }
     return VARIANTS[v].run(a, stream);
