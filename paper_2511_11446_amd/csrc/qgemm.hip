@@ -27,9 +27,9 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 #endif
 
 constexpr int XCDS = 8;    // L2 domains of the chip; consecutive workgroup ids go round-robin over them
-constexpr int GROUP_M = 4; // tile rows walked together so that one L2 sees few distinct A and W panels (2..8 measure alike)
+constexpr int GROUP_ROWS = 1024; // rows of A walked together so that one L2 sees few distinct A and W panels (512..2048 measure alike)
 
-static int pick_group_m(int, int) { return GROUP_M; }
+static int pick_group_m(int bm) { return GROUP_ROWS / bm > 0 ? GROUP_ROWS / bm : 1; }
 
 __device__ __forceinline__ float half_to_float_dev(unsigned short h)
 {
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
     unsigned char *sB = smem + 2 * T::A_BYTES;
     float *sS = reinterpret_cast<float *>(sB + 2 * T::B_BYTES);
 
-    // ---- which tile: spread consecutive logical tiles inside one XCD, walk GROUP_M tile rows at a time
+    // ---- which tile: spread consecutive logical tiles inside one XCD, walk group_m tile rows at a time
     // Workgroup ids go round-robin over the XCDs; each XCD owns per_xcd consecutive logical tiles and its resident
     // workgroups take them in order, gridDim.x / XCDS at a time (all of them at once unless the launch is persistent).
     const int per_xcd = nblk_padded / XCDS;
@@ -922,7 +922,7 @@ static hipError_t run_dma(const GemmArgs &a, hipStream_t s)
         }
         if (grid > resident) grid = resident;
     }
-    hipLaunchKernelGGL((qgemm_dma<T, GLUE>), dim3(grid), dim3(T::NT), T::LDS_BYTES, s, a, tiles_m, tiles_n, padded, pick_group_m(tiles_m, tiles_n));
+    hipLaunchKernelGGL((qgemm_dma<T, GLUE>), dim3(grid), dim3(T::NT), T::LDS_BYTES, s, a, tiles_m, tiles_n, padded, pick_group_m(T::BM));
     return hipGetLastError();
 }
 
@@ -983,7 +983,7 @@ static hipError_t run_variant(const GemmArgs &a, hipStream_t s)
     const int tiles_m = (a.M + T::BM - 1) / T::BM, tiles_n = (a.N + T::BN - 1) / T::BN;
     const int nblk = tiles_m * tiles_n;
     const int padded = (nblk + XCDS - 1) / XCDS * XCDS;
-    hipLaunchKernelGGL((qgemm_mfma<T, GLUE>), dim3(padded), dim3(T::NT), T::LDS_BYTES, s, a, tiles_m, tiles_n, padded, pick_group_m(tiles_m, tiles_n));
+    hipLaunchKernelGGL((qgemm_mfma<T, GLUE>), dim3(padded), dim3(T::NT), T::LDS_BYTES, s, a, tiles_m, tiles_n, padded, pick_group_m(T::BM));
     return hipGetLastError();
 }
 
