@@ -30,8 +30,8 @@ POOL = 4                  # distinct activation sets rotated over the steps (dif
 # WRITE_SIZE runs of `bench.py --traffic-probe`, each scaled by what the same counter reads for a device-to-device copy
 # of known size in the same run (summaries under profiles/).  Keyed by (workload, forced variant); absent = not measured.
 TRAFFIC_BYTES_PER_LAUNCH = {
-    ("c2_block_w8a8_m2048", -1): 34080 * 1024,    # (2*fetch + write) KiB, mean of the 4 GEMM launches of a step
-    ("c4_block_w8a8_m16384", -1): 195827 * 1024,
+    ("c2_block_w8a8_m2048", -1): 36276 * 1024,    # (2*fetch + write) KiB, mean of the 4 GEMM launches of a step
+    ("c4_block_w8a8_m16384", -1): 188161 * 1024,
 }
 
 
