@@ -52,9 +52,9 @@ __device__ __forceinline__ bool has_glue(const GemmArgs &a) { return a.act != 0 
 struct GateRows {
     int base, rem, rows;
     bool one_step;
-    __device__ __forceinline__ GateRows(const GemmArgs &a, int m_first, int span)
+    __device__ __forceinline__ GateRows(const void *gate, int gate_rows, int m_first, int span)
     {
-        rows = a.gate ? a.gate_rows : 1;
+        rows = gate ? gate_rows : 1;
         base = m_first / rows;
         rem = m_first - base * rows;
         one_step = rows >= span;
@@ -77,6 +77,14 @@ __device__ __forceinline__ _Float16 glue_one(const GemmArgs &a, float u, int m, 
     }
     return h;
 }
+
+// what the staged write-back needs of the glue, by value (a pointer to the kernel arguments would force them into
+// scratch memory)
+struct GluePieces {
+    const _Float16 *gate = nullptr, *residual = nullptr;
+    int gate_rows = 1;
+    bool on = false;
+};
 
 // eight neighbouring elements of one row at once (16-byte pieces of the staged tile); g and r were loaded ahead
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
@@ -346,7 +354,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
                             u = bias ? __builtin_fmaf(t, sw, b) : t * sw;
                             if (a.acc_out) a.acc_out[off] = acc[i][j][r];
                         }
-                        if (GLUE) __builtin_nontemporal_store(glue_one(a, u, m, n, GateRows(a, m0, BM).of(row)), &y[off]);
+                        if (GLUE) __builtin_nontemporal_store(glue_one(a, u, m, n, GateRows(a.gate, a.gate_rows, m0, BM).of(row)), &y[off]);
                         else __builtin_nontemporal_store((_Float16)u, &y[off]);
                     }
                 }
@@ -372,7 +380,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
 //   otherwise they are stored to global memory directly (64-byte row segments per half wavefront).
 template <int TM, int TN, bool STAGED, int ROWS = 32, class ValueFn>
 __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane, _Float16 *y, int N, int m_base, int n_base,
-                                                  ValueFn value, const GemmArgs *glue = nullptr)
+                                                  ValueFn value, GluePieces glue = GluePieces())
 {
     constexpr int PITCH = TN * 64 + 16;
     constexpr int CH = TN * 4;  // 16-byte pieces per row
@@ -392,14 +400,14 @@ __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane
             // gate and residual of the pieces this lane will write back are requested before the block is dequantized
             constexpr int PIECES = ROWS * CH / 64;
             h8 pg[PIECES], pr[PIECES];
-            if (glue) {
-                const GateRows gr(*glue, m_base, TM * 32);
+            if (glue.on) {
+                const GateRows gr(glue.gate, glue.gate_rows, m_base, TM * 32);
 #pragma unroll
                 for (int t = 0; t < PIECES; ++t) {
                     const int id = lane + 64 * t;
                     const int row = i * 32 + h * ROWS + id / CH, col = n_base + (id % CH) * 8;
-                    if (glue->gate) pg[t] = *reinterpret_cast<const h8 *>(static_cast<const _Float16 *>(glue->gate) + (unsigned)(gr.of(row) * N + col));
-                    if (glue->residual) pr[t] = *reinterpret_cast<const h8 *>(static_cast<const _Float16 *>(glue->residual) + (unsigned)((m_base + row) * N + col));
+                    if (glue.gate) pg[t] = *reinterpret_cast<const h8 *>(glue.gate + (unsigned)(gr.of(row) * N + col));
+                    if (glue.residual) pr[t] = *reinterpret_cast<const h8 *>(glue.residual + (unsigned)((m_base + row) * N + col));
                 }
             }
 #pragma unroll
@@ -430,7 +438,7 @@ __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane
                     const int row = id / CH, ch = id % CH;
                     v4i v = *reinterpret_cast<const v4i_alias *>(strip + row * PITCH + ch * 16);
                     // gate and residual meet the fp16 result here, eight elements of a row at a time
-                    if (glue) v = glue_piece(glue->gate != nullptr, glue->residual != nullptr, v, pg[t], pr[t]);
+                    if (glue.on) v = glue_piece(glue.gate != nullptr, glue.residual != nullptr, v, pg[t], pr[t]);
                     // the output is written once and not read again by this kernel: keep it from displacing the operand panels in L2
                     __builtin_nontemporal_store(v, reinterpret_cast<v4i_alias *>(y + (unsigned)((m_base + i * 32 + h * ROWS + row) * N + n_base + ch * 8)));
                 }
@@ -816,9 +824,14 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     const bool full = (em0 + BM <= M) && (en0 + BN <= N);
     const bool glue_pieces = GLUE && (a.residual || a.gate);
     const bool glue_aligned = !glue_pieces || (((reinterpret_cast<uintptr_t>(a.residual) | reinterpret_cast<uintptr_t>(a.gate)) & 15) == 0);
-    auto act_of = [&](float u) { return (GLUE && a.act == 1) ? gelu_tanh_dev(u) : u; };
     if (full && (N % 8) == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0 && (W4 || !a.acc_out) && glue_aligned) {
-        const GemmArgs *gl = glue_pieces ? &a : nullptr;
+        GluePieces gl;
+        if (glue_pieces) {
+            gl.gate = static_cast<const _Float16 *>(a.gate);
+            gl.residual = static_cast<const _Float16 *>(a.residual);
+            gl.gate_rows = a.gate_rows;
+            gl.on = true;
+        }
         unsigned char *strip = smem + T::EPI_OFF + T::STRIP_OFF + wave * T::STRIP_BYTES;
         // the 16 row scales of each 32-row block of this lane (rows 8g + 4*frag_half + 0..3), read once as 4 x 16 bytes
         float sr[TM * 16];
@@ -835,22 +848,29 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
                     sr[i * 16 + 4 * g + 3] = t[3];
                 }
         }
-        if (W4 && bias)
-            store_tile_staged<TM, TN, T::STAGED_STORE, T::STRIP_ROWS>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
-                return act_of(__builtin_fmaf(fsum[W4 ? i : 0][W4 ? j : 0][r], sr[i * 16 + r], bj[j]));
-            }, gl);
-        else if (W4)
-            store_tile_staged<TM, TN, T::STAGED_STORE, T::STRIP_ROWS>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
-                return act_of(fsum[W4 ? i : 0][W4 ? j : 0][r] * sr[i * 16 + r]);
-            }, gl);
-        else if (bias)
-            store_tile_staged<TM, TN, T::STAGED_STORE, T::STRIP_ROWS>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
-                return act_of(__builtin_fmaf((float)acc[i][j][r] * sr[i * 16 + r], swt[j], bj[j]));
-            }, gl);
-        else
-            store_tile_staged<TM, TN, T::STAGED_STORE, T::STRIP_ROWS>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
-                return act_of((float)acc[i][j][r] * sr[i * 16 + r] * swt[j]);
-            }, gl);
+        // the activation is chosen once per kernel, not per element
+        auto emit_fast = [&](auto act_tag) {
+            constexpr bool ACT = decltype(act_tag)::value;
+            auto act_of = [&](float u) { return ACT ? gelu_tanh_dev(u) : u; };
+            if (W4 && bias)
+                store_tile_staged<TM, TN, T::STAGED_STORE, T::STRIP_ROWS>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
+                    return act_of(__builtin_fmaf(fsum[W4 ? i : 0][W4 ? j : 0][r], sr[i * 16 + r], bj[j]));
+                }, gl);
+            else if (W4)
+                store_tile_staged<TM, TN, T::STAGED_STORE, T::STRIP_ROWS>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
+                    return act_of(fsum[W4 ? i : 0][W4 ? j : 0][r] * sr[i * 16 + r]);
+                }, gl);
+            else if (bias)
+                store_tile_staged<TM, TN, T::STAGED_STORE, T::STRIP_ROWS>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
+                    return act_of(__builtin_fmaf((float)acc[i][j][r] * sr[i * 16 + r], swt[j], bj[j]));
+                }, gl);
+            else
+                store_tile_staged<TM, TN, T::STAGED_STORE, T::STRIP_ROWS>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
+                    return act_of((float)acc[i][j][r] * sr[i * 16 + r] * swt[j]);
+                }, gl);
+        };
+        if (GLUE && a.act == 1) emit_fast(std::true_type{});
+        else emit_fast(std::false_type{});
     } else {
         auto emit = [&](auto edge) {
             constexpr bool EDGE = decltype(edge)::value;
@@ -877,7 +897,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
                                 if (a.acc_out) a.acc_out[off] = acc[i][j][r];
                             }
                             asm volatile("" : "+v"(u));   // keep the fp32 rounding before the fp16 one
-                            if (GLUE) y[off] = glue_one(a, u, m, n, GateRows(a, em0, BM).of(row));
+                            if (GLUE) y[off] = glue_one(a, u, m, n, GateRows(a.gate, a.gate_rows, em0, BM).of(row));
                             else y[off] = (_Float16)u;
                         }
                     }
@@ -1018,7 +1038,6 @@ using D8_128x192_s3 = TileD<2, 3, 2, 2, 3, 2>;
 using D8_128x192_s2 = TileD<2, 3, 2, 2, 2, 2>;
 using D8_256x128_s3 = TileD<4, 2, 2, 2, 3, 1>;
 using D8_256x192_s2 = TileD<4, 3, 2, 2, 2, 1>;
-using D8_256x256_s2 = TileD<4, 4, 2, 2, 2, 1>;
 using D8_256x256_8w = TileD<4, 2, 2, 4, 2, 2>;
 using D8_256x192_8w = TileD<2, 3, 4, 2, 2, 2>;
 using D8_256x192_8w_e1 = TileD<2, 3, 4, 2, 2, 2, true, 1>;
@@ -1035,8 +1054,6 @@ using D8_128x128_a3b2 = TileD<2, 2, 2, 2, 3, 2, true, 0, false, 2>;
 using D8_128x128_a3b2_e1 = TileD<2, 2, 2, 2, 3, 2, true, 1, false, 2>;
 using D8_128x128_s2_e1 = TileD<2, 2, 2, 2, 2, 2, true, 1>;
 //                                                                               persistent
-using P8_256x192_a3b2 = TileD<2, 3, 4, 2, 3, 2, true, 1, false, 2, true>;
-using P8_256x256_a3b2 = TileD<4, 2, 2, 4, 3, 2, true, 1, false, 2, true>;
 using P8_128x128_a3b2 = TileD<2, 2, 2, 2, 3, 2, true, 1, false, 2, true>;
 using P8_128x192_s2 = TileD<2, 3, 2, 2, 2, 2, true, 1, false, 2, true>;
 
@@ -1047,7 +1064,6 @@ static const Variant VARIANTS[] = {
     {"w8 dma 128x192 s2 4w", 8, 128, 192, 128, run_dma<D8_128x192_s2>},
     {"w8 dma 256x128 s3 4w", 8, 256, 128, 128, run_dma<D8_256x128_s3>},
     {"w8 dma 256x192 s2 4w", 8, 256, 192, 128, run_dma<D8_256x192_s2>},
-    {"w8 dma 256x256 s2 4w", 8, 256, 256, 128, run_dma<D8_256x256_s2>},
     {"w8 dma 256x256 s2 8w", 8, 256, 256, 128, run_dma<D8_256x256_8w>},
     {"w8 dma 256x192 s2 8w", 8, 256, 192, 128, run_dma<D8_256x192_8w>},
     {"w8 dma 64x64 s4 4w", 8, 64, 64, 128, run_dma<D8_64x64_s4>, run_dma<D8_64x64_s4, true>},
@@ -1062,8 +1078,6 @@ static const Variant VARIANTS[] = {
     {"w8 dma 128x128 a3b2 4w", 8, 128, 128, 128, run_dma<D8_128x128_a3b2>, run_dma<D8_128x128_a3b2, true>},
     {"w8 dma 128x128 a3b2 4w spread1", 8, 128, 128, 128, run_dma<D8_128x128_a3b2_e1>, run_dma<D8_128x128_a3b2_e1, true>},
     {"w8 dma 128x128 s2 4w spread1", 8, 128, 128, 128, run_dma<D8_128x128_s2_e1>},
-    {"w8 dma 256x192 a3b2 8w spread1 persistent", 8, 256, 192, 128, run_dma<P8_256x192_a3b2>},
-    {"w8 dma 256x256 a3b2 8w spread1 persistent", 8, 256, 256, 128, run_dma<P8_256x256_a3b2>},
     {"w8 dma 128x128 a3b2 4w spread1 persistent", 8, 128, 128, 128, run_dma<P8_128x128_a3b2>},
     {"w8 dma 128x192 s2 4w spread1 persistent", 8, 128, 192, 128, run_dma<P8_128x192_s2>},
     {"w8 128x128 bk64 4w occ2", 8, 128, 128, 64, run_variant<W8_128x128_k64>},
@@ -1145,7 +1159,7 @@ hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream)
         // block glue in the epilogue: only the shape-chosen tiles carry it
         if (!VARIANTS[v].run_glue) v = choose_variant(a);
         // the prefetched gate and residual pieces need registers the persistent tiles do not have left
-        // (256x192 measured faster here than two resident 128x128 workgroups per CU: 565 against 596 us for a block at M = 16384)
+        // (256x192 and two resident 128x128 workgroups per CU measure alike here: 495 and 491 us for a block at M = 16384)
         static const int big = find_variant("w8 dma 256x192 a3b2 8w spread1");
         if (__builtin_strstr(VARIANTS[v].name, "persistent")) v = big;
         return VARIANTS[v].run_glue(a, stream);
