@@ -106,24 +106,55 @@ __global__ __launch_bounds__(256) void daq_rows_robust(DaqArgs a, int mode)
     if (mode == DAQ_QUANT) {
         tau_bits = a.blockmax[row / a.R];
     } else {
-        // Largest T with count(magnitude >= T) >= top_rank, built bit by bit from the top.  Each half word is
-        // 0x8000 | magnitude; subtracting T from both halves at once leaves bit 15 of a half set iff its
-        // magnitude >= T (no half can borrow from its neighbour: every half result is >= 1).  Lanes past the end of
-        // the row hold zeros, which no T >= 1 counts.
-        unsigned T = 0;
-        for (int bit = 14; bit >= 0; --bit) {
-            const unsigned cand = T | (1u << bit);
-            const unsigned cand2 = cand * 0x00010001u;
+        // Each half word is 0x8000 | magnitude (OR-ing 0x8000 in overwrites the sign bit); subtracting T from both
+        // halves at once leaves bit 15 of a half set iff its magnitude >= T (no half can borrow from its neighbour:
+        // every half result is >= 1).  Lanes past the end of the row hold zeros, which no T >= 1 counts.
+        auto count_ge = [&](unsigned t) {
+            const unsigned t2 = t * 0x00010001u;
             unsigned cnt = 0;
 #pragma unroll
             for (int i = 0; i < CH; ++i) {
-                cnt += ((((v[i].x & 0x7fff7fffu) | 0x80008000u) - cand2) >> 15) & 0x00010001u;
-                cnt += ((((v[i].y & 0x7fff7fffu) | 0x80008000u) - cand2) >> 15) & 0x00010001u;
-                cnt += ((((v[i].z & 0x7fff7fffu) | 0x80008000u) - cand2) >> 15) & 0x00010001u;
-                cnt += ((((v[i].w & 0x7fff7fffu) | 0x80008000u) - cand2) >> 15) & 0x00010001u;
+                cnt += (((v[i].x | 0x80008000u) - t2) >> 15) & 0x00010001u;
+                cnt += (((v[i].y | 0x80008000u) - t2) >> 15) & 0x00010001u;
+                cnt += (((v[i].z | 0x80008000u) - t2) >> 15) & 0x00010001u;
+                cnt += (((v[i].w | 0x80008000u) - t2) >> 15) & 0x00010001u;
             }
-            cnt = wave_sum_u32((cnt & 0xffffu) + (cnt >> 16));
-            if (cnt >= a.top_rank) T = cand;
+            return wave_sum_u32((cnt & 0xffffu) + (cnt >> 16));
+        };
+        unsigned T = 0;
+        if (a.top_rank <= 4) {
+            // tau is among the few largest values (the paper's p = 99.9 %: the 2nd largest of 1152, the 5th of 4608):
+            // walk down the distinct magnitudes from the top, one per pass, until top_rank values lie at or above
+            unsigned prev = 0x8000u;   // above every magnitude
+            for (unsigned pass = 0; pass < a.top_rank; ++pass) {
+                const unsigned p2 = prev * 0x00010001u;
+                unsigned m2 = 0;
+                auto below = [&](unsigned w) {
+                    const unsigned mag = w & 0x7fff7fffu;
+                    const unsigned ge = ((mag | 0x80008000u) - p2) >> 15;          // bit 0 / 16: magnitude >= prev
+                    return mag & ((~ge & 0x00010001u) * 0xffffu);                   // keep the halves below prev
+                };
+#pragma unroll
+                for (int i = 0; i < CH; ++i) {
+                    m2 = absmax_word(m2, below(v[i].x));
+                    m2 = absmax_word(m2, below(v[i].y));
+                    m2 = absmax_word(m2, below(v[i].z));
+                    m2 = absmax_word(m2, below(v[i].w));
+                }
+                const unsigned m = wave_max_u32((m2 & 0xffffu) > (m2 >> 16) ? (m2 & 0xffffu) : (m2 >> 16));
+                if (m == 0) break;                      // everything left is zero: tau = 0
+                if (count_ge(m) >= a.top_rank) {
+                    T = m;
+                    break;
+                }
+                prev = m;
+            }
+        } else {
+            // largest T with count(magnitude >= T) >= top_rank, built bit by bit from the top
+            for (int bit = 14; bit >= 0; --bit) {
+                const unsigned cand = T | (1u << bit);
+                if (count_ge(cand) >= a.top_rank) T = cand;
+            }
         }
         tau_bits = T;
     }
