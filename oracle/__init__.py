@@ -222,6 +222,21 @@ def epilogue_w4(P, s_a, R, s_w, bias):
     return y.view(np.float16)
 
 
+def linear_f16(x, w, bias=None, nthreads=1):
+    """A layer left in FP16: x [M,K], w [N,K], bias [N] float16 -> y float16 [M,N] (fp64 sum, then fp32, then fp16)."""
+    xb, wb = _f16bits(x), _f16bits(w)
+    M, K = xb.shape
+    N = wb.shape[0]
+    assert wb.shape[1] == K
+    b = None if bias is None else _f16bits(bias)
+    y = np.empty((M, N), np.uint16)
+    rc = lib().orc_linear_f16(_p(xb), _p(wb), _p(b), ctypes.c_int64(M), ctypes.c_int64(N), ctypes.c_int64(K), _p(y),
+                              ctypes.c_int(nthreads))
+    if rc:
+        raise ValueError("orc_linear_f16 rc=%d" % rc)
+    return y.view(np.float16)
+
+
 def dequant_w8(acc, s_a, R, s_w, bias):
     """The layer's fp32 values before the fp16 rounding, float32 [M,N]."""
     acc = _c(acc, np.int32)

@@ -414,6 +414,34 @@ int orc_block_glue(const float *u, int64_t M, int64_t N, int act, const uint16_t
 }
 
 /* ------------------------------------------------------------------ */
+/* A layer the plan leaves in FP16 (Step 2 freezes the most sensitive   */
+/* layers; the final plan of Section 6 keeps 22 of 113 in FP16):        */
+/*   y[m,n] = f16( sum_k x[m,k] * w[n,k] + bias[n] )                    */
+/* x [M,K], w [N,K], bias [N] binary16.  The sum is taken in binary64   */
+/* (every product of two binary16 values is exact there), the bias is   */
+/* added in binary64, and the result is rounded to binary32 and then to */
+/* binary16.                                                            */
+/* ------------------------------------------------------------------ */
+int orc_linear_f16(const uint16_t *x, const uint16_t *w, const uint16_t *bias,
+                   int64_t M, int64_t N, int64_t K, uint16_t *y, int nthreads)
+{
+    if (M < 0 || N < 0 || K < 0) return 1;
+    (void)nthreads;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) num_threads(nthreads > 1 ? nthreads : 1)
+#endif
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            double s = 0.0;
+            for (int64_t k = 0; k < K; ++k)
+                s += (double)orc_half_to_float(x[m * K + k]) * (double)orc_half_to_float(w[n * K + k]);
+            if (bias) s += (double)orc_half_to_float(bias[n]);
+            y[m * N + n] = orc_float_to_half((float)s);
+        }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
 /* The whole layer: DAQ -> GEMM -> epilogue.  Optional outputs         */
 /* (q, s_a, acc / P) may be NULL; scratch is then taken from the heap. */
 /* ------------------------------------------------------------------ */

@@ -218,3 +218,25 @@ def test_gate_and_residual_hand_worked_and_broadcast(orc):
     assert orc.block_glue(u2, residual=r2)[0, 0] == np.float16(1.0)
     with pytest.raises(ValueError):
         orc.block_glue(u, gate=gate, gate_rows=3)
+
+
+# ---------------------------------------------------------------- layers the plan leaves in FP16
+
+def test_fp16_layer_against_numpy_float64_and_closed_forms(orc):
+    g = workload.rng("f16-layer")
+    M, K, N = 9, 200, 11
+    x = g.standard_normal((M, K), dtype=np.float32).astype(np.float16)
+    w = (g.standard_normal((N, K), dtype=np.float32) * 0.1).astype(np.float16)
+    b = workload.bias(N, "f16")
+    y = orc.linear_f16(x, w, b)
+    want = (x.astype(np.float64) @ w.astype(np.float64).T + b.astype(np.float64)).astype(np.float32).astype(np.float16)
+    assert np.array_equal(y.view(np.uint16), want.view(np.uint16))
+    # identity weights copy the input; a row of ones sums it; transposing the operands' roles is caught by N != M != K
+    eye = np.eye(K, dtype=np.float16)
+    assert np.array_equal(orc.linear_f16(x, eye), x)
+    ones = np.ones((1, K), np.float16)
+    s = orc.linear_f16(x, ones)[:, 0].astype(np.float64)
+    assert np.allclose(s, x.astype(np.float64).sum(axis=1), rtol=2.0 ** -10, atol=1e-6)
+    # an exactly representable case with cancellation that fp32 running sums would lose: 2048 + 1 - 2048 = 1
+    xc = np.array([[2048.0, 1.0, -2048.0]], np.float16)
+    assert orc.linear_f16(xc, np.ones((1, 3), np.float16))[0, 0] == np.float16(1.0)
