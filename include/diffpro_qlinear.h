@@ -195,6 +195,20 @@ int qlinear_w4a8_fused(const void *x, int64_t M, int64_t K, int64_t R,
                        const ql_fusion *fusion, void *y,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/* ------------------------------------------------------------------------
+ * A layer the plan leaves in FP16 (Step 2 freezes the most sensitive layers;
+ * the final plan of Section 6 keeps 22 layers in FP16): no quantization,
+ *   y[m,n] = fp16( sum_k x[m,k] * w[n,k] + bias[n] )
+ * with fp32 accumulation on the matrix cores (the sum's rounding error is
+ * bounded by K * 2^-24 * sum_k |x w|; the oracle sums in fp64).
+ *   x (device) [M,K] fp16;  w (device) [N,K] fp16;  bias (device) [N] fp16 or NULL
+ *   fusion: as in the *_fused calls, or NULL.  No workspace.
+ * In a plan such a layer has w_bits = 16, group = 0 and w_scale = NULL.
+ * ---------------------------------------------------------------------- */
+int qlinear_f16(const void *x, int64_t M, int64_t K,
+                const void *w, const void *bias, int64_t N,
+                const ql_fusion *fusion, void *y, void *stream);
+
 /* Host helper: pack int8 codes in [-8,7], [N,K] row-major (host), into the
  * 4-bit storage order described at qlinear_w4a8 ([N,K/2] bytes, host).
  * K % 8 == 0.  Returns QL_ERR_SHAPE for a code outside [-8,7]. */
@@ -210,7 +224,7 @@ int ql_pack_w4_host(const int8_t *codes, int64_t N, int64_t K, uint8_t *packed);
 typedef struct ql_layer_desc {
     int64_t K;            /* input features */
     int64_t N;            /* output features */
-    int32_t w_bits;       /* 8 or 4 */
+    int32_t w_bits;       /* 8 or 4; 16 = the layer stays in FP16 (w fp16 [N,K], w_scale NULL, group 0) */
     int32_t group;        /* 0 = one scale per output channel (8-bit); 4-bit: k per scale, a multiple of 32 dividing K */
     const void *w;        /* (device) int8 [N,K] or packed 4-bit [N,K/2] */
     const void *w_scale;  /* (device) fp32 [N] (8-bit) or fp16 [N,K/group] (4-bit) */

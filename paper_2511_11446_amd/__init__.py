@@ -22,7 +22,7 @@ EXPORTS = ("ql_status_string", "ql_last_device_error", "ql_version", "daq_worksp
            "ql_pack_w4_host", "ql_plan_create", "ql_plan_destroy", "ql_plan_num_layers",
            "ql_plan_workspace_bytes", "qlinear_plan_run", "ql_set_gemm_variant", "ql_num_gemm_variants",
            "ql_gemm_variant_name", "ql_probe_mfma_int8", "daq_quantize_robust", "qlinear_plan_run_robust", "ql_time_bin",
-           "qlinear_w4a8_g", "qgemm_w4a8_g", "qlinear_w8a8_fused", "qlinear_w4a8_fused")
+           "qlinear_w4a8_g", "qgemm_w4a8_g", "qlinear_w8a8_fused", "qlinear_w4a8_fused", "qlinear_f16")
 
 
 class QlError(RuntimeError):
@@ -95,6 +95,8 @@ def lib():
     L.qlinear_w8a8_fused.restype = _int
     L.qlinear_w4a8_fused.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _i64, _vp, _i64, ctypes.POINTER(ql_fusion), _vp, _vp, _sz, _vp]
     L.qlinear_w4a8_fused.restype = _int
+    L.qlinear_f16.argtypes = [_vp, _i64, _i64, _vp, _vp, _i64, ctypes.POINTER(ql_fusion), _vp, _vp]
+    L.qlinear_f16.restype = _int
     L.qlinear_plan_run_robust.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _i64, _i64, _vp, _vp, _sz, _vp]
     L.qlinear_plan_run_robust.restype = _int
     L.daq_quantize_robust.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -194,6 +196,20 @@ def qlinear_fused(x, R, w, w_scale, bias=None, bits=8, group=128, act=ACT_NONE, 
         rc = lib().qlinear_w4a8_fused(_ptr(x), M, K, R, _ptr(w), _ptr(w_scale), group, _ptr(bias), N, ctypes.byref(fu),
                                       _ptr(y), _ptr(ws), ws.numel(), _stream(stream))
     _check(rc, "qlinear_w%da8_fused" % bits)
+    return y
+
+
+def qlinear_f16(x, w, bias=None, act=ACT_NONE, residual=None, gate=None, gate_rows=1, y=None, stream=None):
+    """A layer left in FP16: x fp16 [M,K], w fp16 [N,K] -> y fp16 [M,N] (fp32 accumulation)."""
+    import torch
+    _need(x, torch.float16, name="x")
+    _need(w, torch.float16, name="w")
+    M, K = x.shape
+    N = w.shape[0]
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    fu = ql_fusion(act, 0, None if residual is None else residual.data_ptr(), None if gate is None else gate.data_ptr(), gate_rows)
+    _check(lib().qlinear_f16(_ptr(x), M, K, _ptr(w), _ptr(bias), N, ctypes.byref(fu), _ptr(y), _stream(stream)), "qlinear_f16")
     return y
 
 
@@ -327,7 +343,8 @@ class Plan:
         arr = (ql_layer_desc * len(layers))()
         for i, l in enumerate(layers):
             arr[i] = ql_layer_desc(l["K"], l["N"], l["bits"], l.get("group", 128) if l["bits"] == 4 else 0, l["w"].data_ptr(),
-                                   l["w_scale"].data_ptr(), 0 if l.get("bias") is None else l["bias"].data_ptr())
+                                   0 if l.get("w_scale") is None else l["w_scale"].data_ptr(),
+                                   0 if l.get("bias") is None else l["bias"].data_ptr())
         h = _vp()
         _check(lib().ql_plan_create(arr, len(layers), M_max, ctypes.byref(h)), "ql_plan_create")
         self.handle = h

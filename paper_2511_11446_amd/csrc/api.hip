@@ -97,6 +97,27 @@ int run_layer(const void *x, int64_t M, int64_t K, int64_t R, int w_bits, const 
               const void *bias, int64_t N, void *y, const ql_debug *dbg, void *workspace, hipStream_t stream,
               const ql_daq_params *dp = nullptr, int64_t group = 128, const ql_fusion *fu = nullptr)
 {
+    if (w_bits == 16) {
+        // a layer the plan leaves in FP16: no quantization, both operands binary16
+        ql::GemmArgs g{};
+        g.q = static_cast<const int8_t *>(x);
+        g.w = w;
+        g.bias = bias;
+        g.y = y;
+        g.M = (int)M;
+        g.N = (int)N;
+        g.K = (int)K;
+        g.R = 1;
+        g.w_bits = 16;
+        g.group = 128;
+        if (fu) {
+            g.act = fu->act;
+            g.residual = fu->residual;
+            g.gate = fu->gate;
+            g.gate_rows = (int)fu->gate_rows;
+        }
+        return device_status(ql::launch_qgemm(g, g_gemm_variant.load(), stream));
+    }
     const LayerWs lw = layer_ws(M, K, R);
     unsigned char *base = static_cast<unsigned char *>(workspace);
     ql::DaqArgs d{};
@@ -332,6 +353,19 @@ int qlinear_w4a8_fused(const void *x, int64_t M, int64_t K, int64_t R, const voi
     return qlinear_any(4, x, M, K, R, w4, w_scale, bias, N, y, nullptr, workspace, workspace_bytes, stream, group, fusion);
 }
 
+int qlinear_f16(const void *x, int64_t M, int64_t K, const void *w, const void *bias, int64_t N, const ql_fusion *fusion,
+                void *y, void *stream)
+{
+    if (!x || !w || !y) return QL_ERR_NULL;
+    if (misaligned(x, 2) || misaligned(w, 2) || misaligned(y, 2) || misaligned(bias, 2)) return QL_ERR_ALIGN;
+    int rc = check_shape(M, K, 1, N);
+    if (rc) return rc;
+    rc = check_fusion(fusion, M);
+    if (rc) return rc;
+    return run_layer(x, M, K, 1, 16, w, nullptr, bias, N, y, nullptr, nullptr, static_cast<hipStream_t>(stream), nullptr, 128,
+                     fusion);
+}
+
 int qgemm_w4a8_g(const void *q, const void *a_scales, int64_t M, int64_t K, int64_t R, const void *w4,
                  const void *w_scale, int64_t group, const void *bias, int64_t N, void *y, void *acc, void *stream)
 {
@@ -375,16 +409,17 @@ int ql_plan_create(const ql_layer_desc *layers, int32_t n_layers, int64_t M_max,
     int64_t widest = 0;
     for (int32_t l = 0; l < n_layers; ++l) {
         const ql_layer_desc &d = layers[l];
-        if (d.w_bits != 8 && d.w_bits != 4) return QL_ERR_UNSUPPORTED;
-        if (d.w_bits == 8 && d.group != 0) return QL_ERR_UNSUPPORTED;
-        if (!d.w || !d.w_scale) return QL_ERR_NULL;
+        if (d.w_bits != 8 && d.w_bits != 4 && d.w_bits != 16) return QL_ERR_UNSUPPORTED;
+        if (d.w_bits != 4 && d.group != 0) return QL_ERR_UNSUPPORTED;
+        if (!d.w || (!d.w_scale && d.w_bits != 16)) return QL_ERR_NULL;
+        if (d.w_bits == 16 && misaligned(d.w, 2)) return QL_ERR_ALIGN;
         int rc = check_shape(M_max, d.K, 1, d.N);
         if (rc) return rc;
         if (d.w_bits == 4) {
             rc = check_group(d.K, d.group);
             if (rc) return rc;
         }
-        if (misaligned(d.w_scale, d.w_bits == 8 ? 4 : 2) || misaligned(d.bias, 2)) return QL_ERR_ALIGN;
+        if ((d.w_bits != 16 && misaligned(d.w_scale, d.w_bits == 8 ? 4 : 2)) || misaligned(d.bias, 2)) return QL_ERR_ALIGN;
         widest = d.K > widest ? d.K : widest;
     }
     ql_plan *p = new (std::nothrow) ql_plan;

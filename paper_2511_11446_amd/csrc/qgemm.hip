@@ -448,6 +448,17 @@ __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane
     }
 }
 
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+
+// one 32x32 MFMA over a 16-byte fragment per lane: 32 int8 or 16 binary16 along K
+template <bool F16, class Acc>
+__device__ __forceinline__ Acc mfma_step(v4i a, v4i b, Acc c)
+{
+    if constexpr (F16) return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Pipelined variant: tiles go from global memory straight into LDS (global_load_lds_dwordx4, no
 // register staging) through a ring of S stages.  One K step is 128 int8 = one 128-byte LDS row, so
@@ -459,12 +470,15 @@ __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane
 // the next quarter, the hand-over barrier and the next DMA issue all sit behind an MFMA that is
 // already executing.
 // ---------------------------------------------------------------------------------------------
-template <int TM_, int TN_, int WGM_, int WGN_, int S_, int WPS_, bool STG_ = true, int EV_ = 0, bool W4_ = false, int SB_ = S_, bool PERSIST_ = false>
+template <int TM_, int TN_, int WGM_, int WGN_, int S_, int WPS_, bool STG_ = true, int EV_ = 0, bool W4_ = false, int SB_ = S_, bool PERSIST_ = false, bool F16_ = false>
 struct TileD {
     static constexpr int TM = TM_, TN = TN_, WGM = WGM_, WGN = WGN_, WPS = WPS_;
     // ring depth of the activation tile and of the weight tile (K steps resident or in flight); they may differ by one
     static constexpr int SA = S_, SB = SB_;
     static constexpr bool W4 = W4_;
+    // both operands binary16 (a layer the plan leaves unquantized): one K step is 64 values = the same 128 bytes per row
+    static constexpr bool F16 = F16_;
+    static_assert(!(F16_ && W4_), "FP16 layers have no packed weights");
     static constexpr int NW = WGM * WGN, NT = NW * 64;
     static constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32, BK = 128;
     // 1024-byte DMA groups per K step: A rows (8 rows x 128 B) and W rows (8 x 128 B, or 16 x 64 B packed 4-bit)
@@ -507,7 +521,8 @@ template <class T, bool GLUE = false>
 __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles_m, int tiles_n, int nblk_padded, int group_m)
 {
     constexpr int TM = T::TM, TN = T::TN, BM = T::BM, BN = T::BN, NT = T::NT, NW = T::NW;
-    constexpr bool W4 = T::W4;
+    constexpr bool W4 = T::W4, F16 = T::F16;
+    constexpr int EB = F16 ? 2 : 1;   // bytes per element of both operands
     extern __shared__ __align__(1024) unsigned char smem[];
 
     // Workgroup ids go round-robin over the XCDs; each XCD owns per_xcd consecutive logical tiles and its resident
@@ -531,7 +546,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it in a scalar register
     const int wm = wave / T::WGN, wn = wave % T::WGN;
     const int M = a.M, N = a.N, K = a.K;
-    const int nk = K / 128;   // K steps; for 4-bit weights also the number of weight groups
+    const int nk = K * EB / 128;   // K steps (128 bytes per row); for 4-bit weights also the number of weight groups
     QL_PHASE(0)
 
     // Everything the epilogue needs from global memory is requested now, ahead of the first DMA (the oldest loads
@@ -540,12 +555,12 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     static_assert(BM <= NT, "one row scale per thread");
     float sa_pre, swt[TN], bj[TN];
     auto load_scales = [&]() {
-        sa_pre = tid < BM ? a.s_a[min(m0 + tid, M - 1) / a.R] : 0.0f;
+        sa_pre = (!F16 && tid < BM) ? a.s_a[min(m0 + tid, M - 1) / a.R] : 1.0f;
         const unsigned short *bias_h = static_cast<const unsigned short *>(a.bias);
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int n = min(n0 + wn * TN * 32 + j * 32 + (lane & 31), N - 1);
-            swt[j] = W4 ? 1.0f : static_cast<const float *>(a.s_w)[n];
+            swt[j] = (W4 || F16) ? 1.0f : static_cast<const float *>(a.s_w)[n];
             bj[j] = bias_h ? half_to_float_dev(bias_h[n]) : 0.0f;
         }
     };
@@ -569,14 +584,14 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
         for (int i = 0; i < NA; ++i) {
             const int row = 8 * (wave + i * NW) + (lane >> 3);
             const int c = (lane & 7) ^ ((row >> 1) & 7);
-            goffA[i] = (unsigned)(min(m0 + row, M - 1) * K + 16 * c);
+            goffA[i] = (unsigned)(min(m0 + row, M - 1) * K * EB + 16 * c);
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             if (!W4) {
                 const int row = 8 * (wave + i * NW) + (lane >> 3);
                 const int c = (lane & 7) ^ ((row >> 1) & 7);
-                goffB[i] = (unsigned)(min(n0 + row, N - 1) * K + 16 * c);
+                goffB[i] = (unsigned)(min(n0 + row, N - 1) * K * EB + 16 * c);
             } else {
                 // packed 4-bit rows are 64 bytes per K step: 16 rows per group, chunk c of row r at slot c ^ ((r >> 2) & 3)
                 const int row = 16 * (wave + i * NW) + (lane >> 2);
@@ -611,7 +626,8 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory");
     };
 
-    v16i acc[TM][TN];
+    typedef typename std::conditional<F16, v16f, v16i>::type acc_t;   // fp32 accumulators for FP16 operands
+    acc_t acc[TM][TN];
     // 4-bit weights: fp32 sum over the weight groups, f = sum_g fma(float(P_g), s_w[n,g], f)
     float fsum[W4 ? TM : 1][W4 ? TN : 1][16];
     auto clear_sums = [&]() {
@@ -654,6 +670,8 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
     // right before the accumulator is restarted; the group scale carries the 1/16 (exact: a power of two).
     int flush_group = -1;  // group whose partial sums are still in acc
     auto flush_tile = [&](int i, int j) {
+        if constexpr (F16) return;
+        else {
         const int n_loc = wn * TN * 32 + j * 32 + frag_row;
         const float s16 = half_to_float_dev(sScale[n_loc * nk + flush_group]) * 0.0625f;
 #pragma unroll
@@ -663,6 +681,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
                 if (m < M && n < N) a.acc_out[(unsigned)((m * nk + flush_group) * N + n)] = acc[i][j][r] >> 4;
             }
             fsum[W4 ? i : 0][W4 ? j : 0][r] = __builtin_fmaf((float)acc[i][j][r], s16, fsum[W4 ? i : 0][W4 ? j : 0][r]);
+        }
         }
     };
     // MFMAs number [first, last) of one quarter, in (i, j) order; restart = first quarter of a 4-bit weight group
@@ -675,9 +694,9 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
                     if (W4 && restart) {
                         if (flush_group >= 0) flush_tile(i, j);
                         const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], zero, 0, 0, 0);
+                        if constexpr (!F16) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], zero, 0, 0, 0);
                     } else {
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = mfma_step<F16>(af[i], bf[j], acc[i][j]);
                     }
                 }
     };
@@ -697,9 +716,9 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
                     if (W4 && restart) {
                         if (flush_group >= 0) flush_tile(i, j);
                         const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], zero, 0, 0, 0);
+                        if constexpr (!F16) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], zero, 0, 0, 0);
                     } else {
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = mfma_step<F16>(af[i], bf[j], acc[i][j]);
                     }
                     const int li = i0 + (idx - first) / EVERY;
                     if (SPREAD && (idx - first) % EVERY == EVERY - 1 && li < NA + NB) {
@@ -852,7 +871,11 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
         auto emit_fast = [&](auto act_tag) {
             constexpr bool ACT = decltype(act_tag)::value;
             auto act_of = [&](float u) { return ACT ? gelu_tanh_dev(u) : u; };
-            if (W4 && bias)
+            if (F16)
+                store_tile_staged<TM, TN, T::STAGED_STORE, T::STRIP_ROWS>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
+                    return act_of((float)acc[i][j][r] + bj[j]);
+                }, gl);
+            else if (W4 && bias)
                 store_tile_staged<TM, TN, T::STAGED_STORE, T::STRIP_ROWS>(strip, lane, y, N, em0 + wm * TM * 32, en0 + wn * TN * 32, [&](int i, int j, int r) {
                     return act_of(__builtin_fmaf(fsum[W4 ? i : 0][W4 ? j : 0][r], sr[i * 16 + r], bj[j]));
                 }, gl);
@@ -888,13 +911,15 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
                         if (!EDGE || (m < M && n_ok)) {
                             const unsigned off = (unsigned)(m * N + n);
                             float u;
-                            if (W4) {
+                            if (F16) {
+                                u = (float)acc[i][j][r] + b;
+                            } else if (W4) {
                                 const float f = fsum[W4 ? i : 0][W4 ? j : 0][r];
                                 u = bias ? __builtin_fmaf(f, sRow[row], b) : f * sRow[row];
                             } else {
                                 const float t = (float)acc[i][j][r] * sRow[row];
                                 u = bias ? __builtin_fmaf(t, swt[j], b) : t * swt[j];
-                                if (a.acc_out) a.acc_out[off] = acc[i][j][r];
+                                if (a.acc_out) a.acc_out[off] = (int)acc[i][j][r];
                             }
                             asm volatile("" : "+v"(u));   // keep the fp32 rounding before the fp16 one
                             if (GLUE) y[off] = glue_one(a, u, m, n, GateRows(a.gate, a.gate_rows, em0, BM).of(row));
@@ -953,9 +978,19 @@ __global__ __launch_bounds__(256) void qgemm_naive(GemmArgs a)
     const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (m >= a.M || n >= a.N) return;
     const int K = a.K;
-    const float sa = a.s_a[m / a.R];
     const unsigned short *bias = static_cast<const unsigned short *>(a.bias);
     const float b = bias ? half_to_float_dev(bias[n]) : 0.0f;
+    if (a.w_bits == 16) {
+        // a layer left in FP16: a.q holds the binary16 activations, a.w the binary16 weights; fp32 running sum
+        const unsigned short *xr = reinterpret_cast<const unsigned short *>(a.q) + (size_t)m * K;
+        const unsigned short *wr = static_cast<const unsigned short *>(a.w) + (size_t)n * K;
+        float s = 0.0f;
+        for (int k = 0; k < K; ++k) s = __builtin_fmaf(half_to_float_dev(xr[k]), half_to_float_dev(wr[k]), s);
+        const float u16 = s + b;
+        static_cast<_Float16 *>(a.y)[(size_t)m * a.N + n] = has_glue(a) ? glue_one(a, u16, m, n, a.gate ? m / a.gate_rows : 0) : (_Float16)u16;
+        return;
+    }
+    const float sa = a.s_a[m / a.R];
     const int8_t *q = a.q + (size_t)m * K;
     float u;
     if (a.w_bits == 8) {
@@ -1056,6 +1091,10 @@ using D8_128x128_s2_e1 = TileD<2, 2, 2, 2, 2, 2, true, 1>;
 //                                                                               persistent
 using P8_128x128_a3b2 = TileD<2, 2, 2, 2, 3, 2, true, 1, false, 2, true>;
 using P8_128x192_s2 = TileD<2, 3, 2, 2, 2, 2, true, 1, false, 2, true>;
+//                                                                                      FP16 operands
+using H_256x192_8w = TileD<2, 3, 4, 2, 3, 2, true, 1, false, 2, false, true>;
+using H_128x128_4w = TileD<2, 2, 2, 2, 3, 2, true, 1, false, 2, false, true>;
+using H_64x64_4w = TileD<1, 1, 2, 2, 4, 4, true, 0, false, 4, false, true>;
 
 static const Variant VARIANTS[] = {
     {"w8 dma 128x128 s3 4w", 8, 128, 128, 128, run_dma<D8_128x128_s3>},
@@ -1080,6 +1119,9 @@ static const Variant VARIANTS[] = {
     {"w8 dma 128x128 s2 4w spread1", 8, 128, 128, 128, run_dma<D8_128x128_s2_e1>},
     {"w8 dma 128x128 a3b2 4w spread1 persistent", 8, 128, 128, 128, run_dma<P8_128x128_a3b2>},
     {"w8 dma 128x192 s2 4w spread1 persistent", 8, 128, 192, 128, run_dma<P8_128x192_s2>},
+    {"f16 dma 256x192 a3b2 8w spread1", 16, 256, 192, 64, run_dma<H_256x192_8w>, run_dma<H_256x192_8w, true>},
+    {"f16 dma 128x128 a3b2 4w spread1", 16, 128, 128, 64, run_dma<H_128x128_4w>, run_dma<H_128x128_4w, true>},
+    {"f16 dma 64x64 s4 4w", 16, 64, 64, 64, run_dma<H_64x64_4w>, run_dma<H_64x64_4w, true>},
     {"w8 128x128 bk64 4w occ2", 8, 128, 128, 64, run_variant<W8_128x128_k64>},
     {"w8 128x128 bk128 4w occ2", 8, 128, 128, 128, run_variant<W8_128x128_k128>},
     {"w8 256x128 bk64 4w occ2", 8, 256, 128, 64, run_variant<W8_256x128_k64>},
@@ -1120,6 +1162,12 @@ static int choose_variant(const GemmArgs &a)
                      w8_k64 = find_variant("w8 128x128 bk64 4w occ3"), w4_any = find_variant("w4 any-group 128x64 bk128 4w occ3");
     // the register-staged kernel at 3 wavefronts per SIMD hides the per-group VALU work best; its any-group form, whose
     // four K slices share one copy of the loop body, is also the fastest at group 128 (108 against 127 us, fc1 at M = 8192)
+    if (a.w_bits == 16) {
+        static const int h_small = find_variant("f16 dma 64x64 s4 4w"), h_mid = find_variant("f16 dma 128x128 a3b2 4w spread1"),
+                         h_big = find_variant("f16 dma 256x192 a3b2 8w spread1");
+        if (a.M <= 512) return h_small;
+        return (long)((a.M + 255) / 256) * ((a.N + 191) / 192) >= 192 ? h_big : h_mid;
+    }
     if (a.w_bits == 4) return w4_any;
     if (a.K % 128 != 0) return w8_k64;
     if (a.M <= 512) return w8_small;
@@ -1140,7 +1188,7 @@ hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream)
 {
     // MFMA tiles need 16-byte loads along K and a whole number of K steps
     const bool fast = (a.K % 64 == 0) && ((uintptr_t)a.q % 16 == 0) && ((uintptr_t)a.w % 16 == 0) &&
-                      (a.w_bits == 8 || (a.K % 128 == 0 && a.group % 32 == 0));
+                      (a.w_bits != 4 || (a.K % 128 == 0 && a.group % 32 == 0));
     if (!fast || variant >= NUM_VARIANTS) {
         hipLaunchKernelGGL(qgemm_naive, dim3((a.M + 3) / 4, (a.N + 63) / 64), dim3(256), 0, stream, a);
         return hipGetLastError();

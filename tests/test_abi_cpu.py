@@ -202,3 +202,16 @@ def test_fused_epilogue_argument_checks():
     assert call(ql.ql_fusion(0, 0, None, 0x1000, 3)) == 2                     # M % gate_rows
     assert call(ql.ql_fusion(0, 0, None, 0x1000, 0)) == 2
     assert L.qlinear_w4a8_fused(FAKE, 8, 1152, 1, FAKE, FAKE, 48, None, 8, None, FAKE, ws, big, None) == 4   # bad group
+
+
+def test_fp16_layer_argument_checks():
+    L = ql.lib()
+    assert L.qlinear_f16(None, 4, 8, FAKE, None, 8, None, FAKE, None) == 1
+    assert L.qlinear_f16(FAKE, 4, 8, FAKE_ODD, None, 8, None, FAKE, None) == 3
+    assert L.qlinear_f16(FAKE, 0, 8, FAKE, None, 8, None, FAKE, None) == 2
+    h = ctypes.c_void_p()
+    d = ql.ql_layer_desc(64, 8, 16, 0, 0x1000, 0, 0)
+    assert L.ql_plan_create((ql.ql_layer_desc * 1)(d), 1, 16, ctypes.byref(h)) == 0     # FP16 layer: no scales needed
+    L.ql_plan_destroy(h)
+    d = ql.ql_layer_desc(64, 8, 16, 128, 0x1000, 0, 0)
+    assert L.ql_plan_create((ql.ql_layer_desc * 1)(d), 1, 16, ctypes.byref(h)) == 4     # groups belong to 4-bit layers

@@ -643,6 +643,76 @@ def test_fused_epilogue_with_nothing_to_fuse_is_the_plain_layer_and_misaligned_g
     assert assert_y_close(host(y), ref) == 0
 
 
+# ------------------------------------------------------------------ layers the plan leaves in FP16
+
+def _f16_tolerance(x, w, ref):
+    """fp32 accumulation of K exact products in any order: |error| <= K 2^-24 sum|x w| (loose standard bound), plus the
+    rounding to fp16 (the oracle's own fp16 result may sit one ulp away when the two sums straddle a rounding point)."""
+    K = x.shape[1]
+    mag = np.abs(x.astype(np.float64)) @ np.abs(w.astype(np.float64)).T
+    return K * 2.0 ** -24 * mag + 2.0 ** -10 * np.abs(ref.astype(np.float64)) + 2.0 ** -24
+
+
+F16_CASES = [(512, 1152, 384), (300, 1152, 200), (64, 1152, 128), (33, 100, 17), (4096, 1152, 1152), (256, 4608, 256)]
+
+
+@pytest.mark.parametrize("M,K,N", F16_CASES)
+def test_fp16_layer(gpu, orc, M, K, N):
+    say("f16 layer", M, K, N)
+    g = workload.rng("f16-gpu", M, K, N)
+    x = workload.activations(M, K, "f16-gpu", N)
+    w = (g.standard_normal((N, K), dtype=np.float32) * 0.05).astype(np.float16)
+    b = workload.bias(N, "f16-gpu")
+    ref = orc.linear_f16(x, w, b, nthreads=8)
+    y = host(gpu.qlinear_f16(dev(x), dev(w), dev(b)))
+    err = np.abs(y.astype(np.float64) - ref.astype(np.float64))
+    assert (err <= _f16_tolerance(x, w, ref)).all()
+    assert (y.view(np.uint16) != ref.view(np.uint16)).mean() < 0.02      # and almost all outputs are identical
+    y2 = host(gpu.qlinear_f16(dev(x), dev(w), None))
+    ref2 = orc.linear_f16(x, w, None, nthreads=8)
+    assert (np.abs(y2.astype(np.float64) - ref2.astype(np.float64)) <= _f16_tolerance(x, w, ref2)).all()
+
+
+def test_plan_with_fp16_int8_and_int4_layers(gpu, orc):
+    """A plan of the kind Section 6 ends with: FP16, W8 and W4 (two group sizes) layers side by side."""
+    import torch
+    M, R = 512, 1
+    g = workload.rng("plan-f16")
+    layers, xs, refs, tols = [], [], [], []
+    for name, K, N, bits, group in [("a", 1152, 256, 16, 0), ("b", 1152, 384, 8, 0), ("c", 1152, 192, 4, 288), ("d", 256, 128, 16, 0)]:
+        x = workload.activations(M, K, "plan-f16", name)
+        xs.append(dev(x))
+        if bits == 16:
+            w = (g.standard_normal((N, K), dtype=np.float32) * 0.05).astype(np.float16)
+            b = workload.bias(N, "plan-f16", name)
+            ref = orc.linear_f16(x, w, b, nthreads=8)
+            refs.append(ref)
+            tols.append(_f16_tolerance(x, w, ref))
+            layers.append(dict(K=K, N=N, bits=16, w=dev(w), w_scale=None, bias=dev(b)))
+            continue
+        lw = workload.layer_weights(name, K, N, bits, "plan-f16")
+        q, s = orc.daq(x, R)
+        if bits == 8:
+            refs.append(orc.epilogue_w8(orc.gemm_i8(q, lw["w"]), s, R, lw["s_w"], lw["bias"]))
+            layers.append(dict(K=K, N=N, bits=8, w=dev(lw["w"]), w_scale=dev(lw["s_w"]), bias=dev(lw["bias"])))
+        else:
+            sw = workload.w4_scales_group(N, K, group, name)
+            refs.append(orc.epilogue_w4(orc.gemm_w4g(q, orc.pack_w4(lw["w"]), group), s, R, sw, lw["bias"]))
+            layers.append(dict(K=K, N=N, bits=4, group=group, w=dev(gpu.ql_pack_w4_host(lw["w"])), w_scale=dev(sw), bias=dev(lw["bias"])))
+        tols.append(None)
+    plan = gpu.Plan(layers, M_max=M)
+    ys = [torch.zeros((M, l["N"]), dtype=torch.float16, device="cuda") for l in layers]
+    ws = gpu.workspace(plan.workspace_bytes(M, R))
+    plan.run(xs, ys, M, R, ws)
+    torch.cuda.synchronize()
+    for y, ref, tol in zip(ys, refs, tols):
+        if tol is None:
+            assert assert_y_close(host(y), ref) == 0
+        else:
+            assert (np.abs(host(y).astype(np.float64) - ref.astype(np.float64)) <= tol).all()
+    plan.close()
+
+
 # ------------------------------------------------------------------ plan runner
 
 def test_plan_runner_small_mixed_plan(gpu, orc):
