@@ -148,7 +148,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (every GPU box here has one); --gpus %d is not supported. "
-              "The path shards by rows with no exchange; see DESIGN.md." % args.gpus, file=sys.stderr)
+              "The path shards by rows (whole samples) with no exchange between GPUs." % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import torch
