@@ -291,16 +291,32 @@ def main():
     if not args.no_breakdown:
         reps = 20 if not big else 10
 
+        graph_ok = [True]
+
         def timed_graph(fn):
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g):
-                for _ in range(reps):
-                    fn()
-            g.replay()
-            torch.cuda.synchronize()
             a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            if graph_ok[0]:
+                try:
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g):
+                        for _ in range(reps):
+                            fn()
+                    g.replay()
+                    torch.cuda.synchronize()
+                    a0.record(stream)
+                    g.replay()
+                    a1.record(stream)
+                    torch.cuda.synchronize()
+                    return a0.elapsed_time(a1) * 1e-3 / reps
+                except Exception as e:   # no graph capture on this stack: plain back-to-back launches instead
+                    print("bench.py: HIP graph capture unavailable (%s); timing plain launch loops" % e, file=sys.stderr)
+                    graph_ok[0] = False
+                    torch.cuda.synchronize()
+            fn()
+            torch.cuda.synchronize()
             a0.record(stream)
-            g.replay()
+            for _ in range(reps):
+                fn()
             a1.record(stream)
             torch.cuda.synchronize()
             return a0.elapsed_time(a1) * 1e-3 / reps
