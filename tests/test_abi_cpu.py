@@ -215,3 +215,13 @@ def test_fp16_layer_argument_checks():
     L.ql_plan_destroy(h)
     d = ql.ql_layer_desc(64, 8, 16, 128, 0x1000, 0, 0)
     assert L.ql_plan_create((ql.ql_layer_desc * 1)(d), 1, 16, ctypes.byref(h)) == 4     # groups belong to 4-bit layers
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    """No fallback: without the built HIP library every entry point of the binding raises."""
+    monkeypatch.setattr(ql, "_lib", None)
+    monkeypatch.setattr(ql, "LIB_PATH", str(tmp_path / "libdiffpro_qlinear.so"))
+    with pytest.raises(ImportError, match="no fallback"):
+        ql.lib()
+    with pytest.raises(ImportError):
+        ql.daq_workspace_bytes(8, 8, 4)
