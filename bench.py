@@ -38,18 +38,20 @@ TRAFFIC_BYTES_PER_LAUNCH = {
 def build_layers(ql, torch, wl_name, w4_group=128):
     wl = workload.WORKLOADS[wl_name]
     if wl["layers"] == "bit_plan":
-        descs = [(p["name"], p["K"], p["N"], p["bits"], p["block"]) for p in workload.bit_plan()]
+        descs = [(p["name"], p["K"], p["N"], p["bits"], p["block"], w4_group) for p in workload.bit_plan()]
+    elif wl["layers"] == "final_plan":
+        descs = [(p["name"], p["K"], p["N"], p["bits"], p["block"], p["group"] or 128) for p in workload.final_plan()]
     else:
-        descs = [(n, k, o, b, 0) for (n, k, o, b) in wl["layers"]]
+        descs = [(n, k, o, b, 0, w4_group) for (n, k, o, b) in wl["layers"]]
     layers = []
-    for name, K, N, bits, blk in descs:
+    for name, K, N, bits, blk, group in descs:
         lw = workload.layer_weights(name, K, N, bits, wl_name, blk)
-        w = lw["w"] if bits == 8 else ql.ql_pack_w4_host(lw["w"])
-        if bits == 4 and w4_group != 128:
-            lw = dict(lw, s_w=workload.w4_scales_group(N, K, w4_group, wl_name, name, blk))
-        layers.append(dict(name=name, K=K, N=N, bits=bits, group=w4_group, w=torch.from_numpy(w).cuda(),
-                           w_scale=torch.from_numpy(lw["s_w"]).cuda(), bias=torch.from_numpy(lw["bias"]).cuda(),
-                           host=lw))
+        w = ql.ql_pack_w4_host(lw["w"]) if bits == 4 else lw["w"]
+        if bits == 4 and group != 128:
+            lw = dict(lw, s_w=workload.w4_scales_group(N, K, group, wl_name, name, blk))
+        layers.append(dict(name=name, K=K, N=N, bits=bits, group=group, w=torch.from_numpy(w).cuda(),
+                           w_scale=None if lw["s_w"] is None else torch.from_numpy(lw["s_w"]).cuda(),
+                           bias=torch.from_numpy(lw["bias"]).cuda(), host=lw))
     return wl, layers
 
 
@@ -72,7 +74,9 @@ def build_inputs(ql, torch, wl_name, wl, layers):
             x[name] = torch.from_numpy(workload.activations(M, K, wl_name, name, s, sigma=float(sig[s]))).cuda()
         if "fc2" in types and "fc1" in types:
             fc1 = next(l for l in layers if l["name"] == "fc1")
-            if fc1["bits"] == 8:
+            if fc1["bits"] == 16:
+                y1 = ql.qlinear_f16(x["fc1"], fc1["w"], fc1["bias"])
+            elif fc1["bits"] == 8:
                 y1 = ql.qlinear_w8a8(x["fc1"], R, fc1["w"], fc1["w_scale"], fc1["bias"])
             else:
                 y1 = ql.qlinear_w4a8(x["fc1"], R, fc1["w"], fc1["w_scale"], fc1["bias"], group=fc1["group"])
@@ -102,13 +106,15 @@ def cpu_baseline(wl_name, wl, layers, budget_rows=16384, min_seconds=10.0, max_p
     for l in uniq.values():
         x = workload.activations(rows, l["K"], wl_name, l["name"], "cpu")
         lw = l["host"]
-        w = lw["w"] if l["bits"] == 8 else oracle.pack_w4(lw["w"])
+        w = oracle.pack_w4(lw["w"]) if l["bits"] == 4 else lw["w"]
         prepared.append((l, x, w, lw))
     t_total, macs, passes = 0.0, 0, 0
     while passes < max_passes and (passes == 0 or t_total < min_seconds):
         for l, x, w, lw in prepared:
             t0 = time.perf_counter()
-            if l["bits"] == 8:
+            if l["bits"] == 16:
+                oracle.linear_f16(x, w, lw["bias"], nthreads=threads)
+            elif l["bits"] == 8:
                 oracle.qlinear_w8a8(x, Rs, w, lw["s_w"], lw["bias"], nthreads=threads, want_debug=False)
             else:
                 if l["group"] == 128:
@@ -321,12 +327,15 @@ def main():
             torch.cuda.synchronize()
             return a0.elapsed_time(a1) * 1e-3 / reps
 
+        def kind(l):
+            return (l["name"], l["bits"]) if l["bits"] != 4 or l["group"] == args.w4_group else (l["name"], "4g%d" % l["group"])
+
         uniq = {}
         for l in layers:
-            uniq.setdefault((l["name"], l["bits"]), l)
+            uniq.setdefault(kind(l), l)
         counts = {}
         for l in layers:
-            counts[(l["name"], l["bits"])] = counts.get((l["name"], l["bits"]), 0) + 1
+            counts[kind(l)] = counts.get(kind(l), 0) + 1
         gemm_time, gemm_ops, gemm_n, daq_time, daq_bytes, daq_n = 0.0, 0.0, 0, 0.0, 0.0, 0
         for key, l in uniq.items():
             x = pool[0][l["name"]]
@@ -334,7 +343,10 @@ def main():
             sa = torch.empty((M // R,), dtype=torch.float32, device="cuda")
             dws = ql.workspace(ql.daq_workspace_bytes(M, l["K"], R))
             y = torch.empty((M, l["N"]), dtype=torch.float16, device="cuda")
-            if l["bits"] == 8:
+            if l["bits"] == 16:
+                # a layer left in FP16: no DAQ; the "GEMM" is the whole layer on the fp16 input
+                gfn = (lambda q_, sa_, R_, w_, ws_, b_, y=None, _x=x: ql.qlinear_f16(_x, w_, b_, y=y))
+            elif l["bits"] == 8:
                 gfn = ql.qgemm_w8a8
             else:
                 gfn = (lambda *a, _g=l["group"], **kw: ql.qgemm_w4a8(*a, group=_g, **kw))
@@ -343,19 +355,19 @@ def main():
             gfn(q, sa, R, l["w"], l["w_scale"], l["bias"], y=y)
             torch.cuda.synchronize()
             q_ref, y_ref = q.clone(), y.clone()
-            td = timed_graph(lambda: run_daq(x, q, sa, dws))
+            td = timed_graph(lambda: run_daq(x, q, sa, dws)) if l["bits"] != 16 else 0.0
             tg = timed_graph(lambda: gfn(q, sa, R, l["w"], l["w_scale"], l["bias"], y=y))
             if not (torch.equal(q, q_ref) and torch.equal(y, y_ref)):
-                raise RuntimeError("graph replay of %s/w%d differs from the eager launch" % key)
+                raise RuntimeError("graph replay of %s/w%s differs from the eager launch" % key)
             ops = 2.0 * M * l["N"] * l["K"]
             dbytes = 3.0 * M * l["K"] + 4.0 * (M // R)
-            breakdown["%s/w%d" % key] = {"daq_us": td * 1e6, "gemm_us": tg * 1e6, "gemm_tops": ops / tg / 1e12,
-                                          "daq_gbs": dbytes / td / 1e9, "launches_per_step": counts[key]}
+            breakdown["%s/w%s" % key] = {"daq_us": td * 1e6, "gemm_us": tg * 1e6, "gemm_tops": ops / tg / 1e12,
+                                          "daq_gbs": (dbytes / td / 1e9) if td else None, "launches_per_step": counts[key]}
             gemm_time += tg * counts[key]
             gemm_ops += ops * counts[key]
             gemm_n += counts[key]
             daq_time += td * counts[key]
-            daq_bytes += dbytes * counts[key]
+            daq_bytes += (dbytes if td else 0.0) * counts[key]
             daq_n += counts[key]
             del q, sa, y, q_ref, y_ref
         # the matrix cores' own ceiling on this machine: a register-resident MFMA loop, 2 workgroups per CU

@@ -112,6 +112,33 @@ def bit_plan(n_blocks=N_BLOCKS, p_w4=77.0 / 91.0, protect=3, *key):
     return plan
 
 
+def final_plan(n_blocks=N_BLOCKS, *key):
+    """The kind of plan the paper ends Step 2 with, over the 4*n_blocks block linears: of its 113 layers 77 are W4,
+    14 W8 and 22 FP16, with group sizes 288 (86 layers), 64 (9), 128 (5), 192 (6) and 32 (7).  The 113th layer (the final
+    projection) is not a block linear; it is taken to be one of the FP16, group-288 entries.  Which layer gets which
+    entry is a seeded shuffle (the paper does not list them).  Returns dicts(name, block, K, N, bits, group)."""
+    g = rng("final-plan", n_blocks, *key)
+    n = 4 * n_blocks
+    bits = [4] * 77 + [8] * 14 + [16] * 21
+    groups = [288] * 85 + [64] * 9 + [128] * 5 + [192] * 6 + [32] * 7
+    if n != len(bits):      # other depths: same proportions
+        bits = [bits[i * len(bits) // n] for i in range(n)]
+        groups = [groups[i * len(groups) // n] for i in range(n)]
+    bits = [bits[i] for i in g.permutation(n)]
+    groups = [groups[i] for i in g.permutation(n)]
+    plan, i = [], 0
+    for b in range(n_blocks):
+        for name, K, N in BLOCK_LAYERS:
+            plan.append(dict(name=name, block=b, K=K, N=N, bits=bits[i], group=groups[i] if bits[i] == 4 else 0))
+            i += 1
+    return plan
+
+
+def f16_weights(N, K, *key):
+    """fp16 [N,K] ~ N(0, 0.02^2): the weights of a layer the plan leaves unquantized."""
+    return (rng("w16", N, K, *key).standard_normal((N, K), dtype=np.float32) * np.float32(0.02)).astype(np.float16)
+
+
 # Workloads (rows M, DAQ rows-per-scale R, layers, steps); the keys match the
 # benchmark's --workload flag.
 WORKLOADS = {
@@ -127,6 +154,8 @@ WORKLOADS = {
     "c4_block_w8a8_m16384": dict(M=16384, R=1, steps=50, layers=[(n, k, o, 8) for n, k, o in BLOCK_LAYERS]),
     # the full 28-block stack under a seeded bit plan, 64 images x 256 tokens, 25 timesteps
     "c5_stack_plan_m16384": dict(M=16384, R=1, steps=25, layers="bit_plan"),
+    # the same stack under a plan of the paper's final kind: W4 with mixed group sizes, W8 and FP16 layers
+    "c6_stack_final_plan_m16384": dict(M=16384, R=1, steps=25, layers="final_plan"),
 }
 
 
@@ -136,4 +165,6 @@ def layer_weights(name, K, N, bits, *key):
         return dict(bits=8, w=w8_codes(N, K, name, *key), s_w=w8_scales(N, name, *key), bias=bias(N, name, *key))
     if bits == 4:
         return dict(bits=4, w=w4_codes(N, K, name, *key), s_w=w4_scales(N, K, name, *key), bias=bias(N, name, *key))
-    raise ValueError("bits must be 4 or 8")
+    if bits == 16:
+        return dict(bits=16, w=f16_weights(N, K, name, *key), s_w=None, bias=bias(N, name, *key))
+    raise ValueError("bits must be 4, 8 or 16")
