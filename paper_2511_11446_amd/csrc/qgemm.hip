@@ -1095,6 +1095,8 @@ using P8_128x192_s2 = TileD<2, 3, 2, 2, 2, 2, true, 1, false, 2, true>;
 using H_256x192_8w = TileD<2, 3, 4, 2, 3, 2, true, 1, false, 2, false, true>;
 using H_128x128_4w = TileD<2, 2, 2, 2, 3, 2, true, 1, false, 2, false, true>;
 using H_64x64_4w = TileD<1, 1, 2, 2, 4, 4, true, 0, false, 4, false, true>;
+using H_p192 = TileD<2, 3, 2, 2, 2, 2, true, 1, false, 2, true, true>;
+using H_p128 = TileD<2, 2, 2, 2, 3, 2, true, 1, false, 2, true, true>;
 
 static const Variant VARIANTS[] = {
     {"w8 dma 128x128 s3 4w", 8, 128, 128, 128, run_dma<D8_128x128_s3>},
@@ -1122,6 +1124,8 @@ static const Variant VARIANTS[] = {
     {"f16 dma 256x192 a3b2 8w spread1", 16, 256, 192, 64, run_dma<H_256x192_8w>, run_dma<H_256x192_8w, true>},
     {"f16 dma 128x128 a3b2 4w spread1", 16, 128, 128, 64, run_dma<H_128x128_4w>, run_dma<H_128x128_4w, true>},
     {"f16 dma 64x64 s4 4w", 16, 64, 64, 64, run_dma<H_64x64_4w>, run_dma<H_64x64_4w, true>},
+    {"f16 dma 128x192 s2 4w spread1 persistent", 16, 128, 192, 64, run_dma<H_p192>},
+    {"f16 dma 128x128 a3b2 4w spread1 persistent", 16, 128, 128, 64, run_dma<H_p128>},
     {"w8 128x128 bk64 4w occ2", 8, 128, 128, 64, run_variant<W8_128x128_k64>},
     {"w8 128x128 bk128 4w occ2", 8, 128, 128, 128, run_variant<W8_128x128_k128>},
     {"w8 256x128 bk64 4w occ2", 8, 256, 128, 64, run_variant<W8_256x128_k64>},
@@ -1164,9 +1168,11 @@ static int choose_variant(const GemmArgs &a)
     // four K slices share one copy of the loop body, is also the fastest at group 128 (108 against 127 us, fc1 at M = 8192)
     if (a.w_bits == 16) {
         static const int h_small = find_variant("f16 dma 64x64 s4 4w"), h_mid = find_variant("f16 dma 128x128 a3b2 4w spread1"),
-                         h_big = find_variant("f16 dma 256x192 a3b2 8w spread1");
+                         h_big = find_variant("f16 dma 256x192 a3b2 8w spread1"),
+                         h_p192 = find_variant("f16 dma 128x192 s2 4w spread1 persistent");
         if (a.M <= 512) return h_small;
-        return (long)((a.M + 255) / 256) * ((a.N + 191) / 192) >= 192 ? h_big : h_mid;
+        if ((long)((a.M + 255) / 256) * ((a.N + 191) / 192) < 192) return h_mid;
+        return (a.M >= 4096 && a.N < 4096) ? h_p192 : h_big;
     }
     if (a.w_bits == 4) return w4_any;
     if (a.K % 128 != 0) return w8_k64;
@@ -1208,8 +1214,8 @@ hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream)
         if (!VARIANTS[v].run_glue) v = choose_variant(a);
         // the prefetched gate and residual pieces need registers the persistent tiles do not have left
         // (256x192 and two resident 128x128 workgroups per CU measure alike here: 495 and 491 us for a block at M = 16384)
-        static const int big = find_variant("w8 dma 256x192 a3b2 8w spread1");
-        if (__builtin_strstr(VARIANTS[v].name, "persistent")) v = big;
+        static const int big = find_variant("w8 dma 256x192 a3b2 8w spread1"), hbig = find_variant("f16 dma 256x192 a3b2 8w spread1");
+        if (__builtin_strstr(VARIANTS[v].name, "persistent")) v = a.w_bits == 16 ? hbig : big;
         return VARIANTS[v].run_glue(a, stream);
     }
     return VARIANTS[v].run(a, stream);

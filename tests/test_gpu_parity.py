@@ -673,6 +673,23 @@ def test_fp16_layer(gpu, orc, M, K, N):
     assert (np.abs(y2.astype(np.float64) - ref2.astype(np.float64)) <= _f16_tolerance(x, w, ref2)).all()
 
 
+def test_fp16_layer_with_glue_on_a_shape_that_picks_a_persistent_tile(gpu, orc):
+    M, K, N = 4096, 1152, 1152
+    g = workload.rng("f16-glue")
+    x = workload.activations(M, K, "f16-glue")
+    w = (g.standard_normal((N, K), dtype=np.float32) * 0.05).astype(np.float16)
+    res = g.standard_normal((M, N), dtype=np.float32).astype(np.float16)
+    gate = g.standard_normal((M // 256, N), dtype=np.float32).astype(np.float16)
+    rows = np.sort(g.choice(M, size=256, replace=False))
+    y = host(gpu.qlinear_f16(dev(x), dev(w), None, residual=dev(res), gate=dev(gate), gate_rows=256))[rows]
+    h = orc.linear_f16(x[rows], w, None, nthreads=8)
+    ref = (gate[rows // 256].astype(np.float32) * h.astype(np.float32) + res[rows].astype(np.float32)).astype(np.float16)
+    # h may sit one fp16 ulp from the oracle's (fp32 against fp64 sums); the gate carries that into y
+    tol = _f16_tolerance(x[rows], w, h) * np.abs(gate[rows // 256].astype(np.float64)) + 2.0 ** -10 * np.abs(ref.astype(np.float64)) + 2.0 ** -24
+    assert (np.abs(y.astype(np.float64) - ref.astype(np.float64)) <= tol).all()
+    assert (y.view(np.uint16) != ref.view(np.uint16)).mean() < 0.02
+
+
 def test_plan_with_fp16_int8_and_int4_layers(gpu, orc):
     """A plan of the kind Section 6 ends with: FP16, W8 and W4 (two group sizes) layers side by side."""
     import torch
