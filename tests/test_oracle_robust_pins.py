@@ -240,3 +240,48 @@ def test_fp16_layer_against_numpy_float64_and_closed_forms(orc):
     # an exactly representable case with cancellation that fp32 running sums would lose: 2048 + 1 - 2048 = 1
     xc = np.array([[2048.0, 1.0, -2048.0]], np.float16)
     assert orc.linear_f16(xc, np.ones((1, 3), np.float16))[0, 0] == np.float16(1.0)
+
+
+# ---------------------------------------------------------------- fixtures under tests/golden
+
+def _golden(name):
+    import os
+    with open(os.path.join(os.path.dirname(__file__), "golden", name)) as f:
+        return [l.strip() for l in f if l.strip() and not l.startswith("#")]
+
+
+def test_golden_final_plan_counts_match_the_synthetic_final_plan():
+    import collections
+    want_bits, want_groups, total = {}, {}, 0
+    for l in _golden("final_plan_counts.txt"):
+        p = l.split()
+        if p[0] == "layers":
+            total = int(p[1])
+        elif p[0] == "bits":
+            want_bits[int(p[1])] = int(p[2])
+        else:
+            want_groups[int(p[1])] = int(p[2])
+    assert sum(want_bits.values()) == total == sum(want_groups.values()) == 113
+    plan = workload.final_plan()
+    # the 113th layer (final projection) is outside the block linears; it is taken to be an FP16, group-288 entry
+    got = collections.Counter(l["bits"] for l in plan)
+    assert got[4] == want_bits[4] and got[8] == want_bits[8] and got[16] == want_bits[16] - 1 and len(plan) == total - 1
+    assert all(l["group"] in want_groups for l in plan if l["bits"] == 4)
+    assert all(l["K"] % l["group"] == 0 for l in plan if l["bits"] == 4)
+
+
+def test_golden_hand_worked_daq_rows(orc):
+    for l in _golden("daq_hand_worked.txt"):
+        parts = [p.strip() for p in l.split("|")]
+        if parts[0] == "p90":
+            x = f16([[float(v) for v in parts[1].split()]])
+            q, s = orc.daq_robust(x, 1, p_ppm=900000, a_bits=8)
+            tau = float(parts[2].split()[1])
+            assert s[0] == np.float32(tau) / np.float32(127)
+            for item in parts[3:]:
+                idx = int(item[item.index("[") + 1:item.index("]")])
+                assert q[0, idx] == int(item.split()[-1])
+            continue
+        alpha, xs, codes = float(parts[0]), [float(v) for v in parts[1].split()], [int(v) for v in parts[2].split()]
+        q, s = orc.daq(f16([xs]), 1)
+        assert s[0] == np.float32(alpha) and q.tolist() == [codes]
