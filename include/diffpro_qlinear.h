@@ -214,6 +214,13 @@ int qlinear_f16(const void *x, int64_t M, int64_t K,
  * K % 8 == 0.  Returns QL_ERR_SHAPE for a code outside [-8,7]. */
 int ql_pack_w4_host(const int8_t *codes, int64_t N, int64_t K, uint8_t *packed);
 
+/* Host helper for weights that already sit two per byte in the common pair order
+ * (byte i of a row holds k = 2i in its low nibble and k = 2i+1 in its high nibble,
+ * two's-complement nibbles): rewrites them, [N,K/2] bytes (host) to [N,K/2] bytes
+ * (host), into the storage order qlinear_w4a8 reads.  K % 8 == 0; in place is not
+ * supported (QL_ERR_UNSUPPORTED). */
+int ql_repack_w4_pairs_host(const uint8_t *pairs, int64_t N, int64_t K, uint8_t *packed);
+
 /* ------------------------------------------------------------------------
  * Plan runner: Algorithm 2, Phase B ("wrap layers per the bit plan ... forward
  * with quantized weights and activations") and Step 6, restricted to the

@@ -22,7 +22,7 @@ EXPORTS = ("ql_status_string", "ql_last_device_error", "ql_version", "daq_worksp
            "ql_pack_w4_host", "ql_plan_create", "ql_plan_destroy", "ql_plan_num_layers",
            "ql_plan_workspace_bytes", "qlinear_plan_run", "ql_set_gemm_variant", "ql_num_gemm_variants",
            "ql_gemm_variant_name", "ql_probe_mfma_int8", "daq_quantize_robust", "qlinear_plan_run_robust", "ql_time_bin",
-           "qlinear_w4a8_g", "qgemm_w4a8_g", "qlinear_w8a8_fused", "qlinear_w4a8_fused", "qlinear_f16")
+           "qlinear_w4a8_g", "qgemm_w4a8_g", "qlinear_w8a8_fused", "qlinear_w4a8_fused", "qlinear_f16", "ql_repack_w4_pairs_host")
 
 
 class QlError(RuntimeError):
@@ -95,6 +95,8 @@ def lib():
     L.qlinear_w8a8_fused.restype = _int
     L.qlinear_w4a8_fused.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _i64, _vp, _i64, ctypes.POINTER(ql_fusion), _vp, _vp, _sz, _vp]
     L.qlinear_w4a8_fused.restype = _int
+    L.ql_repack_w4_pairs_host.argtypes = [_vp, _i64, _i64, _vp]
+    L.ql_repack_w4_pairs_host.restype = _int
     L.qlinear_f16.argtypes = [_vp, _i64, _i64, _vp, _vp, _i64, ctypes.POINTER(ql_fusion), _vp, _vp]
     L.qlinear_f16.restype = _int
     L.qlinear_plan_run_robust.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _i64, _i64, _vp, _vp, _sz, _vp]
@@ -395,3 +397,13 @@ def probe_mfma_int8(iters, blocks, sink, stream=None):
     """Enqueue the register-resident MFMA loop; returns the number of int8 operations it performs."""
     _check(lib().ql_probe_mfma_int8(iters, blocks, _ptr(sink), _stream(stream)), "ql_probe_mfma_int8")
     return 2.0 * 32 * 32 * 32 * 4 * iters * 4 * blocks
+
+
+def ql_repack_w4_pairs_host(pairs):
+    """uint8 [N,K/2] in pair order (low nibble = even k, high nibble = odd k) -> the library's 4-bit storage order."""
+    import numpy as np
+    pairs = np.ascontiguousarray(pairs, dtype=np.uint8)
+    N, K2 = pairs.shape
+    out = np.empty_like(pairs)
+    _check(lib().ql_repack_w4_pairs_host(pairs.ctypes.data_as(_vp), N, K2 * 2, out.ctypes.data_as(_vp)), "ql_repack_w4_pairs_host")
+    return out

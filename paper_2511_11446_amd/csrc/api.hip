@@ -401,6 +401,21 @@ int ql_pack_w4_host(const int8_t *codes, int64_t N, int64_t K, uint8_t *packed)
     return QL_OK;
 }
 
+int ql_repack_w4_pairs_host(const uint8_t *pairs, int64_t N, int64_t K, uint8_t *packed)
+{
+    if (!pairs || !packed) return QL_ERR_NULL;
+    if (pairs == packed) return QL_ERR_UNSUPPORTED;
+    if (N < 1 || K < 1 || K % 8 != 0) return QL_ERR_SHAPE;
+    for (int64_t n = 0; n < N; ++n) {
+        const uint8_t *src = pairs + n * (K / 2);   // byte i: k = 2i in the low nibble, k = 2i+1 in the high nibble
+        uint8_t *dst = packed + n * (K / 2);
+        auto nib = [&](int64_t k) { return (uint8_t)((k & 1) ? (src[k / 2] >> 4) : (src[k / 2] & 0xf)); };
+        for (int64_t blk = 0; blk < K / 8; ++blk)
+            for (int j = 0; j < 4; ++j) dst[4 * blk + j] = (uint8_t)(nib(8 * blk + j) | (nib(8 * blk + 4 + j) << 4));
+    }
+    return QL_OK;
+}
+
 int ql_plan_create(const ql_layer_desc *layers, int32_t n_layers, int64_t M_max, ql_plan **plan_out)
 {
     if (!layers || !plan_out) return QL_ERR_NULL;

@@ -225,3 +225,17 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
         ql.lib()
     with pytest.raises(ImportError):
         ql.daq_workspace_bytes(8, 8, 4)
+
+
+def test_repack_from_pair_order_equals_packing_the_codes(orc):
+    g = workload.rng("repack")
+    w = g.integers(-8, 8, size=(5, 64), dtype=np.int8)
+    pairs = ((w[:, 0::2] & 0xF) | ((w[:, 1::2] & 0xF) << 4)).astype(np.uint8)      # low nibble = even k, high nibble = odd k
+    got = ql.ql_repack_w4_pairs_host(pairs)
+    assert np.array_equal(got, ql.ql_pack_w4_host(w))
+    assert np.array_equal(orc.unpack_w4(got, 64), w)
+    L = ql.lib()
+    buf = pairs.ctypes.data_as(ctypes.c_void_p)
+    assert L.ql_repack_w4_pairs_host(buf, 5, 64, buf) == 4          # in place
+    assert L.ql_repack_w4_pairs_host(buf, 5, 60, buf) in (2, 4)
+    assert L.ql_repack_w4_pairs_host(None, 5, 64, buf) == 1
