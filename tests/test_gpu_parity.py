@@ -730,6 +730,48 @@ def test_plan_with_fp16_int8_and_int4_layers(gpu, orc):
     plan.close()
 
 
+# ------------------------------------------------------------------ the final-plan features at full size (sampled rows)
+
+def test_full_size_group288_fp16_and_fused_layers_sampled(gpu, orc):
+    """M = 16384, the launch configuration the c6 workload times: a W4 layer with groups of 288, an FP16 layer and a
+    fused W8 layer; the oracle recomputes a seeded sample of rows."""
+    import torch
+    M, K, N = 16384, 1152, 3456
+    g = workload.rng("full-final")
+    rows = np.sort(g.choice(M, size=64, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    idx = torch.from_numpy(rows).cuda()
+    x = workload.activations(M, K, "full-final", sigma=1.0)
+    xd = dev(x)
+    q_ref, s_ref = orc.daq(x[rows], 1, nthreads=8)
+    # W4, groups of 288
+    say("full size w4 g288")
+    lw = workload.layer_weights("qkv", K, N, 4, "full-final")
+    sw = workload.w4_scales_group(N, K, 288, "full-final")
+    y = gpu.qlinear_w4a8(xd, 1, dev(gpu.ql_pack_w4_host(lw["w"])), dev(sw), dev(lw["bias"]), group=288)
+    ref = orc.epilogue_w4(orc.gemm_w4g(q_ref, orc.pack_w4(lw["w"]), 288, nthreads=8), s_ref, 1, sw, lw["bias"])
+    assert assert_y_close(host(y[idx]), ref) == 0
+    # FP16 layer
+    say("full size fp16")
+    w16 = workload.f16_weights(N, K, "full-final")
+    b16 = workload.bias(N, "full-final")
+    y = gpu.qlinear_f16(xd, dev(w16), dev(b16))
+    ref = orc.linear_f16(x[rows], w16, b16, nthreads=8)
+    assert (np.abs(host(y[idx]).astype(np.float64) - ref.astype(np.float64)) <= _f16_tolerance(x[rows], w16, ref)).all()
+    # fused W8 layer: gated residual (no transcendental: identical)
+    say("full size fused w8")
+    lw8 = workload.layer_weights("qkv", K, N, 8, "full-final")
+    res = g.standard_normal((M, N), dtype=np.float32).astype(np.float16)
+    gate = g.standard_normal((M // 256, N), dtype=np.float32).astype(np.float16)
+    y = gpu.qlinear_fused(xd, 1, dev(lw8["w"]), dev(lw8["s_w"]), dev(lw8["bias"]), residual=dev(res), gate=dev(gate), gate_rows=256)
+    u = orc.dequant_w8(orc.gemm_i8(q_ref, lw8["w"], nthreads=8), s_ref, 1, lw8["s_w"], lw8["bias"])
+    # the oracle on the gathered rows, each with its own gate row
+    ref = orc.block_glue(u, residual=res[rows], gate=gate[rows // 256], gate_rows=1)
+    assert assert_y_close(host(y[idx]), ref) == 0
+    del y
+    torch.cuda.empty_cache()
+
+
 # ------------------------------------------------------------------ plan runner
 
 def test_plan_runner_small_mixed_plan(gpu, orc):
