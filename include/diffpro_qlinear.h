@@ -281,6 +281,14 @@ int qlinear_plan_run_robust(const ql_plan *plan, const void *const *x_in, void *
                             int64_t M, int64_t R, const ql_daq_params *params,
                             void *workspace, size_t workspace_bytes, void *stream);
 
+/* The plan walk with everything optional switched per call (Algorithm 2 Phase B: "forward with quantized weights and
+ * activations" for one step of the schedule): params as in qlinear_plan_run_robust or NULL (absolute maximum, 8 bits;
+ * FP16 layers ignore it), fusion = NULL or a host array of n_layers pointers, entry l NULL or the glue folded into
+ * layer l's epilogue (see ql_fusion).  Everything else as qlinear_plan_run. */
+int qlinear_plan_run_ex(const ql_plan *plan, const void *const *x_in, void *const *y_out,
+                        int64_t M, int64_t R, const ql_daq_params *params, const ql_fusion *const *fusion,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
 /* Host helper for the time-bin policy of Step 6: bin of step `step` (0-based, in
  * sampling order) out of num_steps, equal thirds: 0 early, 1 mid, 2 late;
  * -1 for arguments out of range.  The caller maps the bin to a_bits. */

@@ -22,7 +22,7 @@ EXPORTS = ("ql_status_string", "ql_last_device_error", "ql_version", "daq_worksp
            "ql_pack_w4_host", "ql_plan_create", "ql_plan_destroy", "ql_plan_num_layers",
            "ql_plan_workspace_bytes", "qlinear_plan_run", "ql_set_gemm_variant", "ql_num_gemm_variants",
            "ql_gemm_variant_name", "ql_probe_mfma_int8", "daq_quantize_robust", "qlinear_plan_run_robust", "ql_time_bin",
-           "qlinear_w4a8_g", "qgemm_w4a8_g", "qlinear_w8a8_fused", "qlinear_w4a8_fused", "qlinear_f16", "ql_repack_w4_pairs_host")
+           "qlinear_w4a8_g", "qgemm_w4a8_g", "qlinear_w8a8_fused", "qlinear_w4a8_fused", "qlinear_f16", "ql_repack_w4_pairs_host", "qlinear_plan_run_ex")
 
 
 class QlError(RuntimeError):
@@ -97,6 +97,8 @@ def lib():
     L.qlinear_w4a8_fused.restype = _int
     L.ql_repack_w4_pairs_host.argtypes = [_vp, _i64, _i64, _vp]
     L.ql_repack_w4_pairs_host.restype = _int
+    L.qlinear_plan_run_ex.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _i64, _i64, _vp, ctypes.POINTER(ctypes.POINTER(ql_fusion)), _vp, _sz, _vp]
+    L.qlinear_plan_run_ex.restype = _int
     L.qlinear_f16.argtypes = [_vp, _i64, _i64, _vp, _vp, _i64, ctypes.POINTER(ql_fusion), _vp, _vp]
     L.qlinear_f16.restype = _int
     L.qlinear_plan_run_robust.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _i64, _i64, _vp, _vp, _sz, _vp]
@@ -371,6 +373,27 @@ class Plan:
         prm = _DaqParams(p_ppm, a_bits)
         _check(lib().qlinear_plan_run_robust(self.handle, xs, ys, M, R, ctypes.byref(prm), _ptr(ws), ws.numel(), stream_ptr),
                "qlinear_plan_run_robust")
+
+    def run_ex(self, x_in, y_out, M, R, ws, fusions=None, p_ppm=None, a_bits=8, stream=None):
+        """The plan walk with optional percentile DAQ (p_ppm) and per-layer glue: fusions = list of None or
+        dict(act, residual, gate, gate_rows) per layer."""
+        xs = (_vp * self.L)(*[t.data_ptr() for t in x_in])
+        ys = (_vp * self.L)(*[t.data_ptr() for t in y_out])
+        prm = None if p_ppm is None else ctypes.byref(_DaqParams(p_ppm, a_bits))
+        fus = None
+        keep = []
+        if fusions is not None:
+            arr = (ctypes.POINTER(ql_fusion) * self.L)()
+            for i, f in enumerate(fusions):
+                if f is None:
+                    continue
+                fu = ql_fusion(f.get("act", 0), 0, None if f.get("residual") is None else f["residual"].data_ptr(),
+                               None if f.get("gate") is None else f["gate"].data_ptr(), f.get("gate_rows", 1))
+                keep.append(fu)
+                arr[i] = ctypes.pointer(fu)
+            fus = arr
+        _check(lib().qlinear_plan_run_ex(self.handle, xs, ys, M, R, prm, fus, _ptr(ws), ws.numel(), _stream(stream)),
+               "qlinear_plan_run_ex")
 
     def close(self):
         if self.handle:

@@ -457,7 +457,8 @@ size_t ql_plan_workspace_bytes(const ql_plan *plan, int64_t M, int64_t R)
 }
 
 static int plan_run_any(const ql_plan *plan, const void *const *x_in, void *const *y_out, int64_t M, int64_t R,
-                        const ql_daq_params *dp, void *workspace, size_t workspace_bytes, void *stream)
+                        const ql_daq_params *dp, void *workspace, size_t workspace_bytes, void *stream,
+                        const ql_fusion *const *fusion = nullptr)
 {
     if (!plan || !x_in || !y_out) return QL_ERR_NULL;
     if (M < 1 || R < 1 || M % R != 0 || M > plan->M_max) return QL_ERR_SHAPE;
@@ -468,11 +469,16 @@ static int plan_run_any(const ql_plan *plan, const void *const *x_in, void *cons
     }
     int rc = check_workspace(workspace, workspace_bytes, ql_plan_workspace_bytes(plan, M, R));
     if (rc) return rc;
+    if (fusion)
+        for (size_t l = 0; l < plan->layers.size(); ++l) {
+            rc = check_fusion(fusion[l], M);
+            if (rc) return rc;
+        }
     hipStream_t s = static_cast<hipStream_t>(stream);
     for (size_t l = 0; l < plan->layers.size(); ++l) {
         const ql_layer_desc &d = plan->layers[l];
         rc = run_layer(x_in[l], M, d.K, R, d.w_bits, d.w, d.w_scale, d.bias, d.N, y_out[l], nullptr, workspace, s, dp,
-                       d.w_bits == 4 ? d.group : 128);
+                       d.w_bits == 4 ? d.group : 128, fusion ? fusion[l] : nullptr);
         if (rc) return rc;
     }
     return QL_OK;
@@ -482,6 +488,13 @@ int qlinear_plan_run(const ql_plan *plan, const void *const *x_in, void *const *
                      void *workspace, size_t workspace_bytes, void *stream)
 {
     return plan_run_any(plan, x_in, y_out, M, R, nullptr, workspace, workspace_bytes, stream);
+}
+
+int qlinear_plan_run_ex(const ql_plan *plan, const void *const *x_in, void *const *y_out, int64_t M, int64_t R,
+                        const ql_daq_params *params, const ql_fusion *const *fusion, void *workspace, size_t workspace_bytes,
+                        void *stream)
+{
+    return plan_run_any(plan, x_in, y_out, M, R, params, workspace, workspace_bytes, stream, fusion);
 }
 
 int qlinear_plan_run_robust(const ql_plan *plan, const void *const *x_in, void *const *y_out, int64_t M, int64_t R,

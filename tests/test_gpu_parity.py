@@ -808,6 +808,65 @@ def test_plan_runner_small_mixed_plan(gpu, orc):
     plan.close()
 
 
+def test_plan_run_ex_one_block_with_glue_and_percentile_daq(gpu, orc):
+    """One DiT block through the plan walk: qkv plain, proj and fc2 with gated residual, fc1 with GELU; then the same
+    block with the percentile DAQ at 6 activation bits."""
+    import torch
+    M, R, tokens = 512, 1, 256
+    g = workload.rng("plan-ex")
+    specs = [("qkv", 1152, 384, 8, 128), ("proj", 1152, 384, 4, 288), ("fc1", 1152, 512, 8, 128), ("fc2", 512, 384, 16, 0)]
+    res = g.standard_normal((M, 384), dtype=np.float32).astype(np.float16)
+    gate = g.standard_normal((M // tokens, 384), dtype=np.float32).astype(np.float16)
+    fus = [None, dict(residual=dev(res), gate=dev(gate), gate_rows=tokens), dict(act=gpu.ACT_GELU_TANH),
+           dict(residual=dev(res), gate=dev(gate), gate_rows=tokens)]
+    layers, xs, hosts = [], [], []
+    for name, K, N, bits, group in specs:
+        x = workload.activations(M, K, "plan-ex", name)
+        xs.append(x)
+        if bits == 16:
+            w = workload.f16_weights(N, K, "plan-ex")
+            b = workload.bias(N, "plan-ex", name)
+            hosts.append(dict(w=w, bias=b))
+            layers.append(dict(K=K, N=N, bits=16, w=dev(w), w_scale=None, bias=dev(b)))
+            continue
+        lw = workload.layer_weights(name, K, N, bits, "plan-ex")
+        if bits == 4:
+            lw = dict(lw, s_w=workload.w4_scales_group(N, K, group, "plan-ex"))
+        hosts.append(lw)
+        layers.append(dict(K=K, N=N, bits=bits, group=group, w=dev(lw["w"]) if bits == 8 else dev(gpu.ql_pack_w4_host(lw["w"])),
+                           w_scale=dev(lw["s_w"]), bias=dev(lw["bias"])))
+    plan = gpu.Plan(layers, M_max=M)
+    ys = [torch.zeros((M, l["N"]), dtype=torch.float16, device="cuda") for l in layers]
+    ws = gpu.workspace(plan.workspace_bytes(M, R))
+    xd = [dev(x) for x in xs]
+    for p_ppm, a_bits in ((None, 8), (990000, 6)):
+        say("plan_run_ex", p_ppm, a_bits)
+        plan.run_ex(xd, ys, M, R, ws, fusions=fus, p_ppm=p_ppm, a_bits=a_bits)
+        torch.cuda.synchronize()
+        for i, (name, K, N, bits, group) in enumerate(specs):
+            f = fus[i] or {}
+            r = res if "residual" in f else None
+            gt = gate if "gate" in f else None
+            if bits == 16:
+                h = orc.linear_f16(xs[i], hosts[i]["w"], hosts[i]["bias"], nthreads=8)
+                ref = orc.block_glue(h.astype(np.float32), residual=r, gate=gt, gate_rows=tokens)
+                tol = _f16_tolerance(xs[i], hosts[i]["w"], h) * np.abs(np.repeat(gate.astype(np.float64), tokens, 0)) \
+                    + 2.0 ** -10 * np.abs(ref.astype(np.float64)) + 2.0 ** -24
+                assert (np.abs(host(ys[i]).astype(np.float64) - ref.astype(np.float64)) <= tol).all()
+                continue
+            q, s = orc.daq(xs[i], R) if p_ppm is None else orc.daq_robust(xs[i], R, p_ppm=p_ppm, a_bits=a_bits)
+            if bits == 8:
+                u = orc.dequant_w8(orc.gemm_i8(q, hosts[i]["w"], nthreads=8), s, R, hosts[i]["s_w"], hosts[i]["bias"])
+            else:
+                u = orc.dequant_w4(orc.gemm_w4g(q, orc.pack_w4(hosts[i]["w"]), group, nthreads=8), s, R, hosts[i]["s_w"], hosts[i]["bias"])
+            ref = orc.block_glue(u, act=f.get("act", 0), residual=r, gate=gt, gate_rows=tokens)
+            if f.get("act", 0) == 0:
+                assert assert_y_close(host(ys[i]), ref) == 0
+            else:
+                assert_y_close(host(ys[i]), ref)       # GELU alone: within the fp16 tolerance
+    plan.close()
+
+
 def test_c5_plan_stack_m16384_sampled(gpu, orc):
     """The 112-layer stack under the seeded bit plan at full size; the oracle checks sampled rows of sampled layers."""
     import torch
