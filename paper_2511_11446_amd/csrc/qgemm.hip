@@ -3,10 +3,16 @@
 // The paper's linears are "INT8 x INT8 -> INT32 GEMMs" with per-output-channel
 // weight scales (Step 3, Step 5, Section 6) or per-group scales (Step 2).
 // Here: acc[m,n] = sum_k q[m,k] * w[n,k] on v_mfma_i32_32x32x32_i8, both
-// operands K-contiguous, tiles staged through LDS with a two-stage pipeline,
-// and the dequantization + bias + fp16 conversion applied to the accumulators
-// in registers.  4-bit weights are unpacked from nibbles to int8 (times 16) in
-// registers and every group of 128 k is folded into an fp32 sum with its scale.
+// operands K-contiguous, and the dequantization + bias + fp16 conversion applied
+// to the accumulators in registers.  Two kernel families:
+//   qgemm_dma   tiles go global -> LDS by DMA through rings of 2-3 stages, optional
+//               persistent walk over tiles; 8-bit weights, and binary16 operands for
+//               the layers a plan leaves in FP16
+//   qgemm_mfma  tiles staged through registers, two LDS buffers; 4-bit weights (nibbles
+//               unpacked to int8 times 16 in registers, every weight group folded into
+//               an fp32 sum with its scale) and 8-bit weights with K % 128 != 0
+// plus a one-thread-per-element kernel for shapes and alignments neither takes.
+// Activation, gate and residual can be folded into the epilogue (GLUE instantiations).
 #include "ql_internal.h"
 
 #include <type_traits>
