@@ -159,7 +159,8 @@ def main():
 
     import torch
     import paper_2511_11446_amd as ql
-    ql.lib()   # raises if the HIP library is not built: there is no fallback
+    ql.ensure_built()   # compiles only if no built library is there
+    ql.lib()            # raises if the HIP library is missing: there is no fallback
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)

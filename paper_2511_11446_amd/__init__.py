@@ -47,6 +47,15 @@ _lib = None
 _i64, _vp, _sz, _int = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
 
 
+def ensure_built():
+    """For the entry scripts (tests, smoke check, benchmark): compile the library if no built one is there.
+    The binding itself never builds and never falls back: lib() raises when the library is missing."""
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    return LIB_PATH
+
+
 def lib():
     """Load the HIP library (built in-tree by ``python -m paper_2511_11446_amd.build``)."""
     global _lib

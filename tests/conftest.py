@@ -12,6 +12,12 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def pytest_sessionstart(session):
+    # load what is built; compile only if nothing is
+    import paper_2511_11446_amd as ql
+    ql.ensure_built()
+
+
 def _gpu_present():
     try:
         import torch
