@@ -19,6 +19,20 @@ __device__ __forceinline__ void publish_block_max(unsigned *slot, unsigned bits)
     if (__hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < bits) atomicMax(slot, bits);
 }
 
+// Second pass of the modes with several rows per scale: the maximum of scale block b, either reduced already
+// (blockmax) or, when the block has few parts, taken here from its partial maxima (saves a launch)
+__device__ __forceinline__ unsigned block_max_bits(const DaqArgs &a, int b, int lane)
+{
+    if (a.quant_parts <= 0) return a.blockmax[b];
+    const unsigned *pm = a.partmax + (size_t)b * a.quant_parts;
+    unsigned m = 0;
+    for (int i = lane; i < a.quant_parts; i += 64) {
+        const unsigned o = pm[i];
+        m = m > o ? m : o;
+    }
+    return wave_max_u32(m);
+}
+
 constexpr int ROWS_PER_BLOCK = 4;  // 4 wavefronts, one row each (loop kernels)
 
 // Rows held in registers: CH 16-byte chunks per lane and row (K/8 <= 64*CH), RW rows per wavefront (all loads of the
@@ -65,7 +79,7 @@ __global__ __launch_bounds__(256) void daq_rows_cached(DaqArgs a, int mode)
                 continue;
             }
         } else {
-            bits = a.blockmax[row / a.R];
+            bits = block_max_bits(a, row / a.R, lane);
         }
         const float alpha = alpha_from_bits(bits);
         const float rcp = 1.0f / alpha;
@@ -110,7 +124,7 @@ __global__ __launch_bounds__(256) void daq_rows_loop(DaqArgs a, int mode)
             return;
         }
     } else {
-        bits = a.blockmax[row / a.R];
+        bits = block_max_bits(a, row / a.R, lane);
     }
     const float alpha = alpha_from_bits(bits);
     const float rcp = 1.0f / alpha;
@@ -227,6 +241,13 @@ hipError_t launch_daq(const DaqArgs &a, hipStream_t stream)
         if (parts > 0 && (uintptr_t)a.x % 16 == 0 && parts * nblk < (1ull << 31)) {
             hipLaunchKernelGGL(daq_part_absmax, dim3((unsigned)(parts * nblk)), dim3(256), 0, stream,
                                static_cast<const uint4 *>(a.x), (unsigned)((size_t)a.R * a.K / 8), (unsigned)parts, a.partmax);
+            if (parts <= 256) {
+                // few parts per block: every wavefront of the quantize pass reduces them itself
+                DaqArgs q = a;
+                q.quant_parts = (int)parts;
+                run_rows(q, DAQ_QUANT, stream);
+                return hipGetLastError();
+            }
             hipLaunchKernelGGL(daq_reduce_parts, dim3(nblk), dim3(256), 0, stream, a.partmax, (unsigned)parts, a.blockmax);
         } else {
             hipLaunchKernelGGL(fill_u32, dim3((nblk + 255) / 256), dim3(256), 0, stream, a.blockmax, nblk, 0u);

@@ -21,6 +21,7 @@ struct DaqArgs {
     unsigned *blockmax;  // [M/R] fp16 bit patterns of block maxima (workspace), R > 1 only
     unsigned *partmax;   // [M/R][daq_parts_per_block] partial maxima (workspace), R > 1 only
     int M, K, R;
+    int quant_parts;     // > 0: the quantize pass takes each block's maximum from this many partial maxima itself
     // percentile-clipped variant only (launch_daq_robust)
     int qmax;            // 2^(b-1) - 1 for b-bit activation codes
     unsigned top_rank;   // tau = the top_rank-th largest magnitude of a scale block (1 = the maximum)
