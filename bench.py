@@ -288,6 +288,16 @@ def main():
     ms = e0.elapsed_time(e1)
     ms_per_step = ms / steps
     tops = ops_per_step / (ms_per_step * 1e-3) / 1e12
+    # median over individually timed steps (the paper's protocol quotes averages of synchronized events; the
+    # event pairs add a little per step, so the headline value stays the average over the uninterrupted run)
+    n_med = min(steps, 100)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_med + 1)]
+    evs[0].record(stream)
+    for i in range(n_med):
+        run_step(i)
+        evs[i + 1].record(stream)
+    torch.cuda.synchronize()
+    ms_median = float(np.median([evs[i].elapsed_time(evs[i + 1]) for i in range(n_med)]))
 
     # ---- per-kernel breakdown: for every distinct layer, `reps` launches of the DAQ kernel and `reps` launches of the
     # GEMM kernel, each batch captured into a HIP graph (back-to-back on the stream, no host time between them) and
@@ -417,6 +427,9 @@ def main():
                    "sigmas": sigmas, "gemm_variant": args.variant,
                    "w4_group": args.w4_group,
                    "daq": ("percentile p_ppm=%d a_bits=%d" % (args.daq_p_ppm, args.a_bits)) if robust else "absmax a_bits=8"},
+        "ms_per_step_median": ms_median,
+        "inputs": ("one input set, reused every step (cache-hot)" if len(pool) == 1 else
+                   "%d input sets rotated over the steps" % len(pool)),
         "host_wall_ms_per_step": t_wall / steps * 1e3,
         "roofline": roofline,
         "cpu_baseline": cpu,
