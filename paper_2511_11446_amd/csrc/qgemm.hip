@@ -1071,6 +1071,8 @@ using W4_256x128_8w = Tile<2, 2, 4, 2, 128, true, 2>;
 using W4_128x64_k128 = Tile<2, 1, 2, 2, 128, true, 3>;
 using W4G_128x64_k128 = Tile<2, 1, 2, 2, 128, true, 3, true>;   // any group size that is a multiple of 32
 using W4G_128x128_k128 = Tile<2, 2, 2, 2, 128, true, 2, true>;
+using W4G_64x128_k128 = Tile<1, 2, 2, 2, 128, true, 3, true>;
+using W4G_64x64_k128 = Tile<1, 1, 2, 2, 128, true, 4, true>;
 
 //                          TM TN WGM WGN S WPS
 using D8_128x128_s3 = TileD<2, 2, 2, 2, 3, 2>;
@@ -1147,6 +1149,8 @@ static const Variant VARIANTS[] = {
     {"w4 128x64 bk128 4w occ3", 4, 128, 64, 128, run_variant<W4_128x64_k128>},
     {"w4 any-group 128x64 bk128 4w occ3", 4, 128, 64, 128, run_variant<W4G_128x64_k128>, run_variant<W4G_128x64_k128, true>},
     {"w4 any-group 128x128 bk128 4w occ2", 4, 128, 128, 128, run_variant<W4G_128x128_k128>},
+    {"w4 any-group 64x128 bk128 4w occ3", 4, 64, 128, 128, run_variant<W4G_64x128_k128>},
+    {"w4 any-group 64x64 bk128 4w occ4", 4, 64, 64, 128, run_variant<W4G_64x64_k128>, run_variant<W4G_64x64_k128, true>},
 };
 constexpr int NUM_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);
 
@@ -1169,9 +1173,9 @@ static int choose_variant(const GemmArgs &a)
                      w8_p128 = find_variant("w8 dma 128x128 a3b2 4w spread1 persistent"),
                      w8_p192 = find_variant("w8 dma 128x192 s2 4w spread1 persistent"),
                      w8_big = find_variant("w8 dma 256x192 a3b2 8w spread1"),
-                     w8_k64 = find_variant("w8 128x128 bk64 4w occ3"), w4_any = find_variant("w4 any-group 128x64 bk128 4w occ3");
-    // the register-staged kernel at 3 wavefronts per SIMD hides the per-group VALU work best; its any-group form, whose
-    // four K slices share one copy of the loop body, is also the fastest at group 128 (108 against 127 us, fc1 at M = 8192)
+                     w8_k64 = find_variant("w8 128x128 bk64 4w occ3"), w4_any = find_variant("w4 any-group 64x64 bk128 4w occ4");
+    // the register-staged kernel hides the per-group VALU work best at high occupancy (64x64 tiles, 5 workgroups per CU);
+    // its any-group form, whose four K slices share one copy of the loop body, is also the fastest at group 128
     if (a.w_bits == 16) {
         static const int h_small = find_variant("f16 dma 64x64 s4 4w"), h_mid = find_variant("f16 dma 128x128 a3b2 4w spread1"),
                          h_big = find_variant("f16 dma 256x192 a3b2 8w spread1"),
@@ -1209,7 +1213,7 @@ hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream)
     if (v < 0 || VARIANTS[v].w_bits != a.w_bits || a.K % VARIANTS[v].BK != 0) v = choose_variant(a);
     if (a.w_bits == 4) {
         // group sizes other than 128 run on the variants that end a group at any 32-wide K slice
-        static const int any_group = find_variant("w4 any-group 128x64 bk128 4w occ3");
+        static const int any_group = find_variant("w4 any-group 64x64 bk128 4w occ4");
         if (a.group != 128 && !is_any_group(v)) v = any_group;
         // the pipelined 4-bit kernel keeps the group scales of a tile in LDS: at most 40 groups (K <= 5120)
         if (a.K > 128 * 40 && __builtin_strncmp(VARIANTS[v].name, "w4 dma", 6) == 0)
