@@ -946,31 +946,27 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
 template <class T, bool GLUE = false>
 static hipError_t run_dma(const GemmArgs &a, hipStream_t s)
 {
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (T::LDS_BYTES > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&qgemm_dma<T, GLUE>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
-            if (e != hipSuccess) return e;
-        }
-        attr_set = true;
-    }
+    // LDS above 64 KB needs an opt-in, once per kernel (initialised thread-safely on first use)
+    static const hipError_t lds_opt_in = [] {
+        if (T::LDS_BYTES <= 64 * 1024) return hipSuccess;
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(&qgemm_dma<T, GLUE>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+    }();
+    if (lds_opt_in != hipSuccess) return lds_opt_in;
     const int tiles_m = (a.M + T::BM - 1) / T::BM, tiles_n = (a.N + T::BN - 1) / T::BN;
     const int nblk = tiles_m * tiles_n;
     const int padded = (nblk + XCDS - 1) / XCDS * XCDS;
     int grid = padded;
     if (T::PERSIST) {
         // as many workgroups as the chip holds at once (LDS decides), a multiple of the XCD count
-        static int resident = 0;
-        if (!resident) {
+        static const int resident = [] {
             int dev = 0, cus = 0;
-            hipError_t e = hipGetDevice(&dev);
-            if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-            if (e != hipSuccess) return e;
+            if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+                cus = 256;   // MI355X
             const int per_cu = 160 * 1024 / T::LDS_BYTES > 0 ? 160 * 1024 / T::LDS_BYTES : 1;
-            resident = cus / XCDS * XCDS * per_cu;
-            if (resident < XCDS) resident = XCDS;
-        }
+            const int r = cus / XCDS * XCDS * per_cu;
+            return r < XCDS ? XCDS : r;
+        }();
         if (grid > resident) grid = resident;
     }
     hipLaunchKernelGGL((qgemm_dma<T, GLUE>), dim3(grid), dim3(T::NT), T::LDS_BYTES, s, a, tiles_m, tiles_n, padded, pick_group_m(T::BM));
@@ -1032,15 +1028,12 @@ __global__ __launch_bounds__(256) void qgemm_naive(GemmArgs a)
 template <class T, bool GLUE = false>
 static hipError_t run_variant(const GemmArgs &a, hipStream_t s)
 {
-    static bool attr_set = false;  // per variant; LDS above 64 KB needs the opt-in once
-    if (!attr_set) {
-        if (T::LDS_BYTES > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&qgemm_mfma<T, GLUE>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
-            if (e != hipSuccess) return e;
-        }
-        attr_set = true;
-    }
+    static const hipError_t lds_opt_in = [] {
+        if (T::LDS_BYTES <= 64 * 1024) return hipSuccess;
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(&qgemm_mfma<T, GLUE>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+    }();
+    if (lds_opt_in != hipSuccess) return lds_opt_in;
     const int tiles_m = (a.M + T::BM - 1) / T::BM, tiles_n = (a.N + T::BN - 1) / T::BN;
     const int nblk = tiles_m * tiles_n;
     const int padded = (nblk + XCDS - 1) / XCDS * XCDS;
