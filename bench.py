@@ -171,7 +171,7 @@ def main():
     M, R = wl["M"], wl["R"]
     big = M >= 8192
     steps = args.steps if args.steps is not None else (wl["steps"] if wl["steps"] > 1 else (100 if not big else 20))
-    warmup = args.warmup   # None: warm up until the GPU clocks have settled (see below)
+    warmup = args.warmup
     pool, sigmas = build_inputs(ql, torch, args.workload, wl, layers)
     plan = ql.Plan([dict(K=l["K"], N=l["N"], bits=l["bits"], group=l["group"], w=l["w"], w_scale=l["w_scale"], bias=l["bias"])
                     for l in layers], M_max=M)
@@ -274,18 +274,18 @@ def main():
         else:
             ql.daq_quantize(x, R, q, sa, dws)
 
+    # The clocks take tens of milliseconds of load to settle (the first 50 steps of the M = 16384 block run 8 % slower
+    # than the rest): before the W warm-up steps, run the step for at least 0.15 s of wall time (untimed preparation).
+    settle, t_w0 = 0, time.perf_counter()
+    while time.perf_counter() - t_w0 < 0.15:
+        for _ in range(5):
+            run_step(settle)
+            settle += 1
+        torch.cuda.synchronize()
     if warmup is None:
-        # The clocks take tens of milliseconds of load to settle (the first 50 steps of the M = 16384 block run 8 % slower
-        # than the rest): without --warmup, warm up for at least 0.15 s of wall time and at least 10 steps.
-        warmup, t_w0 = 0, time.perf_counter()
-        while warmup < 10 or time.perf_counter() - t_w0 < 0.15:
-            for _ in range(5):
-                run_step(warmup)
-                warmup += 1
-            torch.cuda.synchronize()
-    else:
-        for i in range(warmup):
-            run_step(i)
+        warmup = 10 if not big else 3
+    for i in range(warmup):
+        run_step(i)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t_wall0 = time.perf_counter()
@@ -438,6 +438,7 @@ def main():
                    "w4_group": args.w4_group,
                    "daq": ("percentile p_ppm=%d a_bits=%d" % (args.daq_p_ppm, args.a_bits)) if robust else "absmax a_bits=8"},
         "ms_per_step_median": ms_median,
+        "clock_settle_steps": settle,
         "inputs": ("one input set, reused every step (cache-hot)" if len(pool) == 1 else
                    "%d input sets rotated over the steps" % len(pool)),
         "host_wall_ms_per_step": t_wall / steps * 1e3,
