@@ -11,6 +11,10 @@ Operations and the passages they follow:
   gemm_i8           INT8 x INT8 -> INT32 GEMM (Step 3, Step 5, Section 6)
   gemm_w4g128       the same GEMM on 4-bit group-128 weights (Step 2)
   epilogue_w8/_w4   dequantization with per-channel / per-group weight scales
+  daq_robust        eq. (4) as printed: nearest-rank percentile clipping, activation width from Step 6
+  gemm_w4g          4-bit GEMM with weight groups of any size dividing K (Step 2, Algorithm 1)
+  dequant_w8/_w4    the fp32 values before the fp16 rounding;  block_glue: activation, gate, residual on top of them
+  linear_f16        a layer the plan leaves in FP16 (fp64 sum)
 """
 import ctypes
 import os

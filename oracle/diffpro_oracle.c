@@ -16,7 +16,15 @@
  *     GEMM with per-output-channel (or per-group) weight scales, followed by
  *     dequantization.
  *   - Step 2: weights are integer codes with per-group scales; the symmetric
- *     form (zero-point 0) of the ablation section is used.
+ *     form (zero-point 0) of the ablation section is used.  Group sizes other
+ *     than 128 (Algorithm 1) and layers left in FP16: orc_gemm_w4g, orc_linear_f16.
+ *   - eq. (4) as printed (percentile clipping) with the activation width of
+ *     Step 6: orc_daq_robust.  Residual additions and the MLP activation folded
+ *     into the epilogue (Section 6 counts them in the latency): orc_block_glue.
+ *
+ * Every function is pinned by the CPU tests against something other than itself
+ * (hand-worked cases, invariants, brute force, numpy routines): none is
+ * "parity unpinned".
  *
  * Conventions the paper leaves open (every one is listed in the design notes):
  *   round = round-half-to-even; an all-zero block gets scale 1; the quotient
