@@ -378,6 +378,32 @@ def test_c4_per_sample_scales_m16384(gpu, orc):
     _sampled_layer_check(gpu, orc, "proj", 1152, 1152, 8, M, R, rows, "c4ps", 2.0)
 
 
+def test_daq_seeded_random_shapes(gpu, orc):
+    """Forty seeded shapes, scale granularities and quantizer settings drawn at random: the absmax and the percentile
+    entry points against the oracle, bit for bit."""
+    g = workload.rng("daq-random-shapes")
+    for case in range(40):
+        K = int(g.choice([8, 24, 64, 100, 136, 520, 1152, 1160, 2048, 4608, 9000]))
+        R = int(g.choice([1, 1, 1, 2, 5, 16, 64]))
+        M = R * int(g.integers(1, 12 if K > 2000 else 40))
+        robust = bool(g.integers(0, 2))
+        p_ppm = int(g.choice([1000000, 999000, 990000, 900000, 500000]))
+        a_bits = int(g.integers(2, 9))
+        sigma = float(g.uniform(1e-4, 50.0))
+        say("daq random", case, M, K, R, robust, p_ppm, a_bits)
+        x = workload.activations(M, K, "daq-rand", case, sigma=sigma)
+        if case % 7 == 0:
+            x[:: max(1, M // 3)] = 0          # some all-zero rows
+        if robust:
+            q_ref, s_ref = orc.daq_robust(x, R, p_ppm=p_ppm, a_bits=a_bits, nthreads=8)
+            q, s = gpu.daq_quantize_robust(dev(x), R, p_ppm=p_ppm, a_bits=a_bits)
+        else:
+            q_ref, s_ref = orc.daq(x, R, nthreads=8)
+            q, s = gpu.daq_quantize(dev(x), R)
+        assert np.array_equal(host(s).view(np.uint32), s_ref.view(np.uint32)), case
+        assert np.array_equal(host(q), q_ref), case
+
+
 # ------------------------------------------------------------------ percentile-clipped DAQ (eq. (4) as printed)
 
 ROBUST_CASES = [
@@ -770,6 +796,62 @@ def test_full_size_group288_fp16_and_fused_layers_sampled(gpu, orc):
     assert assert_y_close(host(y[idx]), ref) == 0
     del y
     torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------ seeded random layer shapes
+
+def test_layers_seeded_random_shapes(gpu, orc):
+    """Thirty seeded layers of random shape, weight width, group size, scale granularity and glue, against the oracle."""
+    g = workload.rng("layer-random-shapes")
+    for case in range(30):
+        bits = int(g.choice([8, 8, 4, 4, 16]))
+        K = int(g.choice([64, 128, 192, 576, 1152, 2304]) if bits != 8 else g.choice([24, 64, 200, 576, 1152, 2304]))
+        if bits == 4:
+            group = int(g.choice([gs for gs in (32, 64, 96, 128, 192, 288, 576) if K % gs == 0]))
+        else:
+            group = 128
+        R = int(g.choice([1, 1, 4]))
+        M = R * int(g.integers(1, 100))
+        N = int(g.integers(1, 400))
+        act = int(g.integers(0, 2))
+        use_res, use_gate = bool(g.integers(0, 2)), bool(g.integers(0, 2))
+        gate_rows = int(g.choice([d for d in (1, 2, 4, M) if M % d == 0]))
+        say("layer random", case, bits, M, K, N, R, group, act, use_res, use_gate, gate_rows)
+        x = workload.activations(M, K, "layer-rand", case)
+        res = g.standard_normal((M, N), dtype=np.float32).astype(np.float16) if use_res else None
+        gate = g.standard_normal((M // gate_rows, N), dtype=np.float32).astype(np.float16) if use_gate else None
+        kw = dict(act=act, residual=None if res is None else dev(res), gate=None if gate is None else dev(gate), gate_rows=gate_rows)
+        if bits == 16:
+            w = (g.standard_normal((N, K), dtype=np.float32) * 0.05).astype(np.float16)
+            b = workload.bias(N, "layer-rand", case)
+            h = orc.linear_f16(x, w, b, nthreads=8)
+            y = host(gpu.qlinear_f16(dev(x), dev(w), dev(b), **kw)).astype(np.float64)
+            lo = orc.block_glue(h.astype(np.float32), act=act, residual=res, gate=gate, gate_rows=gate_rows).astype(np.float64)
+            gabs = np.abs(np.repeat(gate.astype(np.float64), gate_rows, 0)) if gate is not None else 1.0
+            # fp32 against fp64 sums (and fp32 GELU): the value before the glue may move by the accumulation bound plus an ulp
+            tol = (_f16_tolerance(x, w, h) + 2.0 ** -9 * np.abs(h.astype(np.float64))) * gabs * (1.2 if act else 1.0) \
+                + 2.0 ** -10 * np.abs(lo) + 2.0 ** -24
+            assert (np.abs(y - lo) <= tol).all(), case
+            continue
+        lw = workload.layer_weights("layer-rand", K, N, bits, case)
+        if bits == 4:
+            lw = dict(lw, s_w=workload.w4_scales_group(N, K, group, "layer-rand", case))
+        q, sc = orc.daq(x, R, nthreads=8)
+        if bits == 8:
+            u = orc.dequant_w8(orc.gemm_i8(q, lw["w"], nthreads=8), sc, R, lw["s_w"], lw["bias"])
+            w = dev(lw["w"])
+        else:
+            u = orc.dequant_w4(orc.gemm_w4g(q, orc.pack_w4(lw["w"]), group, nthreads=8), sc, R, lw["s_w"], lw["bias"])
+            w = dev(gpu.ql_pack_w4_host(lw["w"]))
+        ref = orc.block_glue(u, act=act, residual=res, gate=gate, gate_rows=gate_rows)
+        y = host(gpu.qlinear_fused(dev(x), R, w, dev(lw["s_w"]), dev(lw["bias"]), bits=bits, group=group, **kw))
+        if act == 0:
+            assert assert_y_close(y, ref) == 0, case
+        else:
+            h_ref = orc.block_glue(u, act=1).astype(np.float64)
+            gabs = np.abs(np.repeat(gate.astype(np.float64), gate_rows, 0)) if gate is not None else 1.0
+            tol = 1e-3 * np.abs(ref.astype(np.float64)) + gabs * np.abs(h_ref) * 2.0 ** -10 + 2.0 ** -24
+            assert (np.abs(y.astype(np.float64) - ref.astype(np.float64)) <= tol).all(), case
 
 
 # ------------------------------------------------------------------ plan runner
