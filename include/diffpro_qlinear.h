@@ -145,7 +145,7 @@ int qgemm_w4a8(const void *q, const void *a_scales, int64_t M, int64_t K, int64_
 
 /* The 4-bit layer with weight groups of `group` consecutive k per scale instead
  * of 128 (Step 2 and Algorithm 1 choose the group size per layer; the final plan
- * of Section 6 uses 64, 128, 192 and 288).  group: a multiple of 32
+ * of Step 2 uses 32, 64, 128, 192 and 288).  group: a multiple of 32
  * (else QL_ERR_UNSUPPORTED) that divides K (else QL_ERR_SHAPE).
  *   w_scale (device) fp16 [N, K/group];  dbg->acc, acc: int32 [M, K/group, N]
  *   f = sum over groups g ascending of fma(float(P[m,g,n]), w_scale[n,g], f)
@@ -197,7 +197,7 @@ int qlinear_w4a8_fused(const void *x, int64_t M, int64_t K, int64_t R,
 
 /* ------------------------------------------------------------------------
  * A layer the plan leaves in FP16 (Step 2 freezes the most sensitive layers;
- * the final plan of Section 6 keeps 22 layers in FP16): no quantization,
+ * its final plan keeps 22 of 113 layers in FP16): no quantization,
  *   y[m,n] = fp16( sum_k x[m,k] * w[n,k] + bias[n] )
  * with fp32 accumulation on the matrix cores (the sum's rounding error is
  * bounded by K * 2^-24 * sum_k |x w|; the oracle sums in fp64).

@@ -290,8 +290,8 @@ int orc_gemm_w4g128(const int8_t *q, const uint8_t *w4, int64_t M, int64_t N, in
 
 /* ------------------------------------------------------------------ */
 /* The same with weight groups of `group` consecutive k (Step 2 and    */
-/* Algorithm 1 choose the group size per layer; the final plan of      */
-/* Section 6 uses 64, 128, 192 and 288):                               */
+/* Algorithm 1 choose the group size per layer; Step 2's final plan    */
+/* uses 32, 64, 128, 192 and 288):                               */
 /*   P[m,g,n] = sum_{k in [group*g, group*g+group)} q[m,k] * w4[n,k]   */
 /*   P is [M, K/group, N];  K % group == 0                             */
 /* ------------------------------------------------------------------ */
@@ -423,7 +423,7 @@ int orc_block_glue(const float *u, int64_t M, int64_t N, int act, const uint16_t
 
 /* ------------------------------------------------------------------ */
 /* A layer the plan leaves in FP16 (Step 2 freezes the most sensitive   */
-/* layers; the final plan of Section 6 keeps 22 of 113 in FP16):        */
+/* layers; its final plan keeps 22 of 113 layers in FP16):              */
 /*   y[m,n] = f16( sum_k x[m,k] * w[n,k] + bias[n] )                    */
 /* x [M,K], w [N,K], bias [N] binary16.  The sum is taken in binary64   */
 /* (every product of two binary16 values is exact there), the bias is   */

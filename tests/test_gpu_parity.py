@@ -717,7 +717,7 @@ def test_fp16_layer_with_glue_on_a_shape_that_picks_a_persistent_tile(gpu, orc):
 
 
 def test_plan_with_fp16_int8_and_int4_layers(gpu, orc):
-    """A plan of the kind Section 6 ends with: FP16, W8 and W4 (two group sizes) layers side by side."""
+    """A plan of the kind Step 2 ends with: FP16, W8 and W4 (two group sizes) layers side by side."""
     import torch
     M, R = 512, 1
     g = workload.rng("plan-f16")
