@@ -150,10 +150,20 @@ __global__ __launch_bounds__(256) void daq_rows_robust(DaqArgs a, int mode)
                 prev = m;
             }
         } else {
-            // largest T with count(magnitude >= T) >= top_rank, built bit by bit from the top
+            // largest T with count(magnitude >= T) >= top_rank, built bit by bit from the top; a candidate above the
+            // row maximum cannot succeed and costs no counting round
+            unsigned mx = 0;
+#pragma unroll
+            for (int i = 0; i < CH; ++i) {
+                mx = absmax_word(mx, v[i].x);
+                mx = absmax_word(mx, v[i].y);
+                mx = absmax_word(mx, v[i].z);
+                mx = absmax_word(mx, v[i].w);
+            }
+            mx = wave_max_u32((mx & 0xffffu) > (mx >> 16) ? (mx & 0xffffu) : (mx >> 16));
             for (int bit = 14; bit >= 0; --bit) {
                 const unsigned cand = T | (1u << bit);
-                if (count_ge(cand) >= a.top_rank) T = cand;
+                if (cand <= mx && count_ge(cand) >= a.top_rank) T = cand;
             }
         }
         tau_bits = T;
