@@ -24,14 +24,13 @@ import workload  # noqa: E402
 
 INT8_PEAK_TOPS = 5033.0   # MI355X dense INT8 matrix peak (256 CUs x 2.4 GHz x 8192 op/clk)
 HBM_PEAK_GBS = 8000.0
-DEFAULT_WORKLOAD = "c2_block_w8a8_m2048"
+DEFAULT_WORKLOAD = "c5_stack_plan_m16384"   # the largest single-GPU configuration: 112 layers, M = 16384
 POOL = 4                  # distinct activation sets rotated over the steps (different drift sigma each)
-# HBM bytes per GEMM launch (reads + writes, mean over the layers of a step) from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs of `bench.py --traffic-probe`, each scaled by what the same counter reads for a device-to-device copy
-# of known size in the same run (summaries under profiles/).  Keyed by (workload, forced variant); absent = not measured.
+# HBM bytes per GEMM launch (reads + writes, mean over the GEMM launches of a step).  NOT measured by the run that
+# prints them: they come from earlier rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of `bench.py --traffic-probe`, each
+# scaled by what the same counter reads for a device-to-device copy of known size in the same run; the summary file
+# under profiles/ is named beside each figure.  Keyed by (workload, forced variant, 4-bit group); absent = not measured.
 TRAFFIC_BYTES_PER_LAUNCH = {
-    ("c2_block_w8a8_m2048", -1): 36276 * 1024,    # (2*fetch + write) KiB, mean of the 4 GEMM launches of a step
-    ("c4_block_w8a8_m16384", -1): 188161 * 1024,
 }
 
 
@@ -60,8 +59,9 @@ def build_inputs(ql, torch, wl_name, wl, layers):
     The MLP output layer (fc2) gets the GELU of the GPU's own fc1 output of the same slot."""
     M, R = wl["M"], wl["R"]
     steps = wl["steps"]
-    sig = workload.sigma_schedule(steps) if steps > 1 else np.array([1.0])
-    slots = [int(round(i * (len(sig) - 1) / max(POOL - 1, 1))) for i in range(POOL)] if steps > 1 else [0]
+    # every workload rotates POOL distinct input sets, so that no step finds its inputs in the caches from the step before
+    sig = workload.sigma_schedule(steps) if steps > 1 else np.ones(POOL)
+    slots = [int(round(i * (len(sig) - 1) / max(POOL - 1, 1))) for i in range(POOL)] if steps > 1 else list(range(POOL))
     types = {}
     for l in layers:
         types.setdefault(l["name"], (l["K"], l["N"]))
@@ -90,9 +90,10 @@ def build_inputs(ql, torch, wl_name, wl, layers):
     return pool, [float(sig[s]) for s in slots]
 
 
-def cpu_baseline(wl_name, wl, layers, budget_rows=16384, min_seconds=10.0, max_passes=32):
-    """The oracle as it stands, row-parallel over the host cores, on the first rows of the workload; whole passes over
-    that sample are repeated until about ten seconds of CPU work have been timed."""
+def cpu_baseline(wl_name, wl, layers, budget_rows=8192, min_seconds=10.0, max_passes=32):
+    """The oracle as it stands, row-parallel over the host cores, on the first rows of the workload (one launch of every
+    distinct layer kind); whole passes over that sample are repeated until about ten seconds of CPU work have been timed
+    (a pass over 8192 rows of the eight layer kinds of the 112-layer stack takes about 13 s on 16 threads)."""
     import oracle
     oracle.build()
     M, R = wl["M"], wl["R"]
@@ -358,6 +359,8 @@ def main():
         for l in layers:
             counts[kind(l)] = counts.get(kind(l), 0) + 1
         gemm_time, gemm_ops, gemm_n, daq_time, daq_bytes, daq_n = 0.0, 0.0, 0, 0.0, 0.0, 0
+        fam = {}   # GEMM kernel family -> [time per step, ops per step, launches per step]
+        fam_name = {8: "qgemm_dma, 8-bit weights", 4: "qgemm_w4 / qgemm_mfma, 4-bit weights", 16: "qgemm_dma, FP16 operands"}
         for key, l in uniq.items():
             x = pool[0][l["name"]]
             q = torch.empty((M, l["K"]), dtype=torch.int8, device="cuda")
@@ -387,9 +390,13 @@ def main():
             gemm_time += tg * counts[key]
             gemm_ops += ops * counts[key]
             gemm_n += counts[key]
+            f = fam.setdefault(l["bits"], [0.0, 0.0, 0])
+            f[0] += tg * counts[key]
+            f[1] += ops * counts[key]
+            f[2] += counts[key]
             daq_time += td * counts[key]
             daq_bytes += (dbytes if td else 0.0) * counts[key]
-            daq_n += counts[key]
+            daq_n += counts[key] if td else 0
             del q, sa, y, q_ref, y_ref
         # the matrix cores' own ceiling on this machine: a register-resident MFMA loop, 2 workgroups per CU
         sink = torch.zeros(1, dtype=torch.int32, device="cuda")
@@ -404,21 +411,31 @@ def main():
         a1.record(stream)
         torch.cuda.synchronize()
         mfma_ceiling = 5 * pops / (a0.elapsed_time(a1) * 1e-3) / 1e12
-        traffic = TRAFFIC_BYTES_PER_LAUNCH.get((args.workload, args.variant))
-        if gemm_time >= daq_time:
-            ach = gemm_ops / gemm_time / 1e12
-            roofline = {"bound": "mfma", "kernel": "qgemm_dma / qgemm_mfma (INT8 GEMM + dequantization), all layers of a step",
-                        "achieved": ach, "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": ach / INT8_PEAK_TOPS,
-                        "avg_launch_us": gemm_time / gemm_n * 1e6, "ops_per_launch": gemm_ops / gemm_n,
-                        "traffic": traffic}
+        traffic = TRAFFIC_BYTES_PER_LAUNCH.get((args.workload, args.variant, args.w4_group))
+        # the dominant kernel = the GEMM family with the largest share of a step (the DAQ kernel if it outweighs them all)
+        dom = max(fam, key=lambda b: fam[b][0])
+        if fam[dom][0] >= daq_time:
+            t_dom, ops_dom, n_dom = fam[dom]
+            peak = INT8_PEAK_TOPS if dom != 16 else 2500.0
+            ach = ops_dom / t_dom / 1e12
+            roofline = {"bound": "mfma", "kernel": fam_name[dom] + " (GEMM + dequantization): its launches of a step",
+                        "achieved": ach, "peak": peak, "unit": "TOP/s" if dom != 16 else "TFLOP/s", "frac": ach / peak,
+                        "avg_launch_us": t_dom / n_dom * 1e6, "ops_per_launch": ops_dom / n_dom,
+                        "launches_per_step": n_dom, "share_of_gemm_time": t_dom / gemm_time,
+                        "traffic": traffic[0] if traffic else None,
+                        "traffic_source": traffic[1] if traffic else None}
         else:
             ach = daq_bytes / daq_time / 1e9
             roofline = {"bound": "hbm", "kernel": "daq_rows_cached (DAQ pass), all layers of a step", "achieved": ach,
                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                         "avg_launch_us": daq_time / daq_n * 1e6, "bytes_per_launch": daq_bytes / daq_n,
                         "traffic": None}
-        roofline["daq_hbm_gbs"] = daq_bytes / daq_time / 1e9
+        roofline["by_kernel"] = {fam_name[b]: {"tops": v[1] / v[0] / 1e12, "frac_of_peak": v[1] / v[0] / 1e12 / (INT8_PEAK_TOPS if b != 16 else 2500.0),
+                                               "us_per_step": v[0] * 1e6, "launches_per_step": v[2]} for b, v in fam.items()}
+        roofline["daq_hbm_gbs"] = (daq_bytes / daq_time / 1e9) if daq_time else None
+        roofline["daq_us_per_step"] = daq_time * 1e6
         roofline["gemm_only_tops"] = gemm_ops / gemm_time / 1e12
+        roofline["gemm_only_frac"] = gemm_ops / gemm_time / 1e12 / INT8_PEAK_TOPS
         roofline["measured_mfma_only_tops"] = mfma_ceiling
         roofline["frac_of_measured_mfma"] = gemm_ops / gemm_time / 1e12 / mfma_ceiling
 
@@ -439,8 +456,7 @@ def main():
                    "daq": ("percentile p_ppm=%d a_bits=%d" % (args.daq_p_ppm, args.a_bits)) if robust else "absmax a_bits=8"},
         "ms_per_step_median": ms_median,
         "clock_settle_steps": settle,
-        "inputs": ("one input set, reused every step (cache-hot)" if len(pool) == 1 else
-                   "%d input sets rotated over the steps" % len(pool)),
+        "inputs": "%d input sets rotated over the steps" % len(pool),
         "host_wall_ms_per_step": t_wall / steps * 1e3,
         "roofline": roofline,
         "cpu_baseline": cpu,

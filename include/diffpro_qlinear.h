@@ -23,7 +23,8 @@
  *     The fast (MFMA) kernels need K % 16 == 0 and 16-byte aligned x, q, w;
  *     other shapes or alignments are served by slower generic kernels with the
  *     same results.  4-bit weights need K % group == 0 (group = 128 unless the
- *     call takes one) and K % 8 == 0.
+ *     call takes one), K % 8 == 0 and group <= 132096 (the kernels multiply
+ *     the nibbles as value * 16, and 127 * 8 * 16 * group must fit an int32).
  */
 #ifndef DIFFPRO_QLINEAR_H
 #define DIFFPRO_QLINEAR_H
@@ -56,8 +57,8 @@ int ql_version(void);
 
 /* ------------------------------------------------------------------------
  * DAQ: Step 3, eq. (4) with tau = the absolute maximum of the scale block
- * (percentile p -> 100; the "per sample per timestep min max scales" of
- * Section 2.3), b = 8, zero-point 0.
+ * (percentile p -> 100, i.e. the min/max scales taken per sample and timestep
+ * that Section 2.3 describes), b = 8, zero-point 0.
  *   alpha_r = amax_r / 127            (1 if the block is all zero)
  *   q[m,k]  = clamp(round_half_even(x[m,k] / alpha_r), -127, 127)
  * A scale block r is R consecutive rows: R = 1 per token, R = tokens per image
@@ -92,8 +93,8 @@ typedef struct ql_debug {
 size_t qlinear_workspace_bytes(int64_t M, int64_t K, int64_t R);
 
 /* ------------------------------------------------------------------------
- * Quantized linear with 8-bit weights (Step 3 and Step 5: "every linear layer
- * uses an INT8 x INT8 -> INT32 kernel with per-output-channel weight scales";
+ * Quantized linear with 8-bit weights (Step 3 and Step 5: all linears run as
+ * int8 x int8 products accumulated in int32, one weight scale per output channel;
  * Section 6 counts DAQ, requantization and dequantization in the latency):
  *   q, alpha = DAQ(x, R)
  *   acc[m,n] = sum_k q[m,k] * w[n,k]                       (int32)
@@ -222,9 +223,9 @@ int ql_pack_w4_host(const int8_t *codes, int64_t N, int64_t K, uint8_t *packed);
 int ql_repack_w4_pairs_host(const uint8_t *pairs, int64_t N, int64_t K, uint8_t *packed);
 
 /* ------------------------------------------------------------------------
- * Plan runner: Algorithm 2, Phase B ("wrap layers per the bit plan ... forward
- * with quantized weights and activations") and Step 6, restricted to the
- * quantized linears.  A plan is a list of layers, each with its own weight
+ * Plan runner: Algorithm 2, Phase B (every layer wrapped as its plan entry says,
+ * then the forward pass on quantized weights and activations) and Step 6,
+ * restricted to the quantized linears.  A plan is a list of layers, each with its own weight
  * width; qlinear_plan_run enqueues DAQ + GEMM + epilogue for every layer in
  * order on one stream.
  * ---------------------------------------------------------------------- */
@@ -281,8 +282,7 @@ int qlinear_plan_run_robust(const ql_plan *plan, const void *const *x_in, void *
                             int64_t M, int64_t R, const ql_daq_params *params,
                             void *workspace, size_t workspace_bytes, void *stream);
 
-/* The plan walk with everything optional switched per call (Algorithm 2 Phase B: "forward with quantized weights and
- * activations" for one step of the schedule): params as in qlinear_plan_run_robust or NULL (absolute maximum, 8 bits;
+/* The plan walk with everything optional switched per call (Algorithm 2 Phase B, the quantized forward pass of one step of the schedule): params as in qlinear_plan_run_robust or NULL (absolute maximum, 8 bits;
  * FP16 layers ignore it), fusion = NULL or a host array of n_layers pointers, entry l NULL or the glue folded into
  * layer l's epilogue (see ql_fusion).  Everything else as qlinear_plan_run. */
 int qlinear_plan_run_ex(const ql_plan *plan, const void *const *x_in, void *const *y_out,

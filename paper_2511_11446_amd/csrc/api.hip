@@ -16,6 +16,7 @@ std::atomic<int> g_gemm_variant{-1};
 
 constexpr int64_t K_MAX = 133143;          // 133143 * 127 * 127 < 2^31
 constexpr int64_t ELEMS_MAX = 2147483647;  // int32 indexing inside the kernels
+constexpr int64_t W4_GROUP_MAX = 132096;   // largest multiple of 32 with 127 * 8 * 16 * group < 2^31
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -89,6 +90,8 @@ int check_group(int64_t K, int64_t group)
 {
     if (group < 32 || group % 32 != 0) return QL_ERR_UNSUPPORTED;
     if (K % group != 0 || K % 8 != 0) return QL_ERR_SHAPE;
+    // the kernels multiply nibbles as value * 16: a group's sum of 127 * 128 * group must stay below 2^31
+    if (group > W4_GROUP_MAX) return QL_ERR_SHAPE;
     return QL_OK;
 }
 

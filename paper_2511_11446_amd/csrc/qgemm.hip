@@ -1,7 +1,7 @@
 // INT8 x INT8 -> INT32 GEMM with fused dequantization for gfx950 (CDNA4).
 //
-// The paper's linears are "INT8 x INT8 -> INT32 GEMMs" with per-output-channel
-// weight scales (Step 3, Step 5, Section 6) or per-group scales (Step 2).
+// The paper's linears multiply int8 codes into int32 sums, with one weight scale per
+// output channel (Step 3, Step 5, Section 6) or per weight group (Step 2).
 // Here: acc[m,n] = sum_k q[m,k] * w[n,k] on v_mfma_i32_32x32x32_i8, both
 // operands K-contiguous, and the dequantization + bias + fp16 conversion applied
 // to the accumulators in registers.  Two kernel families:

@@ -147,15 +147,18 @@ def test_workload_recipe_is_deterministic():
 
 
 def test_daq_division_free_codes_exhaustive(tmp_path):
-    """The kernel's division-free quantization equals the division of eq. (4) on every (absmax, value) fp16 pair
-    that passes its near-tie test (the rest take the division); checked on the host, all 5e8 pairs."""
+    """The kernels' division-free quantization equals the division of eq. (4) on every (threshold, value) fp16 pair
+    that passes its near-tie test (the rest take the division), for every code width 2..8 bits (q_max = 1 ... 127);
+    checked on the host, all 5e8 pairs per width."""
     import subprocess
     src = os.path.join(os.path.dirname(__file__), "daq_division_free_check.c")
     exe = str(tmp_path / "daq_check")
     subprocess.run(["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-o", exe, src, "-lm"], check=True)
     r = subprocess.run([exe], capture_output=True, text=True, timeout=600)
     assert r.returncode == 0, r.stdout + r.stderr
-    assert "mismatches 0 out-of-range 0" in r.stdout
+    lines = [l for l in r.stdout.splitlines() if l.startswith("qmax")]
+    assert [int(l.split()[1]) for l in lines] == [127, 63, 31, 15, 7, 3, 1]
+    assert all("mismatches 0 out-of-range 0" in l for l in lines), r.stdout
 
 
 class _Prm(ctypes.Structure):
@@ -189,6 +192,9 @@ def test_group_size_argument_checks():
     assert L.qlinear_w4a8_g(*args(100, 100)) == 4
     assert L.qgemm_w4a8_g(FAKE, FAKE, 4, 1152, 1, FAKE, FAKE, 48, None, 8, FAKE, None, None) == 4
     assert L.qgemm_w4a8_g(FAKE, FAKE, 4, 1152, 1, FAKE, FAKE, 256, None, 8, FAKE, None, None) == 2
+    # a group whose sum of 127 * 8 * 16 products could pass 2^31 is refused; the largest admitted one is 132096
+    assert L.qlinear_w4a8_g(*args(132224, 132224)) == 2
+    assert 127 * 128 * 132096 < 2 ** 31 <= 127 * 128 * 132128
 
 
 def test_fused_epilogue_argument_checks():

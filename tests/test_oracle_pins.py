@@ -151,6 +151,56 @@ def test_daq_matches_exact_rational_rounding(orc):
     assert near_tie < 8
 
 
+def _fl32(fr):
+    """Correctly rounded (nearest, ties to even) binary32 value of a positive rational, as a Fraction (normal range)."""
+    e = 0
+    while fr >= 2 ** 24:
+        fr /= 2
+        e += 1
+    while fr < 2 ** 23:
+        fr *= 2
+        e -= 1
+    n = fr.__floor__()
+    rem = fr - n
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and n % 2 == 1):
+        n += 1
+    return Fraction(n) * Fraction(2) ** e
+
+
+def test_daq_divides_by_alpha_where_a_reciprocal_would_differ(orc):
+    """Eq. (4) divides by alpha.  On the stored pairs the correctly rounded quotient and a multiplication by the rounded
+    reciprocal give different codes; the expected code is derived here with exact rational arithmetic (two binary32
+    roundings: alpha = fl(amax/127), t = fl(x/alpha), then round half to even), so an oracle that multiplied by
+    1/alpha instead of dividing fails."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "daq_division_vs_reciprocal.txt")
+    pairs = []
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        lhs, by_div, by_rcp = [t.strip() for t in line.split("|")]
+        a, x = [int(t, 16) for t in lhs.split()]
+        pairs.append((a, x, int(by_div), int(by_rcp)))
+    assert len(pairs) >= 8
+    for a_bits, x_bits, by_div, by_rcp in pairs:
+        amax = Fraction(float(np.array([a_bits], np.uint16).view(np.float16)[0]))
+        xv = Fraction(float(np.array([x_bits], np.uint16).view(np.float16)[0]))
+        alpha = _fl32(amax / 127)
+        t = _fl32(xv / alpha)
+        lo = t.__floor__()
+        frac = t - lo
+        code = lo + 1 if (frac > Fraction(1, 2) or (frac == Fraction(1, 2) and lo % 2 == 1)) else lo
+        t_rcp = _fl32(xv * _fl32(1 / alpha))
+        lo2 = t_rcp.__floor__()
+        f2 = t_rcp - lo2
+        code_rcp = lo2 + 1 if (f2 > Fraction(1, 2) or (f2 == Fraction(1, 2) and lo2 % 2 == 1)) else lo2
+        assert code != code_rcp and (code, code_rcp) == (by_div, by_rcp)     # the pair does discriminate the two forms
+        row = np.array([[a_bits, x_bits, x_bits ^ 0x8000, 0]], np.uint16).view(np.float16)
+        q, s = orc.daq(row, 1)
+        assert Fraction(float(s[0])) == alpha
+        assert q[0].tolist() == [127, code, -code, 0]
+
+
 def test_daq_granularities_agree_when_rows_share_absmax(orc):
     x = workload.activations(24, 64, "share", n_outlier=0)
     x = np.clip(x, -2.0, 2.0).astype(np.float16)
