@@ -13,98 +13,9 @@
 //               an fp32 sum with its scale) and 8-bit weights with K % 128 != 0
 // plus a one-thread-per-element kernel for shapes and alignments neither takes.
 // Activation, gate and residual can be folded into the epilogue (GLUE instantiations).
-#include "ql_internal.h"
-
-#include <type_traits>
+#include "qgemm_common.h"
 
 namespace ql {
-
-typedef int v2i __attribute__((ext_vector_type(2)));
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-// LDS staging is written as fp16 scalars and read back as 16-byte vectors: tell the compiler these may alias
-typedef _Float16 half_alias __attribute__((may_alias));
-typedef int v4i_alias __attribute__((ext_vector_type(4), may_alias));
-typedef float v4f __attribute__((ext_vector_type(4)));
-
-// Timing hook for kernel phase studies; expands to nothing in the library build.
-#ifndef QL_PHASE
-#define QL_PHASE(id)
-#endif
-
-constexpr int XCDS = 8;    // L2 domains of the chip; consecutive workgroup ids go round-robin over them
-constexpr int GROUP_ROWS = 1024; // rows of A walked together so that one L2 sees few distinct A and W panels (512..2048 measure alike)
-
-static int pick_group_m(int bm) { return GROUP_ROWS / bm > 0 ? GROUP_ROWS / bm : 1; }
-
-__device__ __forceinline__ float half_to_float_dev(unsigned short h)
-{
-    return (float)__builtin_bit_cast(_Float16, h);
-}
-
-// ---- block glue folded into the epilogue: h = f16(act(u)); y = f16(fma(g, h, r)) -----------------------------------
-// GELU in its tanh form, written with the logistic function: u * sigmoid(2 z), z = sqrt(2/pi) (u + 0.044715 u^3).
-// This keeps the relative accuracy in the negative tail, where 1 + tanh z cancels.
-__device__ __forceinline__ float gelu_tanh_dev(float u)
-{
-    const float z = 0.7978845608028654f * (u + 0.044715f * u * u * u);
-    return u * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * z));
-}
-
-__device__ __forceinline__ bool has_glue(const GemmArgs &a) { return a.act != 0 || a.residual != nullptr || a.gate != nullptr; }
-
-// Gate row of tile row d (0 <= d < span) without a division per element: the tile starts at row m_first, whose gate
-// row and remainder are computed once; rows of a tile cross at most one gate boundary when gate_rows >= span.
-struct GateRows {
-    int base, rem, rows;
-    bool one_step;
-    __device__ __forceinline__ GateRows(const void *gate, int gate_rows, int m_first, int span)
-    {
-        rows = gate ? gate_rows : 1;
-        base = m_first / rows;
-        rem = m_first - base * rows;
-        one_step = rows >= span;
-    }
-    __device__ __forceinline__ int of(int d) const { return one_step ? base + (rem + d >= rows ? 1 : 0) : base + (rem + d) / rows; }
-};
-
-// one element: u is the layer's fp32 value, grow its gate row
-__device__ __forceinline__ _Float16 glue_one(const GemmArgs &a, float u, int m, int n, int grow)
-{
-    if (a.act == 1) u = gelu_tanh_dev(u);
-    asm volatile("" : "+v"(u));   // keep the fp32 value: it is rounded to fp16 here and nowhere earlier
-    _Float16 h = (_Float16)u;
-    if (a.residual || a.gate) {
-        const float g = a.gate ? half_to_float_dev(static_cast<const unsigned short *>(a.gate)[(unsigned)(grow * a.N + n)]) : 1.0f;
-        const float r = a.residual ? half_to_float_dev(static_cast<const unsigned short *>(a.residual)[(unsigned)(m * a.N + n)]) : 0.0f;
-        float v = __builtin_fmaf(g, (float)h, r);
-        asm volatile("" : "+v"(v));
-        h = (_Float16)v;
-    }
-    return h;
-}
-
-// what the staged write-back needs of the glue, by value (a pointer to the kernel arguments would force them into
-// scratch memory)
-struct GluePieces {
-    const _Float16 *gate = nullptr, *residual = nullptr;
-    int gate_rows = 1;
-    bool on = false;
-};
-
-// eight neighbouring elements of one row at once (16-byte pieces of the staged tile); g and r were loaded ahead
-typedef _Float16 h8 __attribute__((ext_vector_type(8)));
-__device__ __forceinline__ v4i glue_piece(bool has_g, bool has_r, v4i hv, h8 g, h8 r)
-{
-    h8 h = __builtin_bit_cast(h8, hv);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        float v = __builtin_fmaf(has_g ? (float)g[e] : 1.0f, (float)h[e], has_r ? (float)r[e] : 0.0f);
-        asm volatile("" : "+v"(v));
-        h[e] = (_Float16)v;
-    }
-    return __builtin_bit_cast(v4i, h);
-}
 
 // Tile shape: a workgroup of WGM x WGN wavefronts, each owning TM x TN MFMA
 // tiles of 32x32, walks K in steps of BK int8.
@@ -368,101 +279,6 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_mfma(GemmArgs a, int tile
     };
     if (full) emit(std::false_type{});
     else emit(std::true_type{});
-}
-
-// ---------------------------------------------------------------------------------------------
-// Epilogue for a full tile (no ragged edge, N % 8 == 0).  Each wavefront dequantizes one 32-row
-// block of its accumulators at a time, parks the fp16 results in a private LDS strip
-// [32 rows][TN*32 columns] (row pitch padded by 16 bytes), and reads the strip back as 16-byte
-// pieces, so that every global store instruction writes whole contiguous row segments of
-// TN*64 bytes instead of 2-byte elements.
-//   value(i, j, r) -> fp32 result before the fp16 rounding (W8: fma(float(acc)*s_a, s_w, bias))
-// ---------------------------------------------------------------------------------------------
-// The MFMA result layout gives a lane ONE column (lane & 31) and 16 rows.  Two neighbouring lanes swap
-// one value per pair of consecutive rows (DPP quad_perm), so that the even lane ends up with columns
-// (n, n+1) of the even row and the odd lane with columns (n-1, n) of the odd row: every element then
-// leaves the lane as half of a 4-byte word instead of a 2-byte store.
-//   STAGED: the words go to the LDS strip and are read back as 16-byte pieces (whole row segments per store);
-//   otherwise they are stored to global memory directly (64-byte row segments per half wavefront).
-template <int TM, int TN, bool STAGED, int ROWS = 32, class ValueFn>
-__device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane, _Float16 *y, int N, int m_base, int n_base,
-                                                  ValueFn value, GluePieces glue = GluePieces())
-{
-    constexpr int PITCH = TN * 64 + 16;
-    constexpr int CH = TN * 4;  // 16-byte pieces per row
-    const int frag_row = lane & 31, frag_half = lane >> 5, odd = lane & 1;
-    // v_perm_b32 selector: bytes of {hi source = neighbour's pair, lo source = own pair}
-    //   even lane: (own.lo16, nbr.lo16) -> bytes 0,1 of own then 0,1 of neighbour = 0x05040100
-    //   odd lane:  (nbr.hi16, own.hi16) -> bytes 2,3 of neighbour then 2,3 of own = 0x03020706
-    const unsigned sel = odd ? 0x03020706u : 0x05040100u;
-    unsigned char *wr = strip + (4 * frag_half + odd) * PITCH + (frag_row - odd) * 2;
-    const unsigned g_off = (unsigned)((m_base + 4 * frag_half + odd) * N + n_base + frag_row - odd);
-    static_assert(ROWS == 32 || ROWS == 16, "the strip holds a whole 32-row block or one half of it");
-    constexpr int HALVES = 32 / ROWS;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-        for (int h = 0; h < HALVES; ++h) {
-            // gate and residual of the pieces this lane will write back are requested before the block is dequantized
-            constexpr int PIECES = ROWS * CH / 64;
-            h8 pg[PIECES], pr[PIECES];
-            if (glue.on) {
-                const GateRows gr(glue.gate, glue.gate_rows, m_base, TM * 32);
-#pragma unroll
-                for (int t = 0; t < PIECES; ++t) {
-                    const int id = lane + 64 * t;
-                    const int row = i * 32 + h * ROWS + id / CH, col = n_base + (id % CH) * 8;
-                    if (glue.gate) pg[t] = *reinterpret_cast<const h8 *>(glue.gate + (unsigned)(gr.of(row) * N + col));
-                    if (glue.residual) pr[t] = *reinterpret_cast<const h8 *>(glue.residual + (unsigned)((m_base + row) * N + col));
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int r = h * (16 / HALVES); r < (h + 1) * (16 / HALVES); r += 2) {
-                    float u0 = value(i, j, r), u1 = value(i, j, r + 1);
-                    // keep the fp32 rounding of the fused multiply-add: without this the compiler may select a
-                    // mixed-precision fma that rounds straight to fp16 (one rounding instead of the defined two)
-                    asm volatile("" : "+v"(u0), "+v"(u1));
-                    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-                    const h2 pr = {(_Float16)u0, (_Float16)u1};
-                    const unsigned own = __builtin_bit_cast(unsigned, pr);
-                    // every lane has a valid source, so no fill value is needed (the update form would first clear the destination)
-                    const unsigned nbr = (unsigned)__builtin_amdgcn_mov_dpp((int)own, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true);
-                    const unsigned word = __builtin_amdgcn_perm(nbr, own, sel);
-                    const int row = 8 * (r / 4) + (r % 4);  // + 4*frag_half + odd, already in the lane's base
-                    if (STAGED)
-                        *reinterpret_cast<unsigned __attribute__((may_alias)) *>(wr + (row - h * ROWS) * PITCH + j * 64) = word;
-                    else
-                        *reinterpret_cast<unsigned __attribute__((may_alias)) *>(y + (g_off + (unsigned)((i * 32 + row) * N + j * 32))) = word;
-                }
-            if (STAGED) {
-                asm volatile("" ::: "memory");  // the strip reads below see other lanes' writes: keep program order
-#pragma unroll
-                for (int t = 0; t < ROWS * CH / 64; ++t) {
-                    const int id = lane + 64 * t;
-                    const int row = id / CH, ch = id % CH;
-                    v4i v = *reinterpret_cast<const v4i_alias *>(strip + row * PITCH + ch * 16);
-                    // gate and residual meet the fp16 result here, eight elements of a row at a time
-                    if (glue.on) v = glue_piece(glue.gate != nullptr, glue.residual != nullptr, v, pg[t], pr[t]);
-                    // the output is written once and not read again by this kernel: keep it from displacing the operand panels in L2
-                    __builtin_nontemporal_store(v, reinterpret_cast<v4i_alias *>(y + (unsigned)((m_base + i * 32 + h * ROWS + row) * N + n_base + ch * 8)));
-                }
-                asm volatile("" ::: "memory");
-            }
-        }
-    }
-}
-
-typedef float v16f __attribute__((ext_vector_type(16)));
-typedef _Float16 v8h __attribute__((ext_vector_type(8)));
-
-// one 32x32 MFMA over a 16-byte fragment per lane: 32 int8 or 16 binary16 along K
-template <bool F16, class Acc>
-__device__ __forceinline__ Acc mfma_step(v4i a, v4i b, Acc c)
-{
-    if constexpr (F16) return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
-    else return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1100,6 +916,20 @@ using H_p192 = TileD<2, 3, 2, 2, 2, 2, true, 1, false, 2, true, true>;
 using H_p128 = TileD<2, 2, 2, 2, 3, 2, true, 1, false, 2, true, true>;
 
 static const Variant VARIANTS[] = {
+    {"w8 dma 64x64 s4 4w", 8, 64, 64, 128, run_dma<D8_64x64_s4>, run_dma<D8_64x64_s4, true>},
+    {"w8 dma 256x192 a3b2 8w spread1", 8, 256, 192, 128, run_dma<D8_256x192_8w_a3b2>, run_dma<D8_256x192_8w_a3b2, true>},
+    {"w8 dma 128x128 a3b2 4w", 8, 128, 128, 128, run_dma<D8_128x128_a3b2>, run_dma<D8_128x128_a3b2, true>},
+    {"w8 dma 128x128 a3b2 4w spread1", 8, 128, 128, 128, run_dma<D8_128x128_a3b2_e1>, run_dma<D8_128x128_a3b2_e1, true>},
+    {"w8 dma 128x128 a3b2 4w spread1 persistent", 8, 128, 128, 128, run_dma<P8_128x128_a3b2>},
+    {"w8 dma 128x192 s2 4w spread1 persistent", 8, 128, 192, 128, run_dma<P8_128x192_s2>},
+    {"f16 dma 256x192 a3b2 8w spread1", 16, 256, 192, 64, run_dma<H_256x192_8w>, run_dma<H_256x192_8w, true>},
+    {"f16 dma 128x128 a3b2 4w spread1", 16, 128, 128, 64, run_dma<H_128x128_4w>, run_dma<H_128x128_4w, true>},
+    {"f16 dma 64x64 s4 4w", 16, 64, 64, 64, run_dma<H_64x64_4w>, run_dma<H_64x64_4w, true>},
+    {"f16 dma 128x192 s2 4w spread1 persistent", 16, 128, 192, 64, run_dma<H_p192>},
+    {"w8 128x128 bk64 4w occ3", 8, 128, 128, 64, run_variant<W8_128x128_k64_o3>, run_variant<W8_128x128_k64_o3, true>},
+    {"w4 any-group 64x64 bk128 4w occ4", 4, 64, 64, 128, run_variant<W4G_64x64_k128>, run_variant<W4G_64x64_k128, true>},
+    {"w4 pipelined 128x128 a3b2 4w any-group", 4, 128, 128, 128, launch_qgemm_w4, launch_qgemm_w4},
+#ifdef QL_SWEEP_VARIANTS   // the other tile shapes of the sweeps that chose the ones above
     {"w8 dma 128x128 s3 4w", 8, 128, 128, 128, run_dma<D8_128x128_s3>},
     {"w8 dma 128x128 s2 4w", 8, 128, 128, 128, run_dma<D8_128x128_s2>},
     {"w8 dma 128x192 s3 4w", 8, 128, 192, 128, run_dma<D8_128x192_s3>},
@@ -1108,24 +938,14 @@ static const Variant VARIANTS[] = {
     {"w8 dma 256x192 s2 4w", 8, 256, 192, 128, run_dma<D8_256x192_s2>},
     {"w8 dma 256x256 s2 8w", 8, 256, 256, 128, run_dma<D8_256x256_8w>},
     {"w8 dma 256x192 s2 8w", 8, 256, 192, 128, run_dma<D8_256x192_8w>},
-    {"w8 dma 64x64 s4 4w", 8, 64, 64, 128, run_dma<D8_64x64_s4>, run_dma<D8_64x64_s4, true>},
     {"w8 dma 256x192 s2 8w spread1", 8, 256, 192, 128, run_dma<D8_256x192_8w_e1>},
     {"w8 dma 256x256 s2 8w spread1", 8, 256, 256, 128, run_dma<D8_256x256_8w_e1>},
     {"w8 dma 256x256 s2 8w spread2", 8, 256, 256, 128, run_dma<D8_256x256_8w_e2>},
     {"w8 dma 256x192 s2 4w spread2", 8, 256, 192, 128, run_dma<D8_256x192_4w_e2>},
     {"w4 dma 128x128 s2 4w", 4, 128, 128, 128, run_dma<D4_128x128_4w>},
-    {"w8 dma 256x192 a3b2 8w spread1", 8, 256, 192, 128, run_dma<D8_256x192_8w_a3b2>, run_dma<D8_256x192_8w_a3b2, true>},
     {"w8 dma 256x192 a2b3 8w spread1", 8, 256, 192, 128, run_dma<D8_256x192_8w_a2b3>},
     {"w8 dma 256x256 a3b2 8w spread1", 8, 256, 256, 128, run_dma<D8_256x256_8w_a3b2>},
-    {"w8 dma 128x128 a3b2 4w", 8, 128, 128, 128, run_dma<D8_128x128_a3b2>, run_dma<D8_128x128_a3b2, true>},
-    {"w8 dma 128x128 a3b2 4w spread1", 8, 128, 128, 128, run_dma<D8_128x128_a3b2_e1>, run_dma<D8_128x128_a3b2_e1, true>},
     {"w8 dma 128x128 s2 4w spread1", 8, 128, 128, 128, run_dma<D8_128x128_s2_e1>},
-    {"w8 dma 128x128 a3b2 4w spread1 persistent", 8, 128, 128, 128, run_dma<P8_128x128_a3b2>},
-    {"w8 dma 128x192 s2 4w spread1 persistent", 8, 128, 192, 128, run_dma<P8_128x192_s2>},
-    {"f16 dma 256x192 a3b2 8w spread1", 16, 256, 192, 64, run_dma<H_256x192_8w>, run_dma<H_256x192_8w, true>},
-    {"f16 dma 128x128 a3b2 4w spread1", 16, 128, 128, 64, run_dma<H_128x128_4w>, run_dma<H_128x128_4w, true>},
-    {"f16 dma 64x64 s4 4w", 16, 64, 64, 64, run_dma<H_64x64_4w>, run_dma<H_64x64_4w, true>},
-    {"f16 dma 128x192 s2 4w spread1 persistent", 16, 128, 192, 64, run_dma<H_p192>},
     {"f16 dma 128x128 a3b2 4w spread1 persistent", 16, 128, 128, 64, run_dma<H_p128>},
     {"w8 128x128 bk64 4w occ2", 8, 128, 128, 64, run_variant<W8_128x128_k64>},
     {"w8 128x128 bk128 4w occ2", 8, 128, 128, 128, run_variant<W8_128x128_k128>},
@@ -1135,7 +955,6 @@ static const Variant VARIANTS[] = {
     {"w8 256x192 bk64 4w occ1", 8, 256, 192, 64, run_variant<W8_256x192_k64>},
     {"w8 256x256 bk64 8w occ2", 8, 256, 256, 64, run_variant<W8_256x256_8w>},
     {"w8 64x64 bk64 4w occ4", 8, 64, 64, 64, run_variant<W8_64x64_k64>},
-    {"w8 128x128 bk64 4w occ3", 8, 128, 128, 64, run_variant<W8_128x128_k64_o3>, run_variant<W8_128x128_k64_o3, true>},
     {"w4 128x128 bk128 4w occ2", 4, 128, 128, 128, run_variant<W4_128x128_k128>},
     {"w4 64x128 bk128 4w occ2", 4, 64, 128, 128, run_variant<W4_64x128_k128>},
     {"w4 256x128 bk128 8w occ2", 4, 256, 128, 128, run_variant<W4_256x128_8w>},
@@ -1143,7 +962,7 @@ static const Variant VARIANTS[] = {
     {"w4 any-group 128x64 bk128 4w occ3", 4, 128, 64, 128, run_variant<W4G_128x64_k128>, run_variant<W4G_128x64_k128, true>},
     {"w4 any-group 128x128 bk128 4w occ2", 4, 128, 128, 128, run_variant<W4G_128x128_k128>},
     {"w4 any-group 64x128 bk128 4w occ3", 4, 64, 128, 128, run_variant<W4G_64x128_k128>},
-    {"w4 any-group 64x64 bk128 4w occ4", 4, 64, 64, 128, run_variant<W4G_64x64_k128>, run_variant<W4G_64x64_k128, true>},
+#endif
 };
 constexpr int NUM_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);
 
@@ -1177,7 +996,11 @@ static int choose_variant(const GemmArgs &a)
         if ((long)((a.M + 255) / 256) * ((a.N + 191) / 192) < 192) return h_mid;
         return (a.M >= 4096 && a.N < 4096) ? h_p192 : h_big;
     }
-    if (a.w_bits == 4) return w4_any;
+    // 4-bit weights: the pipelined kernel where the tile's group scales fit its LDS table and the rows fill tiles
+    if (a.w_bits == 4) {
+        static const int w4_pipe = find_variant("w4 pipelined 128x128 a3b2 4w any-group");
+        return (qgemm_w4_takes(a) && a.M > 256) ? w4_pipe : w4_any;
+    }
     if (a.K % 128 != 0) return w8_k64;
     if (a.M <= 512) return w8_small;
     const long tiles_big = (long)((a.M + 255) / 256) * ((a.N + 191) / 192);
@@ -1191,7 +1014,7 @@ static int choose_variant(const GemmArgs &a)
     return a.K >= 2304 ? w8_mid_deep : w8_mid;
 }
 
-static bool is_any_group(int v) { return __builtin_strncmp(VARIANTS[v].name, "w4 any-group", 12) == 0; }
+static bool is_any_group(int v) { return __builtin_strstr(VARIANTS[v].name, "any-group") != nullptr; }
 
 hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream)
 {
@@ -1208,6 +1031,7 @@ hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream)
         // group sizes other than 128 run on the variants that end a group at any 32-wide K slice
         static const int any_group = find_variant("w4 any-group 64x64 bk128 4w occ4");
         if (a.group != 128 && !is_any_group(v)) v = any_group;
+        if (__builtin_strstr(VARIANTS[v].name, "w4 pipelined") && !qgemm_w4_takes(a)) v = any_group;
         // the pipelined 4-bit kernel keeps the group scales of a tile in LDS: at most 40 groups (K <= 5120)
         if (a.K > 128 * 40 && __builtin_strncmp(VARIANTS[v].name, "w4 dma", 6) == 0)
             v = find_variant("w4 128x64 bk128 4w occ3");
