@@ -113,6 +113,27 @@ int qlinear_w8a8(const void *x, int64_t M, int64_t K, int64_t R,
                  void *workspace, size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------
+ * qlinear_w8a8 for callers that cannot allocate or hand over device memory:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arithmetic, same results and same argument meaning as
+ * qlinear_w8a8 without the debug exports; the scratch (codes, activation scales,
+ * partial maxima) is a fixed array inside the library, qlinear_noalloc_max_bytes()
+ * = 24 MiB per GPU, held by every GPU the library runs on until the process ends.
+ *   - The call allocates nothing (no hipMalloc / hipFree, no allocating library
+ *     routine); the first call on a device looks the array's address up once.
+ *   - QL_ERR_WORKSPACE if qlinear_workspace_bytes(M, K, R) exceeds the array
+ *     (M*K up to about 25 million, e.g. 16384 x 1152); the other errors as
+ *     qlinear_w8a8.
+ *   - All calls on one GPU share the array, which keeps the last call's contents
+ *     (nothing in it needs clearing between calls): calls that overlap in time on
+ *     one GPU, on any streams, race.  Calls in order on one stream are safe.
+ * ---------------------------------------------------------------------- */
+size_t qlinear_noalloc_max_bytes(void);
+int qlinear_w8a8_noalloc(const void *x, int64_t M, int64_t K, int64_t R,
+                         const void *w, const void *w_scale, const void *bias, int64_t N,
+                         void *y, void *stream);
+
+/* ------------------------------------------------------------------------
  * Quantized linear with 4-bit group-128 weights (Step 2: integer weights with
  * per-group scales; symmetric, zero-point 0, as in the ablation section):
  *   P[m,g,n] = sum_{k in group g} q[m,k] * w4[n,k]          (int32, g = k/128)

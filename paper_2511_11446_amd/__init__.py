@@ -22,7 +22,7 @@ EXPORTS = ("ql_status_string", "ql_last_device_error", "ql_version", "daq_worksp
            "ql_pack_w4_host", "ql_plan_create", "ql_plan_destroy", "ql_plan_num_layers",
            "ql_plan_workspace_bytes", "qlinear_plan_run", "ql_set_gemm_variant", "ql_num_gemm_variants",
            "ql_gemm_variant_name", "ql_probe_mfma_int8", "daq_quantize_robust", "qlinear_plan_run_robust", "ql_time_bin",
-           "qlinear_w4a8_g", "qgemm_w4a8_g", "qlinear_w8a8_fused", "qlinear_w4a8_fused", "qlinear_f16", "ql_repack_w4_pairs_host", "qlinear_plan_run_ex")
+           "qlinear_w4a8_g", "qgemm_w4a8_g", "qlinear_w8a8_fused", "qlinear_w4a8_fused", "qlinear_f16", "ql_repack_w4_pairs_host", "qlinear_plan_run_ex", "qlinear_w8a8_noalloc", "qlinear_noalloc_max_bytes")
 
 
 class QlError(RuntimeError):
@@ -117,6 +117,10 @@ def lib():
     L.ql_time_bin.argtypes = [_i64, _i64]
     L.ql_time_bin.restype = _int
     L.ql_set_gemm_variant.argtypes = [_int]
+    L.qlinear_noalloc_max_bytes.restype = _sz
+    L.qlinear_noalloc_max_bytes.argtypes = []
+    L.qlinear_w8a8_noalloc.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _i64, _vp, _vp]
+    L.qlinear_w8a8_noalloc.restype = _int
     _lib = L
     return L
 
@@ -290,6 +294,14 @@ def qlinear_w8a8(x, R, w, w_scale, bias=None, y=None, debug=False, ws=None, stre
     if w.shape[1] != x.shape[1]:
         raise ValueError("w must be [N,K]")
     return _qlinear("qlinear_w8a8", x, R, w, w_scale, bias, w.shape[0], y, debug, ws, stream)
+
+
+def qlinear_w8a8_noalloc(x, R, w, w_scale, bias, y, stream=None):
+    """qlinear_w8a8 on the library's own fixed scratch: the call allocates nothing; y is the caller's."""
+    M, K = x.shape
+    _check(lib().qlinear_w8a8_noalloc(_ptr(x), M, K, R, _ptr(w), _ptr(w_scale), _ptr(bias), w.shape[0], _ptr(y), _stream(stream)),
+           "qlinear_w8a8_noalloc")
+    return y
 
 
 def qlinear_w4a8(x, R, w4, w_scale, bias=None, y=None, debug=False, ws=None, stream=None, group=128):

@@ -9,6 +9,12 @@
 #include <new>
 #include <vector>
 
+// Scratch of the allocation-free entry point (qlinear_w8a8_noalloc): one array per GPU the library runs on, held until
+// the process ends.  In host code this name is only a handle for hipGetSymbolAddress; the device address it yields is
+// what kernels and launches receive.
+#define QL_NOALLOC_SCRATCH_BYTES (24u << 20)
+static __device__ __align__(256) unsigned char scratch[QL_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local int g_last_device_error = 0;
@@ -163,6 +169,27 @@ int run_layer(const void *x, int64_t M, int64_t K, int64_t R, int w_bits, const 
         g.gate_rows = (int)fu->gate_rows;
     }
     return device_status(ql::launch_qgemm(g, g_gemm_variant.load(), stream));
+}
+
+// device address of `scratch` on the current device, looked up once per device
+constexpr int NOALLOC_MAX_DEVICES = 64;
+std::atomic<void *> g_scratch_ptr[NOALLOC_MAX_DEVICES];
+
+int noalloc_scratch(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return device_status(e);
+    if (dev < 0 || dev >= NOALLOC_MAX_DEVICES) return QL_ERR_UNSUPPORTED;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return device_status(e);
+        if (!p) return QL_ERR_DEVICE;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return QL_OK;
 }
 
 int check_fusion(const ql_fusion *fu, int64_t M)
@@ -327,6 +354,24 @@ int qlinear_w8a8(const void *x, int64_t M, int64_t K, int64_t R, const void *w, 
                  void *stream)
 {
     return qlinear_any(8, x, M, K, R, w, w_scale, bias, N, y, dbg, workspace, workspace_bytes, stream);
+}
+
+size_t qlinear_noalloc_max_bytes(void) { return QL_NOALLOC_SCRATCH_BYTES; }
+
+int qlinear_w8a8_noalloc(const void *x, int64_t M, int64_t K, int64_t R, const void *w, const void *w_scale,
+                         const void *bias, int64_t N, void *y, void *stream)
+{
+    int rc = check_layer_ptrs(x, w, w_scale, bias, y, nullptr, 8);
+    if (rc) return rc;
+    rc = check_shape(M, K, R, N);
+    if (rc) return rc;
+    if (layer_ws(M, K, R).total > QL_NOALLOC_SCRATCH_BYTES) return QL_ERR_WORKSPACE;
+    void *ws = nullptr;
+    rc = noalloc_scratch(&ws);
+    if (rc) return rc;
+    // nothing in the scratch has to start at zero: codes, scales and partial maxima are written before they are read
+    // (the atomic-maximum fallback of the DAQ pass clears its block maxima with a fill kernel of its own)
+    return run_layer(x, M, K, R, 8, w, w_scale, bias, N, y, nullptr, ws, static_cast<hipStream_t>(stream));
 }
 
 int qlinear_w4a8(const void *x, int64_t M, int64_t K, int64_t R, const void *w4, const void *w_scale,
