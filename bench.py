@@ -133,6 +133,80 @@ def cpu_baseline(wl_name, wl, layers, budget_rows=8192, min_seconds=10.0, max_pa
             "seconds": t_total}
 
 
+def planner_demo(ql, torch, args):
+    """Per-layer latencies measured on this GPU -> ql_plan_greedy (Algorithm 2, Phase A) -> the chosen plan timed through the
+    plan runner.  Sensitivities and drifts are seeded stand-ins (the paper measures them on its trained model): drift large
+    at the first steps and decaying, sensitivity highest in the first and last blocks."""
+    M, R, T = 16384, 1, 50
+    stream = torch.cuda.current_stream()
+
+    def timed(fn, reps=10):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a0.record(stream)
+        for _ in range(reps):
+            fn()
+        a1.record(stream)
+        torch.cuda.synchronize()
+        return a0.elapsed_time(a1) / reps * 1e3      # us
+
+    lat, dev = {}, {}
+    for name, K, N in workload.BLOCK_LAYERS:
+        x = torch.from_numpy(workload.activations(M, K, "planner", name)).cuda()
+        y = torch.empty((M, N), dtype=torch.float16, device="cuda")
+        ws = ql.workspace(ql.qlinear_workspace_bytes(M, K, R))
+        for bits in (16, 8, 4):
+            lw = workload.layer_weights(name, K, N, bits, "planner")
+            w = torch.from_numpy(ql.ql_pack_w4_host(lw["w"]) if bits == 4 else lw["w"]).cuda()
+            sw = None if bits == 16 else torch.from_numpy(lw["s_w"]).cuda()
+            b = torch.from_numpy(lw["bias"]).cuda()
+            dev[(name, bits)] = (w, sw, b)
+            if bits == 16:
+                lat[(name, bits)] = timed(lambda: ql.qlinear_f16(x, w, b, y=y))
+            elif bits == 8:
+                lat[(name, bits)] = timed(lambda: ql.qlinear_w8a8(x, R, w, sw, b, y=y, ws=ws))
+            else:
+                lat[(name, bits)] = timed(lambda: ql.qlinear_w4a8(x, R, w, sw, b, y=y, ws=ws))
+    g = workload.rng("planner-demo")
+    drift = 4.0 * np.exp(-np.arange(T) / 6.0) + 0.05 + 0.02 * g.random(T)
+    descs, layers = [], []
+    for blk in range(workload.N_BLOCKS):
+        for name, K, N in workload.BLOCK_LAYERS:
+            sens = 0.2 + 1.5 * max(0.0, 1.0 - min(blk, workload.N_BLOCKS - 1 - blk) / 4.0) + 0.3 * g.random()
+            floor = lat[(name, 4)]
+            layers.append(dict(bits=[16, 8, 4], c_lat=[T * (lat[(name, b)] - floor) for b in (16, 8, 4)],
+                               c_mem=[N * K * b / 8.0 for b in (16, 8, 4)], sensitivity=sens))
+            descs.append((name, K, N))
+    c_step = np.full(T, sum(lat[(n, 4)] for n, _, _ in descs))
+    full_lat = float(c_step.sum() + sum(l["c_lat"][0] for l in layers))
+    full_mem = float(sum(l["c_mem"][0] for l in layers))
+    B_lat, B_mem = 0.45 * full_lat, 0.40 * full_mem
+    plan = ql.plan_greedy(drift, c_step, layers, B_lat, B_mem, 200000, eps=1e-9)
+    kept = np.flatnonzero(plan["kept"])
+    # run one step of the chosen plan
+    pl, xs, ys = [], [], []
+    xbuf = {n: torch.from_numpy(workload.activations(M, K, "planner", n)).cuda() for n, K, N in workload.BLOCK_LAYERS}
+    ybuf = {n: torch.empty((M, N), dtype=torch.float16, device="cuda") for n, K, N in workload.BLOCK_LAYERS}
+    for (name, K, N), bits in zip(descs, plan["bits"].tolist()):
+        w, sw, b = dev[(name, bits)]
+        pl.append(dict(K=K, N=N, bits=bits, group=128, w=w, w_scale=sw, bias=b))
+        xs.append(xbuf[name])
+        ys.append(ybuf[name])
+    P = ql.Plan(pl, M_max=M)
+    ws = ql.workspace(P.workspace_bytes(M, R))
+    step_us = timed(lambda: P.run(xs, ys, M, R, ws), reps=5)
+    counts = {b: int((plan["bits"] == b).sum()) for b in (16, 8, 4)}
+    print(json.dumps({"planner": "Algorithm 2 Phase A on latencies measured by this library", "M": M, "T": T,
+                      "measured_layer_us": {"%s/w%d" % k: v for k, v in lat.items()},
+                      "budget": {"latency_us": B_lat, "memory_bytes": B_mem, "of_full": [0.45, 0.40]},
+                      "plan_width_counts": counts, "kept_steps": int(len(kept)), "first_kept": kept[:8].tolist(),
+                      "feasible": plan["feasible"], "C_lat_us": plan["C_lat"], "C_mem_bytes": plan["C_mem"],
+                      "predicted_step_us": float(sum(lat[(n, b)] for (n, _, _), b in zip(descs, plan["bits"].tolist()))),
+                      "measured_step_us": step_us}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -150,6 +224,10 @@ def main():
     ap.add_argument("--fused-block", action="store_true",
                     help="time one block with GELU (fc1) and gated residuals (proj, fc2) folded into the epilogues, "
                          "against the same layers followed by separate elementwise kernels")
+    ap.add_argument("--planner", action="store_true",
+                    help="Algorithm 2 Phase A on MEASURED costs: time every layer type at 16/8/4-bit weights with this library, "
+                         "let ql_plan_greedy choose widths and kept timesteps under a latency and a memory budget, then time "
+                         "one step of the chosen plan through qlinear_plan_run")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: a few steps of the workload plus a device copy of known size, no timing")
     args = ap.parse_args()
@@ -167,6 +245,10 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     ql.set_gemm_variant(args.variant)
+
+    if args.planner:
+        planner_demo(ql, torch, args)
+        return
 
     wl, layers = build_layers(ql, torch, args.workload, args.w4_group)
     M, R = wl["M"], wl["R"]

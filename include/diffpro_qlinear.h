@@ -316,6 +316,68 @@ int qlinear_plan_run_ex(const ql_plan *plan, const void *const *x_in, void *cons
 int ql_time_bin(int64_t step, int64_t num_steps);
 
 /* ------------------------------------------------------------------------
+ * Offline side, host memory only (no device call): the stages that produce what
+ * the calls above consume.
+ *
+ * ql_schedule_topk: Step 4, eq. (6).  With T_tail = { t in C : t/T >= 1 - rho }
+ * the kept schedule is T_tail united with the k - |T_tail| steps of C \ T_tail
+ * that have the largest student-teacher error delta(t) of eq. (5) (equal delta:
+ * the earlier step first).  delta: [T] doubles indexed by timestep; candidates:
+ * n_candidates timesteps in [0, T) (duplicates ignored); rho in parts per
+ * million (200000 = the paper's 0.2; the tail test is done in integers);
+ * kept_out: k timesteps, ascending.  QL_ERR_SHAPE if k is below |T_tail| or
+ * above |C|, or a candidate lies outside [0, T).
+ *
+ * ql_plan_greedy: Algorithm 2, Phase A.  Starts from every layer at its widest
+ * option and all T steps kept, protects the last floor(rho T) steps, and while a
+ * budget is exceeded takes the better of: pruning the prunable step of lowest
+ * drift, scored c_step / (eps + D_e); or the best next-narrower move of a layer,
+ * scored (c_lat(l,b) - c_lat(l,b')) / (eps + s_M(l)).  Costs are the caller's
+ * numbers (for example per-layer latencies measured with this library):
+ * C_lat = sum of c_step over kept steps + sum of c_lat(l, Pi(l)),
+ * C_mem = sum of c_mem(l, Pi(l)).  While only the memory budget is exceeded no
+ * step is pruned (a step frees no memory); when nothing is left to take the
+ * plan is returned with *feasible_out = 0.  Outputs: bits_out[L] the chosen
+ * width per layer, kept_out[T] 1/0 per step, the two totals.
+ *
+ * ql_gptq_quantize_host: Step 2, the GPTQ packer.  W [N,K] fp32 row-major, H
+ * [K,K] doubles = the layer's X^T X over calibration inputs.  Inputs with
+ * H_kk = 0 are dropped, damp * mean(diag H) is added to the diagonal, U = the
+ * upper Cholesky factor of H^-1; columns are quantized in order, each group's
+ * scale (and zero point) taken per row from the already compensated weights at
+ * the group's first column, and each column's rounding error e = (w - w_hat) /
+ * U_kk is subtracted as e * U_kj from the columns j > k.  symmetric: codes in
+ * [-127,127] (8 bits) or [-2^(b-1), 2^(b-1)-1], zero point 0; otherwise codes
+ * 0 .. 2^b - 1 with a zero point, both stored minus 2^(b-1) so that codes fit
+ * int8 and (code - zero) is unchanged.  scale_fp16 != 0 rounds every scale to
+ * binary16 before it is used (what the 4-bit kernels read).  codes [N,K] int8,
+ * scales [N,K/group] fp32, zeros [N,K/group] int32 (may be NULL when symmetric).
+ * The int8 codes of a symmetric 4-bit run go to ql_pack_w4_host.
+ * QL_ERR_UNSUPPORTED: bits outside 2..8, or H not positive definite after damping.
+ * ---------------------------------------------------------------------- */
+int ql_schedule_topk(const double *delta, const int32_t *candidates, int32_t n_candidates, int32_t T,
+                     int32_t rho_ppm, int32_t k, int32_t *kept_out);
+
+typedef struct ql_planner_layer {
+    int32_t n_options;     /* widths the layer may take */
+    int32_t reserved;      /* 0 */
+    const int32_t *bits;   /* [n_options] distinct widths, any order */
+    const double *c_lat;   /* [n_options] latency cost at each width */
+    const double *c_mem;   /* [n_options] memory cost at each width */
+    double sensitivity;    /* s_M(l) */
+} ql_planner_layer;
+
+int ql_plan_greedy(const double *drift, const double *c_step, int32_t T,
+                   const ql_planner_layer *layers, int32_t L,
+                   double B_lat, double B_mem, int32_t rho_ppm, double eps,
+                   int32_t *bits_out, uint8_t *kept_out,
+                   double *C_lat_out, double *C_mem_out, int32_t *feasible_out);
+
+int ql_gptq_quantize_host(const float *W, int64_t N, int64_t K, const double *H,
+                          int32_t bits, int64_t group, int32_t symmetric, double damp, int32_t scale_fp16,
+                          int8_t *codes, float *scales, int32_t *zeros);
+
+/* ------------------------------------------------------------------------
  * Tuning hooks (benchmark sweeps).  ql_set_gemm_variant(v) forces GEMM tile
  * variant v for later calls from this process (-1 = choose by shape;
  * v == ql_num_gemm_variants() = the generic one-thread-per-element kernel);

@@ -22,7 +22,8 @@ EXPORTS = ("ql_status_string", "ql_last_device_error", "ql_version", "daq_worksp
            "ql_pack_w4_host", "ql_plan_create", "ql_plan_destroy", "ql_plan_num_layers",
            "ql_plan_workspace_bytes", "qlinear_plan_run", "ql_set_gemm_variant", "ql_num_gemm_variants",
            "ql_gemm_variant_name", "ql_probe_mfma_int8", "daq_quantize_robust", "qlinear_plan_run_robust", "ql_time_bin",
-           "qlinear_w4a8_g", "qgemm_w4a8_g", "qlinear_w8a8_fused", "qlinear_w4a8_fused", "qlinear_f16", "ql_repack_w4_pairs_host", "qlinear_plan_run_ex", "qlinear_w8a8_noalloc", "qlinear_noalloc_max_bytes")
+           "qlinear_w4a8_g", "qgemm_w4a8_g", "qlinear_w8a8_fused", "qlinear_w4a8_fused", "qlinear_f16", "ql_repack_w4_pairs_host", "qlinear_plan_run_ex", "qlinear_w8a8_noalloc", "qlinear_noalloc_max_bytes",
+           "ql_schedule_topk", "ql_plan_greedy", "ql_gptq_quantize_host")
 
 
 class QlError(RuntimeError):
@@ -426,6 +427,71 @@ class Plan:
             self.close()
         except Exception:
             pass
+
+
+class ql_planner_layer(ctypes.Structure):
+    _fields_ = [("n_options", ctypes.c_int32), ("reserved", ctypes.c_int32), ("bits", ctypes.POINTER(ctypes.c_int32)),
+                ("c_lat", ctypes.POINTER(ctypes.c_double)), ("c_mem", ctypes.POINTER(ctypes.c_double)),
+                ("sensitivity", ctypes.c_double)]
+
+
+def schedule_topk(delta, candidates, T, rho_ppm, k):
+    """Step 4, eq. (6): the k kept timesteps (ascending) = protected tail + the largest-delta steps of the rest."""
+    import numpy as np
+    d = np.ascontiguousarray(delta, dtype=np.float64)
+    c = np.ascontiguousarray(candidates, dtype=np.int32)
+    out = np.empty((max(k, 0),), np.int32)
+    rc = lib().ql_schedule_topk(d.ctypes.data_as(_vp), c.ctypes.data_as(_vp), ctypes.c_int32(len(c)), ctypes.c_int32(T),
+                                ctypes.c_int32(rho_ppm), ctypes.c_int32(k), out.ctypes.data_as(_vp))
+    _check(rc, "ql_schedule_topk")
+    return out
+
+
+def plan_greedy(drift, c_step, layers, B_lat, B_mem, rho_ppm, eps=1e-12):
+    """Algorithm 2, Phase A.  layers: list of dict(bits=[...], c_lat=[...], c_mem=[...], sensitivity=s).
+    Returns dict(bits=[L], kept=[T] bool, C_lat, C_mem, feasible)."""
+    import numpy as np
+    dr = np.ascontiguousarray(drift, dtype=np.float64)
+    cs = np.ascontiguousarray(c_step, dtype=np.float64)
+    T, L = len(dr), len(layers)
+    arr = (ql_planner_layer * L)()
+    keep = []
+    for i, l in enumerate(layers):
+        b = np.ascontiguousarray(l["bits"], dtype=np.int32)
+        cl = np.ascontiguousarray(l["c_lat"], dtype=np.float64)
+        cm = np.ascontiguousarray(l["c_mem"], dtype=np.float64)
+        keep += [b, cl, cm]
+        arr[i] = ql_planner_layer(len(b), 0, b.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                  cl.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+                                  cm.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), float(l["sensitivity"]))
+    bits = np.empty((L,), np.int32)
+    kept = np.empty((T,), np.uint8)
+    cl_out, cm_out, feas = ctypes.c_double(), ctypes.c_double(), ctypes.c_int32()
+    fn = lib().ql_plan_greedy
+    fn.argtypes = [_vp, _vp, ctypes.c_int32, ctypes.POINTER(ql_planner_layer), ctypes.c_int32, ctypes.c_double, ctypes.c_double,
+                   ctypes.c_int32, ctypes.c_double, _vp, _vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                   ctypes.POINTER(ctypes.c_int32)]
+    rc = fn(dr.ctypes.data_as(_vp), cs.ctypes.data_as(_vp), T, arr, L, B_lat, B_mem, rho_ppm, eps, bits.ctypes.data_as(_vp),
+            kept.ctypes.data_as(_vp), ctypes.byref(cl_out), ctypes.byref(cm_out), ctypes.byref(feas))
+    _check(rc, "ql_plan_greedy")
+    return dict(bits=bits, kept=kept.astype(bool), C_lat=cl_out.value, C_mem=cm_out.value, feasible=bool(feas.value))
+
+
+def gptq_quantize_host(W, H, bits, group, symmetric=True, damp=0.01, scale_fp16=False):
+    """Step 2, GPTQ: W fp32 [N,K], H float64 [K,K] -> (codes int8 [N,K], scales fp32 [N,K/group], zeros int32 [N,K/group])."""
+    import numpy as np
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    H = np.ascontiguousarray(H, dtype=np.float64)
+    N, K = W.shape
+    codes = np.empty((N, K), np.int8)
+    scales = np.empty((N, K // group), np.float32)
+    zeros = np.zeros((N, K // group), np.int32)
+    fn = lib().ql_gptq_quantize_host
+    fn.argtypes = [_vp, _i64, _i64, _vp, ctypes.c_int32, _i64, ctypes.c_int32, ctypes.c_double, ctypes.c_int32, _vp, _vp, _vp]
+    rc = fn(W.ctypes.data_as(_vp), N, K, H.ctypes.data_as(_vp), bits, group, 1 if symmetric else 0, damp, 1 if scale_fp16 else 0,
+            codes.ctypes.data_as(_vp), scales.ctypes.data_as(_vp), zeros.ctypes.data_as(_vp))
+    _check(rc, "ql_gptq_quantize_host")
+    return codes, scales, zeros
 
 
 def set_gemm_variant(v):
