@@ -338,8 +338,31 @@ def main():
             return a0.elapsed_time(a1) / reps * 1e3
 
         tf, tu = timed(fused), timed(unfused)
+        # LayerNorm + modulation in the DAQ prologue (what feeds qkv and fc1) against LayerNorm, modulation and DAQ as
+        # separate kernels (PyTorch's layer_norm and addcmul, then daq_quantize)
+        xr = torch.randn((M, hid), device="cuda", dtype=torch.float16)
+        shift = torch.randn((M // tokens, hid), device="cuda", dtype=torch.float16)
+        scale = torch.randn((M // tokens, hid), device="cuda", dtype=torch.float16) * 0.3
+        sh3, sc3 = shift.repeat_interleave(tokens, dim=0), (1.0 + scale).repeat_interleave(tokens, dim=0)
+        qb = torch.empty((M, hid), dtype=torch.int8, device="cuda")
+        sb = torch.empty((M,), dtype=torch.float32, device="cuda")
+        lib, vp = ql.lib(), ctypes.c_void_p
+        lib.daq_quantize_ln.argtypes = [vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, vp, vp, ctypes.c_int64, ctypes.c_float,
+                                        vp, vp, vp, vp, ctypes.c_size_t, vp]
+
+        def ln_fused():
+            lib.daq_quantize_ln(vp(xr.data_ptr()), M, hid, 1, vp(shift.data_ptr()), vp(scale.data_ptr()), tokens, 1e-6, None,
+                                vp(qb.data_ptr()), vp(sb.data_ptr()), None, 0, sptr)
+
+        def ln_separate():
+            h = torch.nn.functional.layer_norm(xr, (hid,), eps=1e-6)
+            h = torch.addcmul(sh3, h, sc3)
+            ql.daq_quantize(h, 1, qb, sb)
+
+        t_lnf, t_lns = timed(ln_fused), timed(ln_separate)
         print(json.dumps({"metric": "one block's four linears with GELU and gated residuals", "unit": "us",
                           "fused_epilogues_us": tf, "separate_elementwise_kernels_us": tu, "speedup": tu / tf,
+                          "layernorm_modulate_daq_one_kernel_us": t_lnf, "layernorm_modulate_then_daq_us": t_lns,
                           "config": {"workload": args.workload, "M": M, "rows_per_scale": R, "tokens_per_gate_row": tokens}}))
         return
 

@@ -75,6 +75,28 @@ int daq_quantize(const void *x, int64_t M, int64_t K, int64_t R,
                  void *workspace, size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------
+ * LayerNorm + adaptive modulation + DAQ in one pass (Step 3 keeps LayerNorm in
+ * higher precision in front of the quantized qkv and fc1 layers; Section 6
+ * counts it in the latency).  Per row, in fp32:
+ *   mu = mean(x), var = mean((x - mu)^2), n = (x - mu) / sqrt(var + eps)
+ *   h  = fp16( fma(n, 1 + scale[m / rows_per_mod, k], shift[m / rows_per_mod, k]) )
+ * then daq_quantize(h) -> q, scales.  LayerNorm has no affine parameters; shift
+ * and scale are the per-image modulation vectors of an adaptive-LayerNorm block
+ * (either may be NULL: 0).
+ *   x (device) [M,K] fp16;  shift, scale (device) [M/rows_per_mod, K] fp16 or NULL
+ *   h (device) [M,K] fp16 out or NULL: the normalised, modulated rows
+ *   q (device) [M,K] int8 out or NULL (then only h is written);  scales [M/R] fp32
+ * R = 1 runs in a single pass with the row held in registers; R > 1 needs h
+ * (the rows are staged there) and the workspace of daq_quantize.  Needs
+ * K % 8 == 0, K <= 4608 and 16-byte aligned x, shift, scale, h (QL_ERR_SHAPE /
+ * QL_ERR_ALIGN otherwise).
+ * ---------------------------------------------------------------------- */
+int daq_quantize_ln(const void *x, int64_t M, int64_t K, int64_t R,
+                    const void *shift, const void *scale, int64_t rows_per_mod, float eps,
+                    void *h, void *q, void *scales,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------
  * Optional exports of the integer intermediates, for verification.  Any
  * member may be NULL; the struct pointer itself may be NULL.  They are written
  * by the same kernels that produce y.

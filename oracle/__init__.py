@@ -322,3 +322,18 @@ def qlinear_w4a8(x, R, w4, s_w, bias, nthreads=1, want_debug=True):
     if rc:
         raise ValueError("orc_qlinear_w4a8 rc=%d" % rc)
     return dict(y=y.view(np.float16), q=q, s_a=s_a, P=P)
+
+
+def layernorm_modulate(x, shift=None, scale=None, rows_per_mod=1, eps=1e-6):
+    """LayerNorm without affine parameters followed by the adaptive modulation of a DiT block, in float64, rounded once
+    to binary32 and then to binary16 (Step 3: LayerNorm stays in higher precision in front of the quantized layers):
+        mu = mean(x), var = mean((x - mu)^2), n = (x - mu) / sqrt(var + eps), h = n * (1 + scale[m / rows_per_mod]) + shift[...]
+    x [M,K] float16; shift, scale [M/rows_per_mod, K] float16 or None.  Returns h float16 [M,K]."""
+    xd = np.asarray(x, dtype=np.float16).astype(np.float64)
+    M, K = xd.shape
+    mu = xd.sum(axis=1, keepdims=True) / K
+    var = ((xd - mu) ** 2).sum(axis=1, keepdims=True) / K
+    n = (xd - mu) / np.sqrt(var + eps)
+    g = 1.0 if scale is None else 1.0 + np.repeat(np.asarray(scale, np.float16).astype(np.float64), rows_per_mod, axis=0)
+    b = 0.0 if shift is None else np.repeat(np.asarray(shift, np.float16).astype(np.float64), rows_per_mod, axis=0)
+    return (n * g + b).astype(np.float32).astype(np.float16)

@@ -23,7 +23,7 @@ EXPORTS = ("ql_status_string", "ql_last_device_error", "ql_version", "daq_worksp
            "ql_plan_workspace_bytes", "qlinear_plan_run", "ql_set_gemm_variant", "ql_num_gemm_variants",
            "ql_gemm_variant_name", "ql_probe_mfma_int8", "daq_quantize_robust", "qlinear_plan_run_robust", "ql_time_bin",
            "qlinear_w4a8_g", "qgemm_w4a8_g", "qlinear_w8a8_fused", "qlinear_w4a8_fused", "qlinear_f16", "ql_repack_w4_pairs_host", "qlinear_plan_run_ex", "qlinear_w8a8_noalloc", "qlinear_noalloc_max_bytes",
-           "ql_schedule_topk", "ql_plan_greedy", "ql_gptq_quantize_host")
+           "ql_schedule_topk", "ql_plan_greedy", "ql_gptq_quantize_host", "daq_quantize_ln")
 
 
 class QlError(RuntimeError):
@@ -180,6 +180,27 @@ def daq_quantize(x, R, q=None, scales=None, ws=None, stream=None):
                             _stream(stream))
     _check(rc, "daq_quantize")
     return q, scales
+
+
+def daq_quantize_ln(x, R=1, shift=None, scale=None, rows_per_mod=1, eps=1e-6, want_h=False, want_q=True, ws=None, stream=None):
+    """LayerNorm + modulation + DAQ: x fp16 [M,K] -> dict(q int8, scales fp32 [M/R], h fp16 (if want_h or R > 1))."""
+    import torch
+    _need(x, torch.float16, name="x")
+    M, K = x.shape
+    out = {}
+    if want_h or R > 1:
+        out["h"] = torch.empty((M, K), dtype=torch.float16, device=x.device)
+    if want_q:
+        out["q"] = torch.empty((M, K), dtype=torch.int8, device=x.device)
+        out["scales"] = torch.empty((max(M // max(R, 1), 1),), dtype=torch.float32, device=x.device)
+    if ws is None and R > 1 and want_q:
+        ws = workspace(daq_workspace_bytes(M, K, R), x.device)
+    fn = lib().daq_quantize_ln
+    fn.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _i64, ctypes.c_float, _vp, _vp, _vp, _vp, _sz, _vp]
+    rc = fn(_ptr(x), M, K, R, _ptr(shift), _ptr(scale), rows_per_mod, eps, _ptr(out.get("h")), _ptr(out.get("q")),
+            _ptr(out.get("scales")), _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream))
+    _check(rc, "daq_quantize_ln")
+    return out
 
 
 class ql_fusion(ctypes.Structure):

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdiffpro_qlinear.so")
-SOURCES = ["daq.hip", "daq_robust.hip", "qgemm.hip", "qgemm_w4.hip", "probe.hip", "offline_host.hip", "api.hip"]
+SOURCES = ["daq.hip", "daq_robust.hip", "daq_ln.hip", "qgemm.hip", "qgemm_w4.hip", "probe.hip", "offline_host.hip", "api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",

@@ -337,6 +337,38 @@ int daq_quantize_robust(const void *x, int64_t M, int64_t K, int64_t R, const ql
     return daq_any(x, M, K, R, params, q, scales, workspace, workspace_bytes, stream);
 }
 
+int daq_quantize_ln(const void *x, int64_t M, int64_t K, int64_t R, const void *shift, const void *scale, int64_t rows_per_mod,
+                    float eps, void *h, void *q, void *scales, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!x || (!q && !h) || (q && !scales)) return QL_ERR_NULL;
+    if (misaligned(x, 16) || misaligned(shift, 16) || misaligned(scale, 16) || misaligned(h, 16) || misaligned(q, 8) ||
+        misaligned(scales, 4))
+        return QL_ERR_ALIGN;
+    int rc = check_shape(M, K, R, 1);
+    if (rc) return rc;
+    if (K % 8 != 0 || K > 4608 || !(eps >= 0.0f)) return QL_ERR_SHAPE;
+    if ((shift || scale) && (rows_per_mod < 1 || M % rows_per_mod != 0)) return QL_ERR_SHAPE;
+    if (R > 1 && q && !h) return QL_ERR_NULL;    // several rows per scale: the normalised rows are staged in h
+    if (R > 1 && q) {
+        rc = check_workspace(workspace, workspace_bytes, daq_workspace_bytes(M, K, R));
+        if (rc) return rc;
+    }
+    ql::LnDaqArgs a{};
+    a.x = x;
+    a.shift = shift;
+    a.scale = scale;
+    a.h = h;
+    a.q = R == 1 ? static_cast<int8_t *>(q) : nullptr;
+    a.scales = static_cast<float *>(scales);
+    a.M = (int)M;
+    a.K = (int)K;
+    a.rows_per_mod = (shift || scale) ? (int)rows_per_mod : 1;
+    a.eps = eps;
+    rc = device_status(ql::launch_daq_ln(a, static_cast<hipStream_t>(stream)));
+    if (rc || R == 1 || !q) return rc;
+    return daq_any(h, M, K, R, nullptr, q, scales, workspace, workspace_bytes, stream);
+}
+
 int ql_time_bin(int64_t step, int64_t num_steps)
 {
     if (num_steps < 1 || step < 0 || step >= num_steps) return -1;

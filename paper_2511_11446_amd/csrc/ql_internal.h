@@ -44,6 +44,19 @@ hipError_t launch_daq(const DaqArgs &a, hipStream_t stream);
 // eq. (4) with tau = a percentile of the magnitudes and a selectable code width
 hipError_t launch_daq_robust(const DaqArgs &a, hipStream_t stream);
 
+// LayerNorm + modulation + per-token DAQ in one pass (daq_ln.hip); K % 8 == 0, K <= 4608, 16-byte aligned rows
+struct LnDaqArgs {
+    const void *x;       // [M,K] fp16
+    const void *shift;   // [M/rows_per_mod, K] fp16 or null (0)
+    const void *scale;   // [M/rows_per_mod, K] fp16 or null (0): h = n * (1 + scale) + shift
+    void *h;             // [M,K] fp16 out, or null
+    int8_t *q;           // [M,K] out, or null (then only h is produced)
+    float *scales;       // [M] out
+    int M, K, rows_per_mod;
+    float eps;
+};
+hipError_t launch_daq_ln(const LnDaqArgs &a, hipStream_t stream);
+
 // ---- GEMM + dequantization -------------------------------------------------
 struct GemmArgs {
     const int8_t *q;      // [M,K] activation codes

@@ -245,3 +245,20 @@ def test_repack_from_pair_order_equals_packing_the_codes(orc):
     assert L.ql_repack_w4_pairs_host(buf, 5, 64, buf) == 4          # in place
     assert L.ql_repack_w4_pairs_host(buf, 5, 60, buf) in (2, 4)
     assert L.ql_repack_w4_pairs_host(None, 5, 64, buf) == 1
+
+
+def test_layernorm_daq_argument_checks():
+    L = ql.lib()
+    fn = L.daq_quantize_ln
+    fn.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                   ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    A = ctypes.c_void_p(0x10000)
+    assert fn(None, 8, 64, 1, None, None, 1, 1e-6, None, A, A, None, 0, None) == 1
+    assert fn(A, 8, 64, 1, None, None, 1, 1e-6, None, None, None, None, 0, None) == 1      # nothing to produce
+    assert fn(A, 8, 64, 1, None, None, 1, 1e-6, None, A, None, None, 0, None) == 1          # codes without scales
+    assert fn(ctypes.c_void_p(0x10008), 8, 64, 1, None, None, 1, 1e-6, None, A, A, None, 0, None) == 3
+    assert fn(A, 8, 60, 1, None, None, 1, 1e-6, None, A, A, None, 0, None) == 2             # K % 8
+    assert fn(A, 8, 4616, 1, None, None, 1, 1e-6, None, A, A, None, 0, None) == 2           # longer than the register row
+    assert fn(A, 8, 64, 1, A, None, 3, 1e-6, None, A, A, None, 0, None) == 2                # M % rows_per_mod
+    assert fn(A, 8, 64, 4, None, None, 1, 1e-6, None, A, A, None, 0, None) == 1             # R > 1 needs h
+    assert fn(A, 8, 64, 4, None, None, 1, 1e-6, A, A, A, None, 0, None) in (0, 5, 6)        # shape ok: workspace or device next

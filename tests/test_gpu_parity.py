@@ -854,6 +854,64 @@ def test_layers_seeded_random_shapes(gpu, orc):
             assert (np.abs(y.astype(np.float64) - ref.astype(np.float64)) <= tol).all(), case
 
 
+# ------------------------------------------------------------------ LayerNorm + modulation in the DAQ prologue
+
+def _ln_tolerance(x, sh, sc, rows_per_mod, ref):
+    """One fp16 step of the result, plus what fp32 evaluation can lose where n (1 + scale) and shift nearly cancel:
+    2^-18 of their magnitudes (a handful of fp32 roundings; 128 times below one fp16 step of those magnitudes)."""
+    xd = x.astype(np.float64)
+    mu = xd.mean(axis=1, keepdims=True)
+    n = (xd - mu) / np.sqrt(((xd - mu) ** 2).mean(axis=1, keepdims=True) + 1e-6)
+    g = 1.0 if sc is None else 1.0 + np.repeat(sc.astype(np.float64), rows_per_mod, 0)
+    b = 0.0 if sh is None else np.repeat(sh.astype(np.float64), rows_per_mod, 0)
+    return 2.0 ** -10 * np.abs(ref.astype(np.float64)) + 2.0 ** -18 * (np.abs(n * g) + np.abs(b)) + 2.0 ** -24
+
+
+LN_CASES = [(64, 1152, 1, 16), (300, 1152, 1, 100), (37, 64, 1, 1), (48, 4608, 1, 48), (1024, 1152, 256, 256), (96, 384, 96, 32)]
+
+
+@pytest.mark.parametrize("M,K,R,rows_per_mod", LN_CASES)
+def test_layernorm_modulate_daq(gpu, orc, M, K, R, rows_per_mod):
+    """h (normalised, modulated rows) within one fp16 step of the float64 oracle; the codes and scales are the oracle's
+    DAQ of the kernel's own h, bit for bit (the integer decision is taken on the same fp16 values on both sides)."""
+    say("ln+daq", M, K, R, rows_per_mod)
+    g = workload.rng("ln", M, K)
+    x = (workload.activations(M, K, "ln", sigma=2.0).astype(np.float32) + np.float32(1.5)).astype(np.float16)   # non-zero mean
+    sc = (g.standard_normal((M // rows_per_mod, K)) * 0.3).astype(np.float16)
+    sh = (g.standard_normal((M // rows_per_mod, K)) * 0.5).astype(np.float16)
+    for use_mod in (True, False):
+        out = gpu.daq_quantize_ln(dev(x), R, dev(sh) if use_mod else None, dev(sc) if use_mod else None, rows_per_mod, 1e-6, want_h=True)
+        h = host(out["h"])
+        ref = orc.layernorm_modulate(x, sh if use_mod else None, sc if use_mod else None, rows_per_mod, 1e-6)
+        a, b = h.astype(np.float64), ref.astype(np.float64)
+        assert (np.abs(a - b) <= _ln_tolerance(x, sh if use_mod else None, sc if use_mod else None, rows_per_mod, ref)).all()
+        assert (h.view(np.uint16) != ref.view(np.uint16)).mean() < 0.01
+        q_ref, s_ref = orc.daq(h, R, nthreads=8)
+        assert np.array_equal(host(out["q"]), q_ref)
+        assert np.array_equal(host(out["scales"]).view(np.uint32), s_ref.view(np.uint32))
+    if R == 1:
+        # without the h export the same codes come out
+        out2 = gpu.daq_quantize_ln(dev(x), R, None, None, 1, 1e-6, want_h=False)
+        assert np.array_equal(host(out2["q"]), host(out["q"]))
+
+
+def test_layernorm_modulate_daq_full_size(gpu, orc):
+    M, K = 16384, 1152
+    say("ln+daq full size", M, K)
+    x = workload.activations(M, K, "ln-full", sigma=3.0)
+    g = workload.rng("ln-full")
+    sc = (g.standard_normal((M // 256, K)) * 0.3).astype(np.float16)
+    sh = (g.standard_normal((M // 256, K)) * 0.5).astype(np.float16)
+    out = gpu.daq_quantize_ln(dev(x), 1, dev(sh), dev(sc), 256, 1e-6, want_h=True)
+    h = host(out["h"])
+    ref = orc.layernorm_modulate(x, sh, sc, 256, 1e-6)
+    assert (np.abs(h.astype(np.float64) - ref.astype(np.float64)) <= _ln_tolerance(x, sh, sc, 256, ref)).all()
+    assert (h.view(np.uint16) != ref.view(np.uint16)).mean() < 0.01
+    q_ref, s_ref = orc.daq(h, 1, nthreads=16)
+    assert np.array_equal(host(out["q"]), q_ref)
+    assert np.array_equal(host(out["scales"]).view(np.uint32), s_ref.view(np.uint32))
+
+
 # ------------------------------------------------------------------ plan runner
 
 def test_plan_runner_small_mixed_plan(gpu, orc):

@@ -285,3 +285,39 @@ def test_golden_hand_worked_daq_rows(orc):
         alpha, xs, codes = float(parts[0]), [float(v) for v in parts[1].split()], [int(v) for v in parts[2].split()]
         q, s = orc.daq(f16([xs]), 1)
         assert s[0] == np.float32(alpha) and q.tolist() == [codes]
+
+
+# ------------------------------------------------------------------ LayerNorm + adaptive modulation (Step 3, Section 6)
+
+def test_layernorm_modulate_against_torch_and_closed_forms(orc):
+    import torch
+    g = workload.rng("ln-pin")
+    x = workload.activations(12, 96, "ln-pin", sigma=3.0)
+    # the library routine, in float64 (a different implementation of the same definition)
+    want = torch.nn.functional.layer_norm(torch.from_numpy(x.astype(np.float64)), (96,), eps=1e-6).numpy()
+    got = orc.layernorm_modulate(x, eps=1e-6).astype(np.float64)
+    assert np.abs(got - want).max() <= 2.0 ** -11 * np.abs(want).max() + 1e-12      # one rounding to binary16
+    assert np.array_equal(orc.layernorm_modulate(x, eps=1e-6), want.astype(np.float32).astype(np.float16))
+    # closed form: a row of +a, -a has mean 0 and variance a^2 -> +-1 / sqrt(1 + eps / a^2)
+    row = np.tile(np.array([2.0, -2.0], np.float16), 8)[None]
+    h = orc.layernorm_modulate(row, eps=0.0)
+    assert np.array_equal(h, np.tile(np.array([1.0, -1.0], np.float16), 8)[None])
+    # modulation: h = n (1 + scale) + shift with per-image vectors; scale = 1, shift = 3 on the +-1 row gives 5 and 1
+    sc = np.ones((1, 16), np.float16)
+    sh = np.full((1, 16), 3.0, np.float16)
+    h = orc.layernorm_modulate(np.repeat(row, 4, 0), shift=sh, scale=sc, rows_per_mod=4, eps=0.0)
+    assert np.array_equal(h, np.repeat(np.tile(np.array([5.0, 1.0], np.float16), 8)[None], 4, 0))
+    # invariances with eps = 0: adding a constant to a row or scaling it by a power of two changes nothing
+    x2 = np.round(g.standard_normal((5, 64)) * 4) / 4
+    a = orc.layernorm_modulate(x2.astype(np.float16), eps=0.0)
+    assert np.array_equal(a, orc.layernorm_modulate((x2 + 8.0).astype(np.float16), eps=0.0))
+    assert np.array_equal(a, orc.layernorm_modulate((x2 * 4.0).astype(np.float16), eps=0.0))
+    # rows of different images take different modulation rows (a swapped index would show)
+    sc = (g.standard_normal((3, 64)) * 0.3).astype(np.float16)
+    sh = (g.standard_normal((3, 64)) * 0.5).astype(np.float16)
+    x3 = workload.activations(6, 64, "ln-mod")
+    h = orc.layernorm_modulate(x3, shift=sh, scale=sc, rows_per_mod=2).astype(np.float64)
+    n = torch.nn.functional.layer_norm(torch.from_numpy(x3.astype(np.float64)), (64,), eps=1e-6).numpy()
+    for m in range(6):
+        ref = n[m] * (1.0 + sc[m // 2].astype(np.float64)) + sh[m // 2].astype(np.float64)
+        assert np.abs(h[m] - ref).max() <= 2.0 ** -10 * np.abs(ref).max()
