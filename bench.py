@@ -351,8 +351,10 @@ def main():
                                         vp, vp, vp, vp, ctypes.c_size_t, vp]
 
         def ln_fused():
-            lib.daq_quantize_ln(vp(xr.data_ptr()), M, hid, 1, vp(shift.data_ptr()), vp(scale.data_ptr()), tokens, 1e-6, None,
-                                vp(qb.data_ptr()), vp(sb.data_ptr()), None, 0, sptr)
+            rc = lib.daq_quantize_ln(vp(xr.data_ptr()), M, hid, 1, vp(shift.data_ptr()), vp(scale.data_ptr()), tokens, 1e-6, None,
+                                     vp(qb.data_ptr()), vp(sb.data_ptr()), None, 0, vp(torch.cuda.current_stream().cuda_stream))
+            if rc != 0:
+                raise RuntimeError("daq_quantize_ln failed: %d" % rc)
 
         def ln_separate():
             h = torch.nn.functional.layer_norm(xr, (hid,), eps=1e-6)
