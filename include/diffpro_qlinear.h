@@ -203,6 +203,53 @@ int qgemm_w4a8_g(const void *q, const void *a_scales, int64_t M, int64_t K, int6
                  void *y, void *acc, void *stream);
 
 /* ------------------------------------------------------------------------
+ * The rest of the plan space (Step 2 and Algorithm 1: W3/W4/W6/W8 with group
+ * scales and zero points; Step 3, eq. (4): activation scales per sample,
+ * timestep AND channel group).
+ *
+ * daq_quantize_cg: eq. (4) with tau = the absolute maximum of each sub-block of
+ * R rows (a sample's tokens) x act_group consecutive channels:
+ *   alpha[r, c] = amax / 127 (1 if zero),  q = clamp(rne(x / alpha[m/R, k/act_group]), -127, 127)
+ *   scales (device) [M/R, K/act_group] fp32.  act_group: a multiple of 8 that
+ *   divides K, K/act_group <= 1024 (QL_ERR_UNSUPPORTED / QL_ERR_SHAPE); x 16-byte
+ *   aligned; workspace daq_cg_workspace_bytes().
+ *
+ * qlinear_grouped: the layer with group-wise weight scales for any width:
+ *   w_storage = 4: w is packed 4-bit [N,K/2] as in qlinear_w4a8
+ *   w_storage = 8: w is int8 [N,K] holding codes of ANY width up to 8 bits:
+ *                  W3 in [-4,3], W6 in [-32,31] (ql_unpack_bits_host expands their
+ *                  dense storage), W8 in [-127,127], or codes with a zero point
+ *                  stored as code - zero (ql_zero_point_fold_host; widths <= 7)
+ *   P[m,g,n] = sum_{k in group g} q[m,k] * w[n,k]
+ *   act_group = 0:      q, alpha = daq_quantize(x, R);
+ *                       f = fma(float(P), w_scale[n,g], f);  y = fp16(fma(f, alpha[m/R], bias[n]))
+ *   act_group = group:  q, alpha = daq_quantize_cg(x, R, group);  c = w_scale[n,g] * alpha[m/R, g] (fp32)
+ *                       f = fma(float(P), c, f);  y = fp16(f + bias[n])
+ *   (other act_group values: QL_ERR_UNSUPPORTED.)  w_scale fp16 [N,K/group];
+ *   dbg->a_scales is [M/R] or [M/R, K/group]; dbg->acc [M, K/group, N].
+ * The pipelined kernel takes K % 128 == 0, K/group <= 40 and, with channel-group
+ * activation scales, R % 128 == 0; other shapes run on the generic kernel.
+ * Workspace: qlinear_grouped_workspace_bytes().
+ *
+ * Host helpers: ql_pack_bits_host / ql_unpack_bits_host store b-bit two's-
+ * complement codes (2 <= b <= 7) densely, a row's codes concatenated LSB first
+ * (K * b must be a multiple of 8); ql_zero_point_fold_host turns codes and
+ * per-group zero points (both as ql_gptq_quantize_host returns them) into
+ * int8 differences code - zero (QL_ERR_UNSUPPORTED if one does not fit int8).
+ * ---------------------------------------------------------------------- */
+size_t daq_cg_workspace_bytes(int64_t M, int64_t K, int64_t R, int64_t act_group);
+int daq_quantize_cg(const void *x, int64_t M, int64_t K, int64_t R, int64_t act_group,
+                    void *q, void *scales, void *workspace, size_t workspace_bytes, void *stream);
+size_t qlinear_grouped_workspace_bytes(int64_t M, int64_t K, int64_t R, int64_t act_group);
+int qlinear_grouped(const void *x, int64_t M, int64_t K, int64_t R, int64_t act_group,
+                    const void *w, int32_t w_storage, const void *w_scale, int64_t group,
+                    const void *bias, int64_t N, void *y, const ql_debug *dbg,
+                    void *workspace, size_t workspace_bytes, void *stream);
+int ql_pack_bits_host(const int8_t *codes, int64_t N, int64_t K, int32_t bits, uint8_t *packed);
+int ql_unpack_bits_host(const uint8_t *packed, int64_t N, int64_t K, int32_t bits, int8_t *codes);
+int ql_zero_point_fold_host(const int8_t *codes, const int32_t *zeros, int64_t N, int64_t K, int64_t group, int8_t *out);
+
+/* ------------------------------------------------------------------------
  * Block glue folded into the layer's epilogue (Section 6 counts the residual
  * additions in the latency; Step 3 keeps them in higher precision; the MLP's
  * activation sits between its two quantized linears).  With u the layer's

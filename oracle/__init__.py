@@ -337,3 +337,73 @@ def layernorm_modulate(x, shift=None, scale=None, rows_per_mod=1, eps=1e-6):
     g = 1.0 if scale is None else 1.0 + np.repeat(np.asarray(scale, np.float16).astype(np.float64), rows_per_mod, axis=0)
     b = 0.0 if shift is None else np.repeat(np.asarray(shift, np.float16).astype(np.float64), rows_per_mod, axis=0)
     return (n * g + b).astype(np.float32).astype(np.float16)
+
+
+def gemm_i8g(q, w, group, nthreads=1):
+    """int8 codes q [M,K] x int8 weight codes w [N,K] (any width up to 8 bits held as int8) -> int32 [M, K/group, N]."""
+    q = _c(q, np.int8)
+    w = _c(w, np.int8)
+    M, K = q.shape
+    N = w.shape[0]
+    assert w.shape[1] == K and K % group == 0
+    P = np.empty((M, K // group, N), np.int32)
+    rc = lib().orc_gemm_i8g(_p(q), _p(w), ctypes.c_int64(M), ctypes.c_int64(N), ctypes.c_int64(K), ctypes.c_int64(group), _p(P),
+                            ctypes.c_int(nthreads))
+    if rc:
+        raise ValueError("orc_gemm_i8g rc=%d" % rc)
+    return P
+
+
+def epilogue_cg(P, alpha, R, s_w, bias):
+    """Dequantization with activation scales per (scale block, channel group): alpha float32 [M/R, G], s_w float16 [N, G]."""
+    P = _c(P, np.int32)
+    M, G, N = P.shape
+    alpha = _c(alpha, np.float32)
+    sw = _f16bits(s_w)
+    assert alpha.shape == (M // R, G) and sw.shape == (N, G)
+    b = None if bias is None else _f16bits(bias)
+    y = np.empty((M, N), np.uint16)
+    rc = lib().orc_epilogue_cg(_p(P), _p(alpha), ctypes.c_int64(R), _p(sw), _p(b), ctypes.c_int64(M), ctypes.c_int64(N),
+                               ctypes.c_int64(G), _p(y))
+    if rc:
+        raise ValueError("orc_epilogue_cg rc=%d" % rc)
+    return y.view(np.float16)
+
+
+def daq_cg(x, R, group, nthreads=1):
+    """Eq. (4) of Step 3 with its channel groups: one scale per block of R rows (a sample's tokens) AND group of `group`
+    consecutive channels, tau = that sub-block's absolute maximum.  Written as the definition: every (row block, channel
+    group) sub-matrix goes through daq() as one scale block.  Returns (codes int8 [M,K], alpha float32 [M/R, K/group])."""
+    x = np.ascontiguousarray(x)
+    M, K = x.shape
+    assert M % R == 0 and K % group == 0
+    q = np.empty((M, K), np.int8)
+    alpha = np.empty((M // R, K // group), np.float32)
+    for b in range(M // R):
+        for g in range(K // group):
+            sub = np.ascontiguousarray(x[b * R:(b + 1) * R, g * group:(g + 1) * group])
+            qs, s = daq(sub, R, nthreads=nthreads)
+            q[b * R:(b + 1) * R, g * group:(g + 1) * group] = qs
+            alpha[b, g] = s[0]
+    return q, alpha
+
+
+def pack_bits(codes, bits):
+    """Dense storage of b-bit two's-complement codes (b = 3 or 6: Algorithm 1's W3, Section 2.4's W6): the codes of a row
+    are concatenated LSB first into a little-endian bit stream.  codes int8 [N,K] with K*bits % 8 == 0 -> uint8 [N, K*bits/8]."""
+    codes = np.asarray(codes, np.int8)
+    N, K = codes.shape
+    assert (K * bits) % 8 == 0
+    lo, hi = -(1 << (bits - 1)), (1 << (bits - 1)) - 1
+    assert codes.min() >= lo and codes.max() <= hi
+    u = (codes.astype(np.int64) & ((1 << bits) - 1))
+    bitsarr = ((u[:, :, None] >> np.arange(bits)) & 1).reshape(N, K * bits).astype(np.uint8)
+    return np.packbits(bitsarr, axis=1, bitorder="little")
+
+
+def unpack_bits(packed, bits, K):
+    packed = np.asarray(packed, np.uint8)
+    N = packed.shape[0]
+    b = np.unpackbits(packed, axis=1, bitorder="little")[:, :K * bits].reshape(N, K, bits).astype(np.int64)
+    u = (b << np.arange(bits)).sum(axis=2)
+    return np.where(u >= (1 << (bits - 1)), u - (1 << bits), u).astype(np.int8)

@@ -320,6 +320,57 @@ int orc_gemm_w4g(const int8_t *q, const uint8_t *w4, int64_t M, int64_t N, int64
 }
 
 /* ------------------------------------------------------------------ */
+/* Integer codes of any width up to 8 bits held as int8 (W3, W6, W8 with */
+/* group scales, or asymmetric codes stored as code - zero; Step 2,      */
+/* Algorithm 1), with weight groups of `group` consecutive k:            */
+/*   P[m,g,n] = sum_{k in group g} q[m,k] * w[n,k],  P is [M, K/group, N] */
+/* ------------------------------------------------------------------ */
+int orc_gemm_i8g(const int8_t *q, const int8_t *w, int64_t M, int64_t N, int64_t K, int64_t group,
+                 int32_t *P, int nthreads)
+{
+    if (M < 0 || N < 0 || K < 0 || group <= 0 || (K % group) != 0) return 1;
+    int64_t G = K / group;
+    (void)nthreads;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) num_threads(nthreads > 1 ? nthreads : 1)
+#endif
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n)
+            for (int64_t g = 0; g < G; ++g) {
+                int32_t s = 0;
+                for (int64_t k = group * g; k < group * g + group; ++k) s += (int32_t)q[m * K + k] * (int32_t)w[n * K + k];
+                P[(m * G + g) * N + n] = s;
+            }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Dequantization when the activation scales are per scale block AND    */
+/* per channel group (Step 3, eq. (4): one scale per sample, timestep   */
+/* and group of channels), the channel groups being the weight groups:  */
+/*   c = s_w[n,g] * alpha[m/R, g]                (binary32 product)      */
+/*   f = fma(float(P[m,g,n]), c, f)              g ascending, f from 0   */
+/*   y = f16(f + bias[n])                        (f without a bias)      */
+/* alpha is [M/R, G] binary32, s_w [N, G] binary16.                      */
+/* ------------------------------------------------------------------ */
+int orc_epilogue_cg(const int32_t *P, const float *alpha, int64_t R, const uint16_t *s_w,
+                    const uint16_t *bias, int64_t M, int64_t N, int64_t G, uint16_t *y)
+{
+    if (M < 0 || N < 0 || G < 0 || R <= 0 || (M % R) != 0) return 1;
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            float f = 0.0f;
+            for (int64_t g = 0; g < G; ++g) {
+                float c = orc_half_to_float(s_w[n * G + g]) * alpha[(m / R) * G + g];
+                f = fmaf((float)P[(m * G + g) * N + n], c, f);
+            }
+            float u = bias ? f + orc_half_to_float(bias[n]) : f;
+            y[m * N + n] = orc_float_to_half(u);
+        }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
 /* Dequantization epilogues (Section 6: "dequantization"; Step 5:      */
 /* per-output-channel weight scales).  binary32, one rounding per      */
 /* operation, in the order written; fma = fused multiply-add.          */

@@ -23,7 +23,9 @@ EXPORTS = ("ql_status_string", "ql_last_device_error", "ql_version", "daq_worksp
            "ql_plan_workspace_bytes", "qlinear_plan_run", "ql_set_gemm_variant", "ql_num_gemm_variants",
            "ql_gemm_variant_name", "ql_probe_mfma_int8", "daq_quantize_robust", "qlinear_plan_run_robust", "ql_time_bin",
            "qlinear_w4a8_g", "qgemm_w4a8_g", "qlinear_w8a8_fused", "qlinear_w4a8_fused", "qlinear_f16", "ql_repack_w4_pairs_host", "qlinear_plan_run_ex", "qlinear_w8a8_noalloc", "qlinear_noalloc_max_bytes",
-           "ql_schedule_topk", "ql_plan_greedy", "ql_gptq_quantize_host", "daq_quantize_ln")
+           "ql_schedule_topk", "ql_plan_greedy", "ql_gptq_quantize_host", "daq_quantize_ln",
+           "daq_cg_workspace_bytes", "daq_quantize_cg", "qlinear_grouped_workspace_bytes", "qlinear_grouped", "ql_pack_bits_host",
+           "ql_unpack_bits_host", "ql_zero_point_fold_host")
 
 
 class QlError(RuntimeError):
@@ -200,6 +202,79 @@ def daq_quantize_ln(x, R=1, shift=None, scale=None, rows_per_mod=1, eps=1e-6, wa
     rc = fn(_ptr(x), M, K, R, _ptr(shift), _ptr(scale), rows_per_mod, eps, _ptr(out.get("h")), _ptr(out.get("q")),
             _ptr(out.get("scales")), _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream))
     _check(rc, "daq_quantize_ln")
+    return out
+
+
+def daq_quantize_cg(x, R, act_group, stream=None):
+    """Eq. (4) with channel groups: x fp16 [M,K] -> (q int8 [M,K], alpha fp32 [M/R, K/act_group])."""
+    import torch
+    _need(x, torch.float16, name="x")
+    M, K = x.shape
+    q = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    sc = torch.empty((M // R, K // act_group), dtype=torch.float32, device=x.device)
+    L = lib()
+    L.daq_cg_workspace_bytes.restype = _sz
+    L.daq_cg_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64]
+    ws = workspace(L.daq_cg_workspace_bytes(M, K, R, act_group), x.device)
+    L.daq_quantize_cg.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _sz, _vp]
+    _check(L.daq_quantize_cg(_ptr(x), M, K, R, act_group, _ptr(q), _ptr(sc), _ptr(ws), ws.numel(), _stream(stream)), "daq_quantize_cg")
+    return q, sc
+
+
+def qlinear_grouped(x, R, w, w_scale, group, bias=None, act_group=0, storage=8, debug=False, y=None, stream=None):
+    """Group-scaled layer for any weight width: storage 8 = int8 codes [N,K], 4 = packed nibbles [N,K/2];
+    act_group = 0 (row scales) or group (one activation scale per scale block and channel group)."""
+    import torch
+    _need(x, torch.float16, name="x")
+    M, K = x.shape
+    N = w.shape[0]
+    G = K // group
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    L = lib()
+    L.qlinear_grouped_workspace_bytes.restype = _sz
+    L.qlinear_grouped_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64]
+    ws = workspace(L.qlinear_grouped_workspace_bytes(M, K, R, act_group), x.device)
+    out, dbg = {"y": y}, None
+    if debug:
+        out["q"] = torch.empty((M, K), dtype=torch.int8, device=x.device)
+        out["s_a"] = torch.empty((M // R,) if act_group == 0 else (M // R, G), dtype=torch.float32, device=x.device)
+        out["P"] = torch.empty((M, G, N), dtype=torch.int32, device=x.device)
+        dbg = ctypes.pointer(ql_debug(out["q"].data_ptr(), out["s_a"].data_ptr(), out["P"].data_ptr()))
+    L.qlinear_grouped.argtypes = [_vp, _i64, _i64, _i64, _i64, _vp, ctypes.c_int32, _vp, _i64, _vp, _i64, _vp, ctypes.POINTER(ql_debug),
+                                  _vp, _sz, _vp]
+    rc = L.qlinear_grouped(_ptr(x), M, K, R, act_group, _ptr(w), storage, _ptr(w_scale), group, _ptr(bias), N, _ptr(y), dbg, _ptr(ws),
+                           ws.numel(), _stream(stream))
+    _check(rc, "qlinear_grouped")
+    return out if debug else y
+
+
+def pack_bits_host(codes, bits):
+    import numpy as np
+    codes = np.ascontiguousarray(codes, dtype=np.int8)
+    N, K = codes.shape
+    out = np.empty((N, K * bits // 8), np.uint8)
+    _check(lib().ql_pack_bits_host(codes.ctypes.data_as(_vp), _i64(N), _i64(K), ctypes.c_int32(bits), out.ctypes.data_as(_vp)), "ql_pack_bits_host")
+    return out
+
+
+def unpack_bits_host(packed, bits, K):
+    import numpy as np
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    N = packed.shape[0]
+    out = np.empty((N, K), np.int8)
+    _check(lib().ql_unpack_bits_host(packed.ctypes.data_as(_vp), _i64(N), _i64(K), ctypes.c_int32(bits), out.ctypes.data_as(_vp)), "ql_unpack_bits_host")
+    return out
+
+
+def zero_point_fold_host(codes, zeros, group):
+    import numpy as np
+    codes = np.ascontiguousarray(codes, dtype=np.int8)
+    zeros = np.ascontiguousarray(zeros, dtype=np.int32)
+    N, K = codes.shape
+    out = np.empty((N, K), np.int8)
+    _check(lib().ql_zero_point_fold_host(codes.ctypes.data_as(_vp), zeros.ctypes.data_as(_vp), _i64(N), _i64(K), _i64(group),
+                                         out.ctypes.data_as(_vp)), "ql_zero_point_fold_host")
     return out
 
 

@@ -337,6 +337,170 @@ int daq_quantize_robust(const void *x, int64_t M, int64_t K, int64_t R, const ql
     return daq_any(x, M, K, R, params, q, scales, workspace, workspace_bytes, stream);
 }
 
+// ---- plan-space generality: channel-group activation scales, int8-held codes of any width with group scales ----------
+static int check_act_group(int64_t K, int64_t ag)
+{
+    if (ag < 8 || ag % 8 != 0) return QL_ERR_UNSUPPORTED;
+    if (K % 8 != 0 || K % ag != 0 || K / ag > 1024) return QL_ERR_SHAPE;
+    return QL_OK;
+}
+
+size_t daq_cg_workspace_bytes(int64_t M, int64_t K, int64_t R, int64_t act_group)
+{
+    if (M < 1 || K < 1 || R < 1 || M % R != 0 || act_group < 1 || K % act_group != 0) return 0;
+    return align_up((size_t)(M / R) * (size_t)(K / act_group) * 4, 256);
+}
+
+int daq_quantize_cg(const void *x, int64_t M, int64_t K, int64_t R, int64_t act_group, void *q, void *scales, void *workspace,
+                    size_t workspace_bytes, void *stream)
+{
+    if (!x || !q || !scales) return QL_ERR_NULL;
+    if (misaligned(x, 16) || misaligned(q, 8) || misaligned(scales, 4)) return QL_ERR_ALIGN;
+    int rc = check_shape(M, K, R, 1);
+    if (rc) return rc;
+    rc = check_act_group(K, act_group);
+    if (rc) return rc;
+    rc = check_workspace(workspace, workspace_bytes, daq_cg_workspace_bytes(M, K, R, act_group));
+    if (rc) return rc;
+    ql::DaqArgs d{};
+    d.x = x;
+    d.q = static_cast<int8_t *>(q);
+    d.scales = static_cast<float *>(scales);
+    d.blockmax = static_cast<unsigned *>(workspace);
+    d.M = (int)M;
+    d.K = (int)K;
+    d.R = (int)R;
+    return device_status(ql::launch_daq_cg(d, (int)act_group, static_cast<hipStream_t>(stream)));
+}
+
+size_t qlinear_grouped_workspace_bytes(int64_t M, int64_t K, int64_t R, int64_t act_group)
+{
+    if (M < 1 || K < 1 || R < 1 || M % R != 0) return 0;
+    if (act_group <= 0) return layer_ws(M, K, R).total;
+    if (K % act_group != 0) return 0;
+    return align_up((size_t)(M * K), 256) + 2 * daq_cg_workspace_bytes(M, K, R, act_group);
+}
+
+int qlinear_grouped(const void *x, int64_t M, int64_t K, int64_t R, int64_t act_group, const void *w, int32_t w_storage,
+                    const void *w_scale, int64_t group, const void *bias, int64_t N, void *y, const ql_debug *dbg,
+                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (w_storage != 4 && w_storage != 8) return QL_ERR_UNSUPPORTED;
+    int rc = check_layer_ptrs(x, w, w_scale, bias, y, dbg, 4);
+    if (rc) return rc;
+    rc = check_shape(M, K, R, N);
+    if (rc) return rc;
+    rc = check_group(K, group);
+    if (rc) return rc;
+    if (act_group != 0 && act_group != group) return QL_ERR_UNSUPPORTED;   // the channel groups are the weight groups
+    if (act_group != 0) {
+        rc = check_act_group(K, act_group);
+        if (rc) return rc;
+        if (misaligned(x, 16)) return QL_ERR_ALIGN;
+    }
+    if (dbg && dbg->acc && M > ELEMS_MAX / N / (K / group)) return QL_ERR_SHAPE;
+    rc = check_workspace(workspace, workspace_bytes, qlinear_grouped_workspace_bytes(M, K, R, act_group));
+    if (rc) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    unsigned char *base = static_cast<unsigned char *>(workspace);
+    ql::GemmArgs g{};
+    if (act_group == 0) {
+        const LayerWs lw = layer_ws(M, K, R);
+        ql::DaqArgs d{};
+        d.x = x;
+        d.q = (dbg && dbg->q) ? static_cast<int8_t *>(dbg->q) : reinterpret_cast<int8_t *>(base + lw.q_off);
+        d.scales = (dbg && dbg->a_scales) ? static_cast<float *>(dbg->a_scales) : reinterpret_cast<float *>(base + lw.s_off);
+        d.blockmax = R > 1 ? reinterpret_cast<unsigned *>(base + lw.bm_off) : nullptr;
+        d.partmax = R > 1 ? reinterpret_cast<unsigned *>(base + lw.bm_off + align_up((size_t)(M / R) * 4, 256)) : nullptr;
+        d.M = (int)M;
+        d.K = (int)K;
+        d.R = (int)R;
+        rc = device_status(ql::launch_daq(d, s));
+        if (rc) return rc;
+        g.q = d.q;
+        g.s_a = d.scales;
+    } else {
+        const size_t cgb = daq_cg_workspace_bytes(M, K, R, act_group);
+        ql::DaqArgs d{};
+        d.x = x;
+        d.q = (dbg && dbg->q) ? static_cast<int8_t *>(dbg->q) : reinterpret_cast<int8_t *>(base);
+        d.scales = (dbg && dbg->a_scales) ? static_cast<float *>(dbg->a_scales) : reinterpret_cast<float *>(base + align_up((size_t)(M * K), 256));
+        d.blockmax = reinterpret_cast<unsigned *>(base + align_up((size_t)(M * K), 256) + cgb);
+        d.M = (int)M;
+        d.K = (int)K;
+        d.R = (int)R;
+        rc = device_status(ql::launch_daq_cg(d, (int)act_group, s));
+        if (rc) return rc;
+        g.q = d.q;
+        g.s_ag = d.scales;
+    }
+    g.w = w;
+    g.s_w = w_scale;
+    g.bias = bias;
+    g.y = y;
+    g.acc_out = dbg ? static_cast<int32_t *>(dbg->acc) : nullptr;
+    g.M = (int)M;
+    g.N = (int)N;
+    g.K = (int)K;
+    g.R = (int)R;
+    g.w_bits = w_storage;
+    g.w_grouped = w_storage == 8 ? 1 : 0;
+    g.group = (int)group;
+    return device_status(ql::launch_qgemm(g, g_gemm_variant.load(), s));
+}
+
+int ql_pack_bits_host(const int8_t *codes, int64_t N, int64_t K, int32_t bits, uint8_t *packed)
+{
+    if (!codes || !packed) return QL_ERR_NULL;
+    if (bits < 2 || bits > 7) return QL_ERR_UNSUPPORTED;
+    if (N < 1 || K < 1 || (K * bits) % 8 != 0) return QL_ERR_SHAPE;
+    const int64_t row_bytes = K * bits / 8;
+    const int lo = -(1 << (bits - 1)), hi = (1 << (bits - 1)) - 1;
+    for (int64_t n = 0; n < N; ++n) {
+        uint8_t *dst = packed + n * row_bytes;
+        for (int64_t i = 0; i < row_bytes; ++i) dst[i] = 0;
+        for (int64_t k = 0; k < K; ++k) {
+            const int c = codes[n * K + k];
+            if (c < lo || c > hi) return QL_ERR_SHAPE;
+            const unsigned u = (unsigned)c & ((1u << bits) - 1);
+            for (int b = 0; b < bits; ++b)
+                if (u >> b & 1) dst[(k * bits + b) / 8] |= (uint8_t)(1u << ((k * bits + b) % 8));
+        }
+    }
+    return QL_OK;
+}
+
+int ql_unpack_bits_host(const uint8_t *packed, int64_t N, int64_t K, int32_t bits, int8_t *codes)
+{
+    if (!codes || !packed) return QL_ERR_NULL;
+    if (bits < 2 || bits > 7) return QL_ERR_UNSUPPORTED;
+    if (N < 1 || K < 1 || (K * bits) % 8 != 0) return QL_ERR_SHAPE;
+    const int64_t row_bytes = K * bits / 8;
+    for (int64_t n = 0; n < N; ++n) {
+        const uint8_t *src = packed + n * row_bytes;
+        for (int64_t k = 0; k < K; ++k) {
+            int u = 0;
+            for (int b = 0; b < bits; ++b) u |= ((src[(k * bits + b) / 8] >> ((k * bits + b) % 8)) & 1) << b;
+            codes[n * K + k] = (int8_t)(u >= (1 << (bits - 1)) ? u - (1 << bits) : u);
+        }
+    }
+    return QL_OK;
+}
+
+int ql_zero_point_fold_host(const int8_t *codes, const int32_t *zeros, int64_t N, int64_t K, int64_t group, int8_t *out)
+{
+    if (!codes || !zeros || !out) return QL_ERR_NULL;
+    if (N < 1 || K < 1 || group < 1 || K % group != 0) return QL_ERR_SHAPE;
+    const int64_t G = K / group;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            const int d = (int)codes[n * K + k] - zeros[n * G + k / group];
+            if (d < -127 || d > 127) return QL_ERR_UNSUPPORTED;   // 8-bit codes with a zero point do not fit
+            out[n * K + k] = (int8_t)d;
+        }
+    return QL_OK;
+}
+
 int daq_quantize_ln(const void *x, int64_t M, int64_t K, int64_t R, const void *shift, const void *scale, int64_t rows_per_mod,
                     float eps, void *h, void *q, void *scales, void *workspace, size_t workspace_bytes, void *stream)
 {

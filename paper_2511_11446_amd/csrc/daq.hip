@@ -231,6 +231,59 @@ static void run_rows(const DaqArgs &a, int mode, hipStream_t s)
     else hipLaunchKernelGGL(daq_rows_loop<8>, grid, dim3(256), 0, s, a, mode);
 }
 
+// ---- eq. (4) with its channel groups: one scale per block of R rows AND group of `cg` consecutive channels ------------
+// pass 1: every wavefront takes one row; a lane's 16-byte piece lies inside one channel group (cg % 8 == 0), its maximum
+// goes to the wavefront's LDS table and from there, once per row and group, to blockmax[block][group]
+constexpr int DAQ_CG_MAX_GROUPS = 1024;
+__global__ __launch_bounds__(256) void daq_cg_absmax(DaqArgs a, int cg)
+{
+    __shared__ unsigned gmax[4][DAQ_CG_MAX_GROUPS];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row = blockIdx.x * 4 + wave;
+    const int G = a.K / cg, nch = a.K >> 3;
+    for (int g = lane; g < G; g += 64) gmax[wave][g] = 0;
+    __builtin_amdgcn_wave_barrier();
+    if (row < a.M) {
+        const uint4 *xr = reinterpret_cast<const uint4 *>(static_cast<const unsigned short *>(a.x) + (size_t)row * a.K);
+        for (int c = lane; c < nch; c += 64) {
+            const uint4 v = xr[c];
+            unsigned m = absmax_word(absmax_word(absmax_word(absmax_word(0, v.x), v.y), v.z), v.w);
+            m = (m & 0xffffu) > (m >> 16) ? (m & 0xffffu) : (m >> 16);
+            atomicMax(&gmax[wave][(c * 8) / cg], m);
+        }
+    }
+    __syncthreads();
+    if (row < a.M)
+        for (int g = lane; g < G; g += 64) publish_block_max(a.blockmax + (size_t)(row / a.R) * G + g, gmax[wave][g]);
+}
+
+// pass 2: codes from the block maxima; the row is read again (the first read normally left it in L2)
+__global__ __launch_bounds__(256) void daq_cg_quant(DaqArgs a, int cg)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= a.M) return;
+    const int G = a.K / cg, nch = a.K >> 3;
+    const unsigned *bm = a.blockmax + (size_t)(row / a.R) * G;
+    const uint4 *xr = reinterpret_cast<const uint4 *>(static_cast<const unsigned short *>(a.x) + (size_t)row * a.K);
+    uint2 *qr = reinterpret_cast<uint2 *>(a.q + (size_t)row * a.K);
+    for (int c = lane; c < nch; c += 64) {
+        const float alpha = alpha_from_bits(bm[(c * 8) / cg]);
+        qr[c] = daq_piece(xr[c], alpha, 1.0f / alpha);
+    }
+    if (row % a.R == 0)
+        for (int g = lane; g < G; g += 64) a.scales[(size_t)(row / a.R) * G + g] = alpha_from_bits(bm[g]);
+}
+
+hipError_t launch_daq_cg(const DaqArgs &a, int cg, hipStream_t stream)
+{
+    const int n = (a.M / a.R) * (a.K / cg);
+    hipLaunchKernelGGL(fill_u32, dim3((n + 255) / 256), dim3(256), 0, stream, a.blockmax, n, 0u);
+    hipLaunchKernelGGL(daq_cg_absmax, dim3((a.M + 3) / 4), dim3(256), 0, stream, a, cg);
+    hipLaunchKernelGGL(daq_cg_quant, dim3((a.M + 3) / 4), dim3(256), 0, stream, a, cg);
+    return hipGetLastError();
+}
+
 hipError_t launch_daq(const DaqArgs &a, hipStream_t stream)
 {
     if (a.R == 1) {

@@ -808,10 +808,10 @@ __global__ __launch_bounds__(256) void qgemm_naive(GemmArgs a)
         static_cast<_Float16 *>(a.y)[(size_t)m * a.N + n] = has_glue(a) ? glue_one(a, u16, m, n, a.gate ? m / a.gate_rows : 0) : (_Float16)u16;
         return;
     }
-    const float sa = a.s_a[m / a.R];
+    const float sa = a.s_ag ? 1.0f : a.s_a[m / a.R];
     const int8_t *q = a.q + (size_t)m * K;
     float u;
-    if (a.w_bits == 8) {
+    if (a.w_bits == 8 && !a.w_grouped) {
         const int8_t *w = static_cast<const int8_t *>(a.w) + (size_t)n * K;
         int s = 0;
         for (int k = 0; k < K; ++k) s += (int)q[k] * (int)w[k];
@@ -820,20 +820,28 @@ __global__ __launch_bounds__(256) void qgemm_naive(GemmArgs a)
         const float sw = static_cast<const float *>(a.s_w)[n];
         u = bias ? __builtin_fmaf(t, sw, b) : t * sw;
     } else {
-        const unsigned char *w = static_cast<const unsigned char *>(a.w) + (size_t)n * (K / 2);
+        // group-wise weight scales: packed nibbles, or int8 codes of any width up to 8 bits
+        const unsigned char *w = static_cast<const unsigned char *>(a.w) + (size_t)n * (a.w_grouped ? K : K / 2);
         const int gsz = a.group;
         const int G = K / gsz;
         float f = 0.0f;
         for (int g = 0; g < G; ++g) {
             int s = 0;
             for (int k = gsz * g; k < gsz * g + gsz; ++k) {
-                const unsigned byte = w[4 * (k / 8) + (k % 4)];
-                int v = (k % 8) >= 4 ? (int)(byte >> 4) : (int)(byte & 0xf);
-                v = v >= 8 ? v - 16 : v;
+                int v;
+                if (a.w_grouped) {
+                    v = (int)(int8_t)w[k];
+                } else {
+                    const unsigned byte = w[4 * (k / 8) + (k % 4)];
+                    v = (k % 8) >= 4 ? (int)(byte >> 4) : (int)(byte & 0xf);
+                    v = v >= 8 ? v - 16 : v;
+                }
                 s += (int)q[k] * v;
             }
             if (a.acc_out) a.acc_out[((size_t)m * G + g) * a.N + n] = s;
-            f = __builtin_fmaf((float)s, half_to_float_dev(static_cast<const unsigned short *>(a.s_w)[(size_t)n * G + g]), f);
+            float c = half_to_float_dev(static_cast<const unsigned short *>(a.s_w)[(size_t)n * G + g]);
+            if (a.s_ag) c = c * a.s_ag[(size_t)(m / a.R) * G + g];
+            f = __builtin_fmaf((float)s, c, f);
         }
         u = bias ? __builtin_fmaf(f, sa, b) : f * sa;
     }
@@ -1018,6 +1026,13 @@ static bool is_any_group(int v) { return __builtin_strstr(VARIANTS[v].name, "any
 
 hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream)
 {
+    if (a.w_grouped || a.s_ag) {
+        // plan-space generality: the pipelined grouped kernel where it takes the shape, else one thread per element
+        if (variant < NUM_VARIANTS && qgemm_w4_takes(a) && !(a.act != 0 || a.residual != nullptr || a.gate != nullptr))
+            return launch_qgemm_w4(a, stream);
+        hipLaunchKernelGGL(qgemm_naive, dim3((a.M + 3) / 4, (a.N + 63) / 64), dim3(256), 0, stream, a);
+        return hipGetLastError();
+    }
     // MFMA tiles need 16-byte loads along K and a whole number of K steps
     const bool fast = (a.K % 64 == 0) && ((uintptr_t)a.q % 16 == 0) && ((uintptr_t)a.w % 16 == 0) &&
                       (a.w_bits != 4 || (a.K % 128 == 0 && a.group % 32 == 0));

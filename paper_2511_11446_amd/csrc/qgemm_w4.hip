@@ -25,14 +25,16 @@ namespace ql {
 typedef __attribute__((address_space(3))) void lds_void_w4;
 
 // WGM_: wavefront rows of the workgroup (2: 128x128 tile, 4: 256x128); SA_/SB_: ring depths of the two operands
-template <int WGM_, int SA_, int SB_>
+// B8_: the weight operand is int8 codes (128 bytes per row and K step) instead of packed nibbles
+template <int WGM_, int SA_, int SB_, bool B8_ = false>
 struct TileW4 {
+    static constexpr bool B8 = B8_;
     static constexpr int TM = 2, TN = 2, WGM = WGM_, WGN = 2;
     static constexpr int NW = WGM * WGN, NT = NW * 64;
     static constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
     static constexpr int SA = SA_, SB = SB_;
     // 1024-byte DMA groups per K step: 8 activation rows x 128 B, 16 packed weight rows x 64 B
-    static constexpr int A_GROUPS = BM / 8, B_GROUPS = BN / 16;
+    static constexpr int A_GROUPS = BM / 8, B_GROUPS = B8 ? BN / 8 : BN / 16;
     static constexpr int NA = A_GROUPS / NW, NB = B_GROUPS / NW;
     static constexpr int A_BYTES = A_GROUPS * 1024, B_BYTES = B_GROUPS * 1024;
     static constexpr int B_RING = SA * A_BYTES;
@@ -83,6 +85,8 @@ __global__ __launch_bounds__(T::NT, 2) void qgemm_w4(GemmArgs a, int tiles_m, in
 {
     constexpr int TM = T::TM, TN = T::TN, BM = T::BM, BN = T::BN, NT = T::NT, NW = T::NW;
     constexpr int SA = T::SA, SB = T::SB, NA = T::NA, NB = T::NB;
+    constexpr bool B8 = T::B8;
+    typedef typename std::conditional<B8, v4i, v2i>::type bfrag_t;   // a lane's weight fragment as read from LDS
     extern __shared__ __align__(1024) unsigned char smem[];
 
     // Workgroup ids go round-robin over the XCDs; each XCD owns per_xcd consecutive logical tiles and its resident
@@ -125,9 +129,15 @@ __global__ __launch_bounds__(T::NT, 2) void qgemm_w4(GemmArgs a, int tiles_m, in
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
-            const int row = 16 * (wave + i * NW) + (lane >> 2);
-            const int c = (lane & 3) ^ ((row >> 2) & 3);
-            goffB[i] = (unsigned)(min(n0 + row, N - 1) * (K / 2) + 16 * c);
+            if (B8) {
+                const int row = 8 * (wave + i * NW) + (lane >> 3);
+                const int c = (lane & 7) ^ ((row >> 1) & 7);
+                goffB[i] = (unsigned)(min(n0 + row, N - 1) * K + 16 * c);
+            } else {
+                const int row = 16 * (wave + i * NW) + (lane >> 2);
+                const int c = (lane & 3) ^ ((row >> 2) & 3);
+                goffB[i] = (unsigned)(min(n0 + row, N - 1) * (K / 2) + 16 * c);
+            }
         }
     };
     set_goff();
@@ -135,7 +145,7 @@ __global__ __launch_bounds__(T::NT, 2) void qgemm_w4(GemmArgs a, int tiles_m, in
         dma16_w4(a.q, M * K, smem + slot * T::A_BYTES + (wave + i * NW) * 1024, goffA[i], kt * 128);
     };
     auto issue_b = [&](int kt, int slot, int i) {
-        dma16_w4(a.w, N * (K / 2), smem + T::B_RING + slot * T::B_BYTES + (wave + i * NW) * 1024, goffB[i], kt * 64);
+        dma16_w4(a.w, B8 ? N * K : N * (K / 2), smem + T::B_RING + slot * T::B_BYTES + (wave + i * NW) * 1024, goffB[i], kt * (B8 ? 128 : 64));
     };
     // Refill window j = the loads issued after the hand-over barrier of K step j, into the slots that step used:
     // weight tile of step j+SB and activation tile of step j+SA; the operand with the shallower ring goes first.
@@ -163,14 +173,19 @@ __global__ __launch_bounds__(T::NT, 2) void qgemm_w4(GemmArgs a, int tiles_m, in
     const int frag_row = lane & 31, frag_half = lane >> 5;
     const int key = (lane >> 1) & 7, key4 = (lane >> 2) & 3;
     const int a_off = (wm * TM * 32 + frag_row) * 128;
-    const int b_off = T::B_RING + (wn * TN * 32 + frag_row) * 64 + frag_half * 8;
-    auto read_frags = [&](int sl_a, int sl_b, int quarter, v4i(&af)[TM], v2i(&bp)[TN]) {
+    const int b_off = B8 ? T::B_RING + (wn * TN * 32 + frag_row) * 128 : T::B_RING + (wn * TN * 32 + frag_row) * 64 + frag_half * 8;
+    auto read_frags = [&](int sl_a, int sl_b, int quarter, v4i(&af)[TM], bfrag_t(&bp)[TN]) {
         const unsigned char *st = smem + sl_a * T::A_BYTES + a_off + ((2 * quarter + frag_half) ^ key) * 16;
-        const unsigned char *stb = smem + sl_b * T::B_BYTES + b_off + (quarter ^ key4) * 16;
+        const unsigned char *stb = smem + sl_b * T::B_BYTES + b_off + (B8 ? ((2 * quarter + frag_half) ^ key) : (quarter ^ key4)) * 16;
 #pragma unroll
         for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const v4i *>(st + i * 32 * 128);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bp[j] = *reinterpret_cast<const v2i *>(stb + j * 32 * 64);
+        for (int j = 0; j < TN; ++j) bp[j] = *reinterpret_cast<const bfrag_t *>(stb + j * 32 * (B8 ? 128 : 64));
+    };
+    // the MFMA operand of a fragment: int8 codes as they are, nibbles as value * 16
+    auto operand = [&](const bfrag_t &p) {
+        if constexpr (B8) return p;
+        else return unpack_w4(p);
     };
 
     v16i acc[TM][TN];
@@ -185,7 +200,7 @@ __global__ __launch_bounds__(T::NT, 2) void qgemm_w4(GemmArgs a, int tiles_m, in
             if (EXPORT) {
                 const int m = m0 + wm * TM * 32 + i * 32 + 8 * (r / 4) + 4 * frag_half + (r % 4);
                 const int n = n0 + wn * TN * 32 + j * 32 + frag_row;
-                if (grp_acc >= 0 && m < M && n < N) a.acc_out[(unsigned)((m * G + grp_acc) * N + n)] = acc[i][j][r] >> 4;
+                if (grp_acc >= 0 && m < M && n < N) a.acc_out[(unsigned)((m * G + grp_acc) * N + n)] = B8 ? acc[i][j][r] : acc[i][j][r] >> 4;
             }
             fsum[i][j][r] = __builtin_fmaf((float)acc[i][j][r], s16[j], fsum[i][j][r]);
         }
@@ -210,14 +225,14 @@ __global__ __launch_bounds__(T::NT, 2) void qgemm_w4(GemmArgs a, int tiles_m, in
         }
     };
     // first MFMA of a quarter (the reads of the next quarter's fragments follow it)
-    auto quarter_head = [&](auto restart_tag, const v4i(&af)[TM], const v2i(&bp)[TN], v4i &bf0) {
-        bf0 = unpack_w4(bp[0]);
+    auto quarter_head = [&](auto restart_tag, const v4i(&af)[TM], const bfrag_t(&bp)[TN], v4i &bf0) {
+        bf0 = operand(bp[0]);
         mma_one(restart_tag, af, bf0, 0);
     };
     // MFMAs 1..3 of a quarter, one DMA instruction of refill window `win` behind each (loads i0, i0+1, i0+2)
-    auto quarter_tail = [&](auto restart_tag, const v4i(&af)[TM], const v2i(&bp)[TN], const v4i &bf0, bool on, int win, int slot_a,
+    auto quarter_tail = [&](auto restart_tag, const v4i(&af)[TM], const bfrag_t(&bp)[TN], const v4i &bf0, bool on, int win, int slot_a,
                             int slot_b, int i0) {
-        const v4i bf1 = unpack_w4(bp[1]);
+        const v4i bf1 = operand(bp[1]);
 #pragma unroll
         for (int idx = 1; idx < 4; ++idx) {
             mma_one(restart_tag, af, idx < 2 ? bf0 : bf1, idx);
@@ -232,7 +247,14 @@ __global__ __launch_bounds__(T::NT, 2) void qgemm_w4(GemmArgs a, int tiles_m, in
     auto open_group = [&]() {
         grp_acc = grp_next;
 #pragma unroll
-        for (int j = 0; j < TN; ++j) s16[j] = half_to_float_dev(sScale[(wn * TN * 32 + j * 32 + frag_row) * G + grp_next]) * 0.0625f;
+        for (int j = 0; j < TN; ++j) s16[j] = half_to_float_dev(sScale[(wn * TN * 32 + j * 32 + frag_row) * G + grp_next]) * (B8 ? 1.0f : 0.0625f);
+        if (a.s_ag) {
+            // one activation scale per scale block and channel group (eq. (4)): the tile lies inside one scale block
+            // (the dispatcher sends R % BM == 0 only), so the scale is wavefront-uniform and joins the group's weight scale
+            const float alpha_g = a.s_ag[(size_t)(m0 / a.R) * G + grp_next];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) s16[j] *= alpha_g;
+        }
         ++grp_next;
     };
 
@@ -240,7 +262,7 @@ __global__ __launch_bounds__(T::NT, 2) void qgemm_w4(GemmArgs a, int tiles_m, in
     issue_step0();
     for (;;) {   // one pass per tile
         // ---- per tile: row scale of one tile row per thread, bias of this lane's columns, group scales of the tile's columns
-        sa_pre = tid < BM ? a.s_a[min(m0 + tid, M - 1) / a.R] : 1.0f;
+        sa_pre = (tid < BM && !a.s_ag) ? a.s_a[min(m0 + tid, M - 1) / a.R] : 1.0f;
         {
             const unsigned short *bias_h = static_cast<const unsigned short *>(a.bias);
 #pragma unroll
@@ -281,7 +303,7 @@ __global__ __launch_bounds__(T::NT, 2) void qgemm_w4(GemmArgs a, int tiles_m, in
             }
         }
         v4i af0[TM], af1[TM], bfa;
-        v2i bp0[TN], bp1[TN];
+        bfrag_t bp0[TN], bp1[TN];
         if (nk >= T::SMAX) wait_vm(std::integral_constant<int, T::WAIT_START>{});
         else wait_vm(std::integral_constant<int, 0>{});
         __syncthreads();   // K step 0 and the group scales are in LDS
@@ -292,7 +314,7 @@ __global__ __launch_bounds__(T::NT, 2) void qgemm_w4(GemmArgs a, int tiles_m, in
             const bool refill = kt > 0;   // refill window kt-1 is still being issued during quarter 0
             // One quarter of the K step on fragments (afc, bpc): first MFMA, [hand-over], the reads of the next quarter's
             // fragments, then the other three MFMAs with the DMA instructions li = i0, i0+1, i0+2 of window `win` behind them.
-            auto quarter = [&](auto restart_tag, const v4i(&afc)[TM], const v2i(&bpc)[TN], auto next_read, auto hand_tag, bool on, int win,
+            auto quarter = [&](auto restart_tag, const v4i(&afc)[TM], const bfrag_t(&bpc)[TN], auto next_read, auto hand_tag, bool on, int win,
                                int slot_a, int slot_b, int i0) {
                 quarter_head(restart_tag, afc, bpc, bfa);
                 __builtin_amdgcn_sched_barrier(0);
@@ -310,7 +332,7 @@ __global__ __launch_bounds__(T::NT, 2) void qgemm_w4(GemmArgs a, int tiles_m, in
                 __builtin_amdgcn_sched_barrier(0);
             };
             // the same with the group bookkeeping: a quarter that opens a weight group folds the finished one first
-            auto step = [&](auto first_tag, const v4i(&afc)[TM], const v2i(&bpc)[TN], auto next_read, auto hand_tag, bool on, int win,
+            auto step = [&](auto first_tag, const v4i(&afc)[TM], const bfrag_t(&bpc)[TN], auto next_read, auto hand_tag, bool on, int win,
                             int slot_a, int slot_b, int i0) {
                 if constexpr (QGF == 4) {
                     quarter(first_tag, afc, bpc, next_read, hand_tag, on, win, slot_a, slot_b, i0);
@@ -448,6 +470,10 @@ static hipError_t run_w4(const GemmArgs &a, hipStream_t s)
 
 bool qgemm_w4_takes(const GemmArgs &a)
 {
+    if (a.s_ag && (a.R % 128 != 0 || a.M % a.R != 0)) return false;   // channel-group activation scales: tiles inside one scale block
+    if (a.w_grouped)
+        return a.w_bits == 8 && a.K % 128 == 0 && a.group % 32 == 0 && a.K % a.group == 0 && a.K / a.group <= TileW4<2, 3, 2>::MAX_GROUPS &&
+               (uintptr_t)a.q % 16 == 0 && (uintptr_t)a.w % 16 == 0;
     return a.w_bits == 4 && a.K % 128 == 0 && a.group % 32 == 0 && a.K % a.group == 0 && a.K / a.group <= TileW4<2, 3, 2>::MAX_GROUPS &&
            (uintptr_t)a.q % 16 == 0 && (uintptr_t)a.w % 16 == 0;
 }
@@ -456,6 +482,12 @@ hipError_t launch_qgemm_w4(const GemmArgs &a, hipStream_t stream)
 {
     using T = TileW4<2, 3, 2>;
     const bool glue = a.act != 0 || a.residual != nullptr || a.gate != nullptr;
+    if (a.w_grouped) {
+        // int8 codes with group scales: one workgroup per CU (the weight ring is twice as large)
+        using T8 = TileW4<2, 3, 2, true>;
+        if (glue) return hipErrorInvalidValue;
+        return a.acc_out ? run_w4<T8, 0, true, false>(a, stream) : run_w4<T8, 0, false, false>(a, stream);
+    }
     if (a.acc_out) return run_w4<T, 0, true, true>(a, stream);   // verification: group partial sums exported
     if (glue) return a.group == 128 ? run_w4<T, 4, false, true>(a, stream) : run_w4<T, 0, false, true>(a, stream);
     return a.group == 128 ? run_w4<T, 4, false, false>(a, stream) : run_w4<T, 0, false, false>(a, stream);

@@ -41,6 +41,8 @@ inline size_t daq_parts_per_block(int64_t K, int64_t R)
 }
 
 hipError_t launch_daq(const DaqArgs &a, hipStream_t stream);
+// eq. (4) with channel groups: scales [M/R, K/cg], blockmax workspace of the same count; K % 8 == 0, cg % 8 == 0, K/cg <= 1024
+hipError_t launch_daq_cg(const DaqArgs &a, int cg, hipStream_t stream);
 // eq. (4) with tau = a percentile of the magnitudes and a selectable code width
 hipError_t launch_daq_robust(const DaqArgs &a, hipStream_t stream);
 
@@ -74,6 +76,11 @@ struct GemmArgs {
     const void *residual; // fp16 [M,N] r, or null (0)
     const void *gate;     // fp16 [M/gate_rows, N] g, or null (1)
     int gate_rows;        // rows sharing one gate row
+    // plan-space generality (Step 2, Algorithm 1, eq. (4)'s channel groups); all zero = none
+    int w_grouped;        // 1: w holds int8 codes [N,K] (W3, W6, W8 or asymmetric codes stored as code - zero) with fp16 scales
+                          //    [N,K/group] like the 4-bit layers (w_bits stays 8)
+    const float *s_ag;    // activation scales per (scale block, channel group) [M/R, K/group] instead of s_a; the channel
+                          //    groups are the weight groups
 };
 
 int num_gemm_variants();

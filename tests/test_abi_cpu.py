@@ -262,3 +262,37 @@ def test_layernorm_daq_argument_checks():
     assert fn(A, 8, 64, 1, A, None, 3, 1e-6, None, A, A, None, 0, None) == 2                # M % rows_per_mod
     assert fn(A, 8, 64, 4, None, None, 1, 1e-6, None, A, A, None, 0, None) == 1             # R > 1 needs h
     assert fn(A, 8, 64, 4, None, None, 1, 1e-6, A, A, A, None, 0, None) in (0, 5, 6)        # shape ok: workspace or device next
+
+
+def test_plan_space_host_helpers_and_argument_checks(orc):
+    g = np.random.default_rng(5)
+    for b in (3, 6, 2, 7):
+        c = g.integers(-(1 << (b - 1)), 1 << (b - 1), (4, 64), dtype=np.int8)
+        p = ql.pack_bits_host(c, b)
+        assert np.array_equal(p, orc.pack_bits(c, b))                 # the same documented storage on both sides
+        assert np.array_equal(ql.unpack_bits_host(p, b, 64), c)
+    with pytest.raises(ql.QlError):
+        ql.pack_bits_host(np.full((1, 8), 4, np.int8), 3)            # 4 is not a 3-bit code
+    with pytest.raises(ql.QlError):
+        ql.pack_bits_host(np.zeros((1, 5), np.int8), 3)              # 15 bits: not whole bytes
+    # asymmetric codes and zero points (as the GPTQ packer returns them: both shifted by 2^(b-1)) -> code - zero
+    codes = np.array([[-8, 7, 0, -3]], np.int8)
+    zeros = np.array([[-2, 5]], np.int32)
+    assert ql.zero_point_fold_host(codes, zeros, 2).tolist() == [[-6, 9, -5, -8]]
+    with pytest.raises(ql.QlError):
+        ql.zero_point_fold_host(np.array([[-128, 127]], np.int8), np.array([[100]], np.int32), 2)
+    L = ql.lib()
+    A = ctypes.c_void_p(0x10000)
+    L.daq_quantize_cg.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
+                                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    assert L.daq_quantize_cg(A, 8, 64, 4, 12, A, A, A, 1 << 20, None) == 4       # not a multiple of 8
+    assert L.daq_quantize_cg(A, 8, 64, 4, 24, A, A, A, 1 << 20, None) == 2       # does not divide K
+    assert L.daq_quantize_cg(A, 8, 64, 4, 16, A, A, None, 0, None) == 5
+    L.qlinear_grouped.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
+                                  ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
+                                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    call = lambda ag, st, grp: L.qlinear_grouped(A, 128, 256, 128, ag, A, st, A, grp, None, 64, A, None, A, 1 << 24, None)
+    assert call(0, 5, 128) == 4          # storage must be 4 or 8
+    assert call(64, 8, 128) == 4         # channel groups must be the weight groups
+    assert call(0, 8, 48) == 4           # group not a multiple of 32
+    assert call(0, 8, 96) == 2           # group does not divide K

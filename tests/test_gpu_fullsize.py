@@ -101,6 +101,30 @@ def test_w4a8_m16384_every_element(gpu, orc, name, K, N, group):
     free()
 
 
+@pytest.mark.parametrize("storage,rng_", [(4, (-8, 7)), (8, (-32, 31))])
+def test_channel_group_scales_m16384_every_element(gpu, orc, storage, rng_):
+    """Eq. (4) as printed (one activation scale per image and channel group of 128) through the pipelined grouped kernel at
+    full size: proj shape, 64 images of 256 tokens."""
+    M, K, N, R, group = M_FULL, 1152, 1152, 256, 128
+    say("full channel-group scales", M, K, N, "storage", storage)
+    x = workload.activations(M, K, "fullcg", storage, sigma=1.1)
+    codes = workload.rng("fullcg-w", storage).integers(rng_[0], rng_[1] + 1, (N, K), dtype=np.int8)
+    s_w = workload.w4_scales_group(N, K, group, "fullcg")
+    bias = workload.bias(N, "fullcg")
+    q_ref, a_ref = orc.daq_cg(x, R, group, nthreads=16)
+    P_ref = orc.gemm_i8g(q_ref, codes, group, nthreads=16)
+    y_ref = orc.epilogue_cg(P_ref, a_ref, R, s_w, bias)
+    wd = dev(gpu.ql_pack_w4_host(codes)) if storage == 4 else dev(codes)
+    y = gpu.qlinear_grouped(dev(x), R, wd, dev(s_w), group, dev(bias), act_group=group, storage=storage)
+    assert y_mismatches(host(y), y_ref) == 0
+    out = gpu.qlinear_grouped(dev(x), R, wd, dev(s_w), group, dev(bias), act_group=group, storage=storage, debug=True)
+    assert np.array_equal(host(out["q"]), q_ref)
+    assert np.array_equal(host(out["s_a"]).view(np.uint32), a_ref.view(np.uint32))
+    assert np.array_equal(host(out["P"]), P_ref)
+    del out
+    free()
+
+
 @pytest.mark.parametrize("K", [1152, 4608])
 def test_daq_per_tensor_m16384(gpu, orc, K):
     """One scale for the whole tensor: R*K is 19 M / 75 M values, so the block maximum comes from more than 256 partial

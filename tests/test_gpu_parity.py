@@ -912,6 +912,81 @@ def test_layernorm_modulate_daq_full_size(gpu, orc):
     assert np.array_equal(host(out["scales"]).view(np.uint32), s_ref.view(np.uint32))
 
 
+# ------------------------------------------------------------------ rest of the plan space
+
+@pytest.mark.parametrize("M,K,R,cg", [(512, 1152, 256, 128), (64, 4608, 16, 8), (37, 64, 37, 16), (96, 384, 1, 32), (1024, 1152, 1024, 288)])
+def test_daq_channel_groups(gpu, orc, M, K, R, cg):
+    say("daq channel groups", M, K, R, cg)
+    x = workload.activations(M, K, "daqcg", R, cg, sigma=1.3)
+    q_ref, a_ref = orc.daq_cg(x, R, cg, nthreads=8)
+    q, a = gpu.daq_quantize_cg(dev(x), R, cg)
+    assert np.array_equal(host(a).view(np.uint32), a_ref.view(np.uint32))
+    assert np.array_equal(host(q), q_ref)
+
+
+GROUPED_CASES = [
+    # M, K, N, R, group, code range, storage, act_group
+    (384, 1152, 256, 1, 64, (-4, 3), 8, 0),        # W3 held as int8
+    (300, 1152, 200, 1, 128, (-32, 31), 8, 0),     # W6, ragged tile edges
+    (256, 1152, 384, 64, 288, (-127, 127), 8, 0),  # W8 with group scales, per-sample row scales
+    (256, 1152, 128, 1, 32, (-15, 15), 8, 0),      # 4-bit codes minus their zero points
+    (512, 1152, 256, 256, 128, (-8, 7), 4, 128),   # packed 4-bit, one activation scale per image and channel group
+    (512, 1152, 256, 128, 128, (-32, 31), 8, 128), # W6 with channel-group activation scales
+    (256, 4608, 128, 128, 128, (-4, 3), 8, 128),   # long K: 36 groups
+    (40, 96, 24, 4, 32, (-4, 3), 8, 32),           # neither K nor R fit the pipelined kernel: generic kernel
+    (128, 4608, 64, 128, 64, (-8, 7), 4, 64),      # 72 groups: more than the kernel's scale table holds
+]
+
+
+@pytest.mark.parametrize("M,K,N,R,group,rng_,storage,act_group", GROUPED_CASES)
+def test_grouped_layer(gpu, orc, M, K, N, R, group, rng_, storage, act_group):
+    say("grouped", M, K, N, R, group, rng_, storage, act_group)
+    g = workload.rng("grouped", M, K, N, group, storage, act_group)
+    x = workload.activations(M, K, "grouped", group, storage, sigma=0.8)
+    codes = g.integers(rng_[0], rng_[1] + 1, (N, K), dtype=np.int8)
+    s_w = workload.w4_scales_group(N, K, group, "grouped")
+    bias = workload.bias(N, "grouped")
+    if act_group:
+        q_ref, a_ref = orc.daq_cg(x, R, act_group, nthreads=8)
+    else:
+        q_ref, a_ref = orc.daq(x, R, nthreads=8)
+    P_ref = orc.gemm_i8g(q_ref, codes, group, nthreads=16)
+    y_ref = orc.epilogue_cg(P_ref, a_ref, R, s_w, bias) if act_group else orc.epilogue_w4(P_ref, a_ref, R, s_w, bias)
+    wd = dev(gpu.ql_pack_w4_host(codes)) if storage == 4 else dev(codes)
+    out = gpu.qlinear_grouped(dev(x), R, wd, dev(s_w), group, dev(bias), act_group=act_group, storage=storage, debug=True)
+    assert np.array_equal(host(out["q"]), q_ref)
+    assert np.array_equal(host(out["s_a"]).view(np.uint32), a_ref.view(np.uint32))
+    assert np.array_equal(host(out["P"]), P_ref)
+    assert assert_y_close(host(out["y"]), y_ref) == 0
+    y2 = gpu.qlinear_grouped(dev(x), R, wd, dev(s_w), group, dev(bias), act_group=act_group, storage=storage)
+    assert np.array_equal(host(y2).view(np.uint16), host(out["y"]).view(np.uint16))
+
+
+def test_gptq_asymmetric_codes_through_the_grouped_layer(gpu, orc):
+    """Step 2 end to end on synthetic data: GPTQ with per-group scale and zero point (host), zero points folded into the
+    codes, dense 3-bit storage and back, then the grouped layer against the oracle on the same codes."""
+    say("gptq asym -> grouped layer")
+    M, K, N, group = 256, 256, 64, 64
+    g = workload.rng("gptq-e2e")
+    W = (g.standard_normal((N, K)) * 0.05 + 0.01).astype(np.float32)
+    X = workload.activations(512, K, "gptq-e2e-x").astype(np.float64)
+    codes, scales, zeros = gpu.gptq_quantize_host(W, X.T @ X, 3, group, symmetric=False, scale_fp16=True)
+    diff = gpu.zero_point_fold_host(codes, zeros, group)
+    assert diff.min() >= -7 and diff.max() <= 7
+    stored = gpu.pack_bits_host(codes, 3)
+    assert np.array_equal(gpu.unpack_bits_host(stored, 3, K), codes)
+    x = workload.activations(M, K, "gptq-e2e-a")
+    s_w = scales.astype(np.float16)
+    q_ref, a_ref = orc.daq(x, 1)
+    y_ref = orc.epilogue_w4(orc.gemm_i8g(q_ref, diff, group), a_ref, 1, s_w, None)
+    y = gpu.qlinear_grouped(dev(x), 1, dev(diff), dev(s_w), group, None)
+    assert assert_y_close(host(y), y_ref) == 0
+    # and the quantized layer does approximate the float layer it came from
+    yf = x.astype(np.float64) @ W.astype(np.float64).T
+    rel = np.linalg.norm(host(y).astype(np.float64) - yf) / np.linalg.norm(yf)
+    assert rel < 0.6, rel      # 3-bit weights: a gross-scale sanity bound, not parity
+
+
 # ------------------------------------------------------------------ plan runner
 
 def test_plan_runner_small_mixed_plan(gpu, orc):

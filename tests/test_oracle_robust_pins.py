@@ -321,3 +321,83 @@ def test_layernorm_modulate_against_torch_and_closed_forms(orc):
     for m in range(6):
         ref = n[m] * (1.0 + sc[m // 2].astype(np.float64)) + sh[m // 2].astype(np.float64)
         assert np.abs(h[m] - ref).max() <= 2.0 ** -10 * np.abs(ref).max()
+
+
+# ------------------------------------------------------------------ rest of the plan space: int8-held codes with group scales,
+# channel-group activation scales (eq. (4)), dense 3/6-bit storage
+
+def test_gemm_i8g_against_numpy_block_sums_and_the_plain_gemm(orc):
+    g = workload.rng("i8g")
+    M, N, K = 9, 7, 96
+    q = g.integers(-127, 128, (M, K), dtype=np.int8)
+    for lo, hi, group in ((-4, 4, 32), (-32, 32, 48), (-127, 128, 96), (-15, 16, 8)):
+        w = g.integers(lo, hi, (N, K), dtype=np.int8)
+        P = orc.gemm_i8g(q, w, group, nthreads=2)
+        want = np.einsum("mgk,ngk->mgn", q.astype(np.int64).reshape(M, K // group, group), w.astype(np.int64).reshape(N, K // group, group))
+        assert np.array_equal(P, want)
+        assert np.array_equal(P.sum(axis=1), orc.gemm_i8(q, w))
+    # one-hot weight: P[m, g, n] = q[m, k0] exactly in the group that holds k0
+    w = np.zeros((N, K), np.int8)
+    w[3, 50] = 1
+    P = orc.gemm_i8g(q, w, 32)
+    assert np.array_equal(P[:, 1, 3], q[:, 50].astype(np.int32)) and P.sum() == q[:, 50].astype(np.int64).sum()
+
+
+def test_daq_cg_is_eq4_per_sample_and_channel_group(orc):
+    # every (row block, channel group) sub-block with its own power-of-two maximum: the scales are exactly 2^j / 127
+    M, K, R, cg = 8, 32, 4, 8
+    x = np.zeros((M, K), np.float16)
+    want = np.zeros((M // R, K // cg), np.float32)
+    g = workload.rng("daqcg")
+    for b in range(M // R):
+        for c in range(K // cg):
+            amax = 2.0 ** (b * 4 + c - 3)
+            blk = g.uniform(-1, 1, (R, cg)) * amax * 0.9
+            blk[g.integers(R), g.integers(cg)] = -amax
+            x[b * R:(b + 1) * R, c * cg:(c + 1) * cg] = blk.astype(np.float16)
+            want[b, c] = np.float32(amax) / np.float32(127.0)
+    q, alpha = orc.daq_cg(x, R, cg)
+    assert np.array_equal(alpha, want)
+    assert (np.abs(q).reshape(M // R, R, K // cg, cg).max(axis=(1, 3)) == 127).all()
+    # one channel group spanning all of K is the row-block DAQ; error bound of the quantizer per element
+    q1, a1 = orc.daq_cg(x, R, K)
+    q2, a2 = orc.daq(x, R)
+    assert np.array_equal(q1, q2) and np.array_equal(a1[:, 0], a2)
+    err = np.abs(x.astype(np.float64) - q * np.repeat(np.repeat(alpha.astype(np.float64), R, 0), cg, 1))
+    assert (err <= np.repeat(np.repeat(alpha.astype(np.float64), R, 0), cg, 1) * (0.5 + 2.0 ** -16)).all()
+
+
+def test_epilogue_cg_special_cases(orc):
+    g = workload.rng("epicg")
+    M, G, N, R = 8, 3, 5, 4
+    P = g.integers(-50000, 50000, (M, G, N), dtype=np.int32)
+    s_w = g.uniform(1e-2, 1e-1, (N, G)).astype(np.float16)
+    bias = (g.standard_normal(N) * 0.02).astype(np.float16)
+    # the same power-of-two scale for all groups of a block: multiplying by it commutes with every rounding, so the
+    # result equals the row-scale epilogue with that scale (given a zero bias, where fma(f, a, 0) = f a)
+    a_blk = np.array([2.0 ** -7, 2.0 ** -4], np.float32)
+    alpha = np.repeat(a_blk[:, None], G, 1)
+    assert np.array_equal(orc.epilogue_cg(P, alpha, R, s_w, None), orc.epilogue_w4(P, a_blk, R, s_w, None))
+    # hand-worked: one group, P = 3, s_w = 0.5, alpha = 0.25, bias = 1  ->  3 * 0.125 + 1 = 1.375
+    y = orc.epilogue_cg(np.array([[[3]]], np.int32), np.array([[0.25]], np.float32), 1, np.array([[0.5]], np.float16), np.array([1.0], np.float16))
+    assert y[0, 0] == np.float16(1.375)
+    # general case against float64 (every product and the short sum are far inside float64): within one fp16 step
+    alpha = g.uniform(1e-3, 1e-1, (M // R, G)).astype(np.float32)
+    y = orc.epilogue_cg(P, alpha, R, s_w, bias).astype(np.float64)
+    ref = np.einsum("mgn,ng,mg->mn", P.astype(np.float64), s_w.astype(np.float64), np.repeat(alpha.astype(np.float64), R, 0)) + bias.astype(np.float64)
+    assert (np.abs(y - ref) <= 2.0 ** -10 * np.abs(ref) + 1e-6).all()
+    # a group's scale belongs to its own group: permuting alpha's groups changes the result
+    assert not np.array_equal(orc.epilogue_cg(P, alpha[:, ::-1].copy(), R, s_w, bias), orc.epilogue_cg(P, alpha, R, s_w, bias))
+
+
+def test_dense_bit_storage(orc):
+    # literal: 3-bit codes 1, -1 (111b), 2, -4 (100b), 0, 3, -2 (110b), 1 -> bit stream LSB first
+    codes = np.array([[1, -1, 2, -4, 0, 3, -2, 1]], np.int8)
+    bits = "100" + "111" + "010" + "001" + "000" + "110" + "011" + "100"      # each code written LSB first
+    want = np.array([[int(bits[i:i + 8][::-1], 2) for i in range(0, 24, 8)]], np.uint8)
+    assert np.array_equal(orc.pack_bits(codes, 3), want)
+    g = workload.rng("bits")
+    for b in (3, 6, 5):
+        c = g.integers(-(1 << (b - 1)), 1 << (b - 1), (5, 64), dtype=np.int8)
+        p = orc.pack_bits(c, b)
+        assert p.shape == (5, 64 * b // 8) and np.array_equal(orc.unpack_bits(p, b, 64), c)
