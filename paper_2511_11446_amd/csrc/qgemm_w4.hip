@@ -78,7 +78,15 @@ __device__ __forceinline__ v4i unpack_w4(v2i p)
                (int)(((unsigned)p[1] << 4) & 0xf0f0f0f0u), (int)((unsigned)p[1] & 0xf0f0f0f0u)};
 }
 
-// QGF: 32-wide K slices per weight group when fixed at compile time (4 = groups of 128), 0 = read from the arguments
+template <class F, int... S>
+__device__ __forceinline__ void unrolled_steps(F &f, int kt, std::integer_sequence<int, S...>)
+{
+    (f(std::integral_constant<int, S>{}, kt + S), ...);
+}
+
+// QGF: 32-wide K slices per weight group when fixed at compile time (4 = groups of 128, 9 = groups of 288, ...): the quarters
+// that open a group are then known statically over a period of lcm(QGF, 4) slices, which is unrolled; 0 = read from the
+// arguments, one uniform branch per MFMA
 // EXPORT: the int32 group partial sums are also written to a.acc_out
 template <class T, int QGF, bool EXPORT, bool GLUE>
 __global__ __launch_bounds__(T::NT, 2) void qgemm_w4(GemmArgs a, int tiles_m, int tiles_n, int nblk_padded, int group_m)
@@ -258,6 +266,11 @@ __global__ __launch_bounds__(T::NT, 2) void qgemm_w4(GemmArgs a, int tiles_m, in
         ++grp_next;
     };
 
+    // does quarter Q of step S of the period open a weight group?  (compile-time group sizes only)
+    auto restart_at = [](auto s_tag, auto q_tag) {
+        return std::integral_constant<bool, QGF != 0 && (4 * decltype(s_tag)::value + decltype(q_tag)::value) % (QGF ? QGF : 1) == 0>{};
+    };
+
     float sa_pre, bj[TN];
     issue_step0();
     for (;;) {   // one pass per tile
@@ -309,7 +322,8 @@ __global__ __launch_bounds__(T::NT, 2) void qgemm_w4(GemmArgs a, int tiles_m, in
         __syncthreads();   // K step 0 and the group scales are in LDS
         read_frags(0, 0, 0, af0, bp0);
         int sa = 0, sb = 0, pa = SA - 1, pb = SB - 1;   // ring slots of K step kt and of step kt-1
-        for (int kt = 0; kt < nk; ++kt) {
+        // one K step; with a compile-time group size s_tag is the step's index inside the period of the restart pattern
+        auto kstep = [&](auto s_tag, int kt) {
             const int na = sa + 1 == SA ? 0 : sa + 1, nb = sb + 1 == SB ? 0 : sb + 1;
             const bool refill = kt > 0;   // refill window kt-1 is still being issued during quarter 0
             // One quarter of the K step on fragments (afc, bpc): first MFMA, [hand-over], the reads of the next quarter's
@@ -334,7 +348,7 @@ __global__ __launch_bounds__(T::NT, 2) void qgemm_w4(GemmArgs a, int tiles_m, in
             // the same with the group bookkeeping: a quarter that opens a weight group folds the finished one first
             auto step = [&](auto first_tag, const v4i(&afc)[TM], const bfrag_t(&bpc)[TN], auto next_read, auto hand_tag, bool on, int win,
                             int slot_a, int slot_b, int i0) {
-                if constexpr (QGF == 4) {
+                if constexpr (QGF > 0) {
                     quarter(first_tag, afc, bpc, next_read, hand_tag, on, win, slot_a, slot_b, i0);
                     if (decltype(first_tag)::value) open_group();
                 } else {
@@ -345,18 +359,25 @@ __global__ __launch_bounds__(T::NT, 2) void qgemm_w4(GemmArgs a, int tiles_m, in
                 }
             };
             // quarter 0 (fragments 0) while reading quarter 1; the rest of refill window kt-1 goes behind its MFMAs
-            step(std::true_type{}, af0, bp0, [&]() { read_frags(sa, sb, 1, af1, bp1); }, std::false_type{}, refill, kt - 1, pa, pb, 3);
+            step(restart_at(s_tag, std::integral_constant<int, 0>{}), af0, bp0, [&]() { read_frags(sa, sb, 1, af1, bp1); }, std::false_type{}, refill, kt - 1, pa, pb, 3);
             // quarter 1 while reading quarter 2
-            step(std::false_type{}, af1, bp1, [&]() { read_frags(sa, sb, 2, af0, bp0); }, std::false_type{}, refill, kt - 1, pa, pb, 6);
+            step(restart_at(s_tag, std::integral_constant<int, 1>{}), af1, bp1, [&]() { read_frags(sa, sb, 2, af0, bp0); }, std::false_type{}, refill, kt - 1, pa, pb, 6);
             // quarter 2 while reading quarter 3
-            step(std::false_type{}, af0, bp0, [&]() { read_frags(sa, sb, 3, af1, bp1); }, std::false_type{}, false, 0, 0, 0, NA + NB);
+            step(restart_at(s_tag, std::integral_constant<int, 2>{}), af0, bp0, [&]() { read_frags(sa, sb, 3, af1, bp1); }, std::false_type{}, false, 0, 0, 0, NA + NB);
             // quarter 3: after its first MFMA the hand-over (step kt+1 must be in LDS; after the barrier this step's slots
             // can be refilled), the first fragments of step kt+1, and the first three loads of refill window kt
-            step(std::false_type{}, af1, bp1, [&]() { if (kt + 1 < nk) read_frags(na, nb, 0, af0, bp0); }, std::true_type{}, true, kt, sa, sb, 0);
+            step(restart_at(s_tag, std::integral_constant<int, 3>{}), af1, bp1, [&]() { if (kt + 1 < nk) read_frags(na, nb, 0, af0, bp0); }, std::true_type{}, true, kt, sa, sb, 0);
             pa = sa;
             pb = sb;
             sa = na;
             sb = nb;
+        };
+        if constexpr (QGF > 0) {
+            // the restart pattern repeats every PERIOD K steps (lcm(QGF, 4) slices); the dispatcher sends nk % PERIOD == 0 only
+            constexpr int PERIOD = QGF % 4 == 0 ? QGF / 4 : QGF % 2 == 0 ? QGF / 2 : QGF;
+            for (int kt = 0; kt < nk; kt += PERIOD) unrolled_steps(kstep, kt, std::make_integer_sequence<int, PERIOD>{});
+        } else {
+            for (int kt = 0; kt < nk; ++kt) kstep(std::integral_constant<int, 0>{}, kt);
         }
         // the last group's partial sums
 #pragma unroll
@@ -490,7 +511,17 @@ hipError_t launch_qgemm_w4(const GemmArgs &a, hipStream_t stream)
     }
     if (a.acc_out) return run_w4<T, 0, true, true>(a, stream);   // verification: group partial sums exported
     if (glue) return a.group == 128 ? run_w4<T, 4, false, true>(a, stream) : run_w4<T, 0, false, true>(a, stream);
-    return a.group == 128 ? run_w4<T, 4, false, false>(a, stream) : run_w4<T, 0, false, false>(a, stream);
+    // the group set of Algorithm 1 (32, 64, 128, 192, 288) with the restart pattern unrolled, when K holds whole periods of it
+    const int nk = a.K / 128;
+    switch (a.group) {
+    case 32: return run_w4<T, 1, false, false>(a, stream);
+    case 64: return run_w4<T, 2, false, false>(a, stream);
+    case 128: return run_w4<T, 4, false, false>(a, stream);
+    case 192: if (nk % 3 == 0) return run_w4<T, 6, false, false>(a, stream); break;
+    case 288: if (nk % 9 == 0) return run_w4<T, 9, false, false>(a, stream); break;
+    default: break;
+    }
+    return run_w4<T, 0, false, false>(a, stream);
 }
 
 }  // namespace ql

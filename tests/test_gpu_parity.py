@@ -518,6 +518,14 @@ W4G_CASES = [
     (64, 1152, 96, 1, 384),
     (48, 576, 80, 1, 288),        # K % 128 != 0: generic kernel
     (40, 96, 24, 1, 96),
+    # more than 256 rows: the pipelined kernel, whose restart pattern is unrolled for the group set of Algorithm 1
+    (384, 1152, 320, 1, 32),
+    (384, 1152, 320, 1, 64),
+    (300, 2304, 200, 1, 192),     # period of 3 K steps, 6 periods
+    (520, 1152, 136, 4, 288),     # period of 9 K steps = the whole row
+    (300, 4608, 200, 1, 288),     # 4 periods
+    (300, 4608, 200, 1, 64),
+    (300, 1152, 200, 1, 384),     # a group size outside the set: the uniform-branch form
 ]
 
 
