@@ -38,6 +38,26 @@ TRAFFIC_BYTES_PER_LAUNCH = {
 }
 
 
+def mfma_probe():
+    """The benchmark's own measurement aid (bench_mfma_probe.hip, its own shared object beside this file): returns
+    probe(iters, blocks, sink) that enqueues the register-resident MFMA loop on torch's current stream."""
+    import ctypes
+    import torch
+    path = os.path.join(ROOT, "libbench_mfma_probe.so")
+    if not os.path.exists(path):
+        from paper_2511_11446_amd import build as hip_build
+        hip_build.build_bench_probe(verbose=False)
+    fn = ctypes.CDLL(path).bench_mfma_probe
+    fn.restype = ctypes.c_int
+    fn.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+
+    def probe(iters, blocks, sink):
+        rc = fn(iters, blocks, sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        if rc != 0:
+            raise RuntimeError("bench_mfma_probe failed: %d" % rc)
+    return probe
+
+
 def build_layers(ql, torch, wl_name, w4_group=128):
     wl = workload.WORKLOADS[wl_name]
     if wl["layers"] == "bit_plan":
@@ -512,13 +532,15 @@ def main():
         # the matrix cores' own ceiling on this machine: a register-resident MFMA loop, 2 workgroups per CU
         sink = torch.zeros(1, dtype=torch.int32, device="cuda")
         cus = torch.cuda.get_device_properties(0).multi_processor_count
+        probe = mfma_probe()
+        pops = 2.0 * 32 * 32 * 32 * 4 * 4096 * 4 * (2 * cus)
         for _ in range(2):
-            pops = ql.probe_mfma_int8(4096, 2 * cus, sink)
+            probe(4096, 2 * cus, sink)
         torch.cuda.synchronize()
         a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a0.record(stream)
         for _ in range(5):
-            ql.probe_mfma_int8(4096, 2 * cus, sink)
+            probe(4096, 2 * cus, sink)
         a1.record(stream)
         torch.cuda.synchronize()
         mfma_ceiling = 5 * pops / (a0.elapsed_time(a1) * 1e-3) / 1e12

@@ -312,6 +312,14 @@ int ql_pack_w4_host(const int8_t *codes, int64_t N, int64_t K, uint8_t *packed);
  * supported (QL_ERR_UNSUPPORTED). */
 int ql_repack_w4_pairs_host(const uint8_t *pairs, int64_t N, int64_t K, uint8_t *packed);
 
+/* The same re-layout on the device, for weights that arrive in the common pair
+ * order (Step 2 packs the weights offline, once): pairs (device) [N,K/2] bytes,
+ * byte i of a row = k = 2i (low nibble) and k = 2i+1 (high nibble); packed
+ * (device) [N,K/2] bytes in the storage order qlinear_w4a8 reads.  Both buffers
+ * are the caller's, 4-byte aligned, and must not overlap (the same pointer is
+ * QL_ERR_UNSUPPORTED).  K % 8 == 0.  Asynchronous on `stream`. */
+int ql_prepack_w4(const void *pairs, int64_t N, int64_t K, void *packed, void *stream);
+
 /* ------------------------------------------------------------------------
  * Plan runner: Algorithm 2, Phase B (every layer wrapped as its plan entry says,
  * then the forward pass on quantized weights and activations) and Step 6,
@@ -458,16 +466,6 @@ int ql_gptq_quantize_host(const float *W, int64_t N, int64_t K, const double *H,
 int ql_set_gemm_variant(int variant);
 int ql_num_gemm_variants(void);
 const char *ql_gemm_variant_name(int variant);
-
-/* ------------------------------------------------------------------------
- * Measurement aid (Section 6 reports time; this build reports the GEMM rate
- * against the matrix cores' measured ceiling as well as the datasheet peak).
- * Enqueues on `stream` a kernel of `blocks` workgroups x 4 wavefronts, each
- * wavefront issuing 4*iters 32x32x32 INT8 MFMAs on registers only:
- * 2*32*32*32 * 4*iters * 4*blocks operations in all.  sink: device int
- * (4 bytes, never written in practice).  1 <= iters, 1 <= blocks <= 65535.
- * ---------------------------------------------------------------------- */
-int ql_probe_mfma_int8(int iters, int blocks, void *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -21,8 +21,8 @@ EXPORTS = ("ql_status_string", "ql_last_device_error", "ql_version", "daq_worksp
            "qlinear_workspace_bytes", "qlinear_w8a8", "qlinear_w4a8", "qgemm_w8a8", "qgemm_w4a8",
            "ql_pack_w4_host", "ql_plan_create", "ql_plan_destroy", "ql_plan_num_layers",
            "ql_plan_workspace_bytes", "qlinear_plan_run", "ql_set_gemm_variant", "ql_num_gemm_variants",
-           "ql_gemm_variant_name", "ql_probe_mfma_int8", "daq_quantize_robust", "qlinear_plan_run_robust", "ql_time_bin",
-           "qlinear_w4a8_g", "qgemm_w4a8_g", "qlinear_w8a8_fused", "qlinear_w4a8_fused", "qlinear_f16", "ql_repack_w4_pairs_host", "qlinear_plan_run_ex", "qlinear_w8a8_noalloc", "qlinear_noalloc_max_bytes",
+           "ql_gemm_variant_name", "daq_quantize_robust", "qlinear_plan_run_robust", "ql_time_bin",
+           "qlinear_w4a8_g", "qgemm_w4a8_g", "qlinear_w8a8_fused", "qlinear_w4a8_fused", "qlinear_f16", "ql_repack_w4_pairs_host", "ql_prepack_w4", "qlinear_plan_run_ex", "qlinear_w8a8_noalloc", "qlinear_noalloc_max_bytes",
            "ql_schedule_topk", "ql_plan_greedy", "ql_gptq_quantize_host", "daq_quantize_ln",
            "daq_cg_workspace_bytes", "daq_quantize_cg", "qlinear_grouped_workspace_bytes", "qlinear_grouped", "ql_pack_bits_host",
            "ql_unpack_bits_host", "ql_zero_point_fold_host")
@@ -77,8 +77,6 @@ def lib():
     L.ql_status_string.argtypes = [_int]
     L.ql_gemm_variant_name.restype = ctypes.c_char_p
     L.ql_gemm_variant_name.argtypes = [_int]
-    L.ql_probe_mfma_int8.restype = _int
-    L.ql_probe_mfma_int8.argtypes = [_int, _int, _vp, _vp]
     L.daq_workspace_bytes.restype = _sz
     L.daq_workspace_bytes.argtypes = [_i64, _i64, _i64]
     L.qlinear_workspace_bytes.restype = _sz
@@ -109,6 +107,8 @@ def lib():
     L.qlinear_w4a8_fused.restype = _int
     L.ql_repack_w4_pairs_host.argtypes = [_vp, _i64, _i64, _vp]
     L.ql_repack_w4_pairs_host.restype = _int
+    L.ql_prepack_w4.argtypes = [_vp, _i64, _i64, _vp, _vp]
+    L.ql_prepack_w4.restype = _int
     L.qlinear_plan_run_ex.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _i64, _i64, _vp, ctypes.POINTER(ctypes.POINTER(ql_fusion)), _vp, _sz, _vp]
     L.qlinear_plan_run_ex.restype = _int
     L.qlinear_f16.argtypes = [_vp, _i64, _i64, _vp, _vp, _i64, ctypes.POINTER(ql_fusion), _vp, _vp]
@@ -599,10 +599,14 @@ def gemm_variants():
     return [L.ql_gemm_variant_name(i).decode() for i in range(L.ql_num_gemm_variants())]
 
 
-def probe_mfma_int8(iters, blocks, sink, stream=None):
-    """Enqueue the register-resident MFMA loop; returns the number of int8 operations it performs."""
-    _check(lib().ql_probe_mfma_int8(iters, blocks, _ptr(sink), _stream(stream)), "ql_probe_mfma_int8")
-    return 2.0 * 32 * 32 * 32 * 4 * iters * 4 * blocks
+def prepack_w4(pairs, stream=None):
+    """Device uint8 [N,K/2] in pair order (low nibble = even k, high nibble = odd k) -> a new device tensor in the
+    library's 4-bit storage order."""
+    import torch
+    N, K2 = pairs.shape
+    out = torch.empty_like(pairs)
+    _check(lib().ql_prepack_w4(_ptr(pairs), N, K2 * 2, _ptr(out), _stream(stream)), "ql_prepack_w4")
+    return out
 
 
 def ql_repack_w4_pairs_host(pairs):

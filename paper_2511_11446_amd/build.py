@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdiffpro_qlinear.so")
-SOURCES = ["daq.hip", "daq_robust.hip", "daq_ln.hip", "qgemm.hip", "qgemm_w4.hip", "probe.hip", "offline_host.hip", "api.hip"]
+SOURCES = ["daq.hip", "daq_robust.hip", "daq_ln.hip", "qgemm.hip", "qgemm_w4.hip", "offline_host.hip", "api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
@@ -44,5 +44,22 @@ def build(verbose=True):
     return LIB
 
 
+# bench.py's measurement aid (a register-resident MFMA loop): a shared object of its own beside bench.py, not in the library
+PROBE_SRC = os.path.join(os.path.dirname(HERE), "bench_mfma_probe.hip")
+PROBE_LIB = os.path.join(os.path.dirname(HERE), "libbench_mfma_probe.so")
+
+
+def build_bench_probe(verbose=True):
+    tmp = PROBE_LIB + ".tmp%d" % os.getpid()
+    r = subprocess.run([HIPCC, *FLAGS, "-shared", PROBE_SRC, "-o", tmp], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for %s:\n%s" % (PROBE_SRC, r.stdout))
+    os.replace(tmp, PROBE_LIB)
+    if verbose:
+        print("built", PROBE_LIB)
+    return PROBE_LIB
+
+
 if __name__ == "__main__":
     build()
+    build_bench_probe()

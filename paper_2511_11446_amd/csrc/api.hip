@@ -660,6 +660,15 @@ int ql_repack_w4_pairs_host(const uint8_t *pairs, int64_t N, int64_t K, uint8_t 
     return QL_OK;
 }
 
+int ql_prepack_w4(const void *pairs, int64_t N, int64_t K, void *packed, void *stream)
+{
+    if (!pairs || !packed) return QL_ERR_NULL;
+    if (pairs == packed) return QL_ERR_UNSUPPORTED;
+    if (N < 1 || K < 1 || K % 8 != 0 || N * K / 8 > ((int64_t)1 << 31) * 256 - 256) return QL_ERR_SHAPE;
+    if (misaligned(pairs, 4) || misaligned(packed, 4)) return QL_ERR_ALIGN;
+    return device_status(ql::launch_prepack_w4(pairs, packed, N * K / 8, static_cast<hipStream_t>(stream)));
+}
+
 int ql_plan_create(const ql_layer_desc *layers, int32_t n_layers, int64_t M_max, ql_plan **plan_out)
 {
     if (!layers || !plan_out) return QL_ERR_NULL;
@@ -758,13 +767,5 @@ int ql_set_gemm_variant(int variant)
 int ql_num_gemm_variants(void) { return ql::num_gemm_variants(); }
 
 const char *ql_gemm_variant_name(int variant) { return ql::gemm_variant_name(variant); }
-
-int ql_probe_mfma_int8(int iters, int blocks, void *sink, void *stream)
-{
-    if (!sink) return QL_ERR_NULL;
-    if (iters < 1 || blocks < 1 || blocks > 65535) return QL_ERR_SHAPE;
-    if (misaligned(sink, 4)) return QL_ERR_ALIGN;
-    return device_status(ql::launch_mfma_probe(iters, blocks, static_cast<int *>(sink), static_cast<hipStream_t>(stream)));
-}
 
 }  // extern "C"

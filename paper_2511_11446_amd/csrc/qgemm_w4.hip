@@ -524,4 +524,24 @@ hipError_t launch_qgemm_w4(const GemmArgs &a, hipStream_t stream)
     return run_w4<T, 0, false, false>(a, stream);
 }
 
+// Pair order (byte i of a row: k = 2i low nibble, k = 2i+1 high nibble) -> the storage order unpack_w4 reads (byte j of a
+// 4-byte block: k = 8b+j low, k = 8b+4+j high).  One thread per 4-byte block; `blocks` = N*K/8.
+__global__ __launch_bounds__(256) void prepack_w4_pairs(const unsigned *__restrict__ pairs, unsigned *__restrict__ packed, long long blocks)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= blocks) return;
+    const unsigned s = pairs[i];                       // nibble t (bits 4t..4t+3) holds k = 8b+t
+    unsigned d = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) d |= (((s >> (4 * j)) & 0xfu) | (((s >> (4 * (4 + j))) & 0xfu) << 4)) << (8 * j);
+    packed[i] = d;
+}
+
+hipError_t launch_prepack_w4(const void *pairs, void *packed, long long blocks, hipStream_t stream)
+{
+    hipLaunchKernelGGL(prepack_w4_pairs, dim3((unsigned)((blocks + 255) / 256)), dim3(256), 0, stream,
+                       static_cast<const unsigned *>(pairs), static_cast<unsigned *>(packed), blocks);
+    return hipGetLastError();
+}
+
 }  // namespace ql

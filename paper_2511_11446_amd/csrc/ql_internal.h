@@ -91,8 +91,7 @@ hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream);
 // the pipelined 4-bit kernel (qgemm_w4.hip): shapes it takes, and its launch (group 128 or any 32 j, exports, glue)
 bool qgemm_w4_takes(const GemmArgs &a);
 hipError_t launch_qgemm_w4(const GemmArgs &a, hipStream_t stream);
-
-// measurement aid: blocks x 4 wavefronts, each issuing 4 * iters MFMAs (32x32x32 int8) on registers only
-hipError_t launch_mfma_probe(int iters, int blocks, int *sink, hipStream_t stream);
+// pair-order nibbles (device) -> the 4-bit storage order (device); blocks = N*K/8 four-byte blocks
+hipError_t launch_prepack_w4(const void *pairs, void *packed, long long blocks, hipStream_t stream);
 
 }  // namespace ql

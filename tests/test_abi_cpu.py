@@ -247,6 +247,18 @@ def test_repack_from_pair_order_equals_packing_the_codes(orc):
     assert L.ql_repack_w4_pairs_host(None, 5, 64, buf) == 1
 
 
+def test_prepack_w4_argument_checks():
+    """The device-side re-layout validates before any device call (fake, aligned pointers)."""
+    L = ql.lib()
+    a, b = ctypes.c_void_p(0x10000), ctypes.c_void_p(0x20000)
+    assert L.ql_prepack_w4(None, 5, 64, b, None) == 1
+    assert L.ql_prepack_w4(a, 5, 64, None, None) == 1
+    assert L.ql_prepack_w4(a, 5, 64, a, None) == 4                  # in place
+    assert L.ql_prepack_w4(a, 5, 60, b, None) == 2                  # K % 8
+    assert L.ql_prepack_w4(a, 0, 64, b, None) == 2
+    assert L.ql_prepack_w4(ctypes.c_void_p(0x10002), 5, 64, b, None) == 3
+
+
 def test_layernorm_daq_argument_checks():
     L = ql.lib()
     fn = L.daq_quantize_ln

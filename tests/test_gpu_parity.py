@@ -505,6 +505,27 @@ def test_plan_runner_robust_time_bins(gpu, orc):
     plan.close()
 
 
+def test_prepack_w4_from_pair_order_on_the_device(gpu, orc):
+    """Weights that arrive two per byte in pair order (low nibble = even k): the device re-layout gives the bytes the
+    oracle's own packer writes for the same codes, and a layer run on them matches the oracle."""
+    import torch
+    M, K, N, R = 300, 1152, 200, 1
+    say("prepack w4", M, K, N)
+    lw = workload.layer_weights("prepack", K, N, 4, 0)
+    w = lw["w"]
+    pairs = ((w[:, 0::2] & 0xF) | ((w[:, 1::2] & 0xF) << 4)).astype(np.uint8)
+    packed = gpu.prepack_w4(dev(pairs))
+    assert np.array_equal(host(packed), orc.pack_w4(w))
+    x = workload.activations(M, K, "prepack")
+    ref = orc.qlinear_w4a8(x, R, orc.pack_w4(w), lw["s_w"], lw["bias"], nthreads=8, want_debug=False)["y"]
+    y = gpu.qlinear_w4a8(dev(x), R, packed, dev(lw["s_w"]), dev(lw["bias"]))
+    assert assert_y_close(host(y), ref) == 0
+    # a ragged block count (N*K/8 not a multiple of 256) and the smallest row
+    w2 = workload.rng("prepack2").integers(-8, 8, size=(3, 8), dtype=np.int8)
+    p2 = ((w2[:, 0::2] & 0xF) | ((w2[:, 1::2] & 0xF) << 4)).astype(np.uint8)
+    assert np.array_equal(host(gpu.prepack_w4(dev(p2))), orc.pack_w4(w2))
+
+
 # ------------------------------------------------------------------ 4-bit weights with other group sizes
 
 W4G_CASES = [
