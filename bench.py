@@ -386,9 +386,23 @@ def main():
             ql.daq_quantize(h, 1, qb, sb)
 
         t_lnf, t_lns = timed(ln_fused), timed(ln_separate)
+        # fc1's epilogue leaves the row maxima of its output; fc2's DAQ starts from them (one scale per token, and one
+        # per image of `tokens` rows, where the separate DAQ needs a pass of its own to find the maximum)
+        rowmax = torch.zeros((M,), dtype=torch.int32, device="cuda")
+        f1, kf2 = outs["fc1"], by["fc2"]["K"]
+        qf = torch.empty((M, kf2), dtype=torch.int8, device="cuda")
+        sf = torch.empty((M,), dtype=torch.float32, device="cuda")
+        dws = ql.workspace(ql.daq_workspace_bytes(M, kf2, tokens))
+        t_fc1 = timed(lambda: layer("fc1", act=ql.ACT_GELU_TANH))
+        t_fc1_rm = timed(lambda: layer("fc1", act=ql.ACT_GELU_TANH, row_absmax=rowmax))
+        side = {"fc1_gelu_us": t_fc1, "fc1_gelu_with_row_absmax_us": t_fc1_rm}
+        for rr in (1, tokens):
+            side["fc2_daq_R%d_us" % rr] = timed(lambda: ql.daq_quantize(f1, rr, qf, sf, dws))
+            side["fc2_daq_from_row_absmax_R%d_us" % rr] = timed(lambda: ql.daq_quantize_rowmax(f1, rr, rowmax, qf, sf, dws))
         print(json.dumps({"metric": "one block's four linears with GELU and gated residuals", "unit": "us",
                           "fused_epilogues_us": tf, "separate_elementwise_kernels_us": tu, "speedup": tu / tf,
                           "layernorm_modulate_daq_one_kernel_us": t_lnf, "layernorm_modulate_then_daq_us": t_lns,
+                          "row_absmax_side_output": side,
                           "config": {"workload": args.workload, "M": M, "rows_per_scale": R, "tokens_per_gate_row": tokens}}))
         return
 

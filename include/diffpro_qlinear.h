@@ -262,6 +262,12 @@ int ql_zero_point_fold_host(const int8_t *codes, const int32_t *zeros, int64_t N
  * i.e. the result of the unfused sequence layer -> fp16 -> gated residual add.
  *   residual  (device) [M,N] fp16 or NULL;  gate (device) [M/gate_rows, N] fp16 or NULL
  *   gate_rows: rows sharing one gate row (tokens per image); M % gate_rows == 0
+ *   row_absmax (device) [M] uint32 or NULL: side output for the DAQ of the layer
+ *              that consumes y (the MLP's second linear after the first one's
+ *              GELU): entry m receives max_n |y[m,n]| as a binary16 bit pattern
+ *              (for non-negative binary16 numbers the integer order of the
+ *              patterns is the numeric order), taken on the fp16 values written
+ *              to y.  The call clears it first.  daq_quantize_rowmax consumes it.
  * The GELU is evaluated in fp32 on the GPU (relative error about 1e-6 before the
  * fp16 rounding).  fusion == NULL or all-zero gives the plain layer.  group: as in
  * qlinear_w4a8_g.  Errors: QL_ERR_UNSUPPORTED for an unknown act, QL_ERR_SHAPE for
@@ -275,6 +281,7 @@ typedef struct ql_fusion {
     const void *residual;
     const void *gate;
     int64_t gate_rows;
+    void *row_absmax;      /* side output or NULL, see above */
 } ql_fusion;
 
 int qlinear_w8a8_fused(const void *x, int64_t M, int64_t K, int64_t R,
@@ -372,6 +379,16 @@ typedef struct ql_daq_params {
     int32_t p_ppm;
     int32_t a_bits;
 } ql_daq_params;
+
+/* DAQ (Step 3, eq. (4), absolute maximum, 8 bits) of a tensor whose row maxima are
+ * already known: row_absmax (device) [M] uint32, entry m = max_k |x[m,k]| as a
+ * binary16 bit pattern, as the row_absmax side output of the layer that wrote x
+ * leaves it.  The pass over x that finds the maxima is skipped: scales come from
+ * the R row maxima of each scale block and x is read once, by the quantize pass.
+ * Results are those of daq_quantize when row_absmax is right (not checked).
+ * Arguments, workspace (daq_workspace_bytes) and errors as daq_quantize. */
+int daq_quantize_rowmax(const void *x, int64_t M, int64_t K, int64_t R, const void *row_absmax,
+                        void *q, void *scales, void *workspace, size_t workspace_bytes, void *stream);
 
 int daq_quantize_robust(const void *x, int64_t M, int64_t K, int64_t R, const ql_daq_params *params,
                         void *q, void *scales, void *workspace, size_t workspace_bytes, void *stream);

@@ -339,6 +339,15 @@ def layernorm_modulate(x, shift=None, scale=None, rows_per_mod=1, eps=1e-6):
     return (n * g + b).astype(np.float32).astype(np.float16)
 
 
+def row_absmax_bits(y):
+    """The statistic a layer may leave for the DAQ of the layer that consumes its output (Step 3, eq. (4): tau is the
+    largest magnitude of the scale block): per row of the fp16 matrix y, max_n |y[m,n]| as a binary16 bit pattern
+    (uint32 [M]).  Written as the definition: magnitudes as numbers, the largest one, then its bit pattern."""
+    y = np.asarray(y, dtype=np.float16)
+    mag = np.abs(y.astype(np.float64)).max(axis=1)
+    return mag.astype(np.float16).view(np.uint16).astype(np.uint32)
+
+
 def gemm_i8g(q, w, group, nthreads=1):
     """int8 codes q [M,K] x int8 weight codes w [N,K] (any width up to 8 bits held as int8) -> int32 [M, K/group, N]."""
     q = _c(q, np.int8)

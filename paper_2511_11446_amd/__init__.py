@@ -22,7 +22,7 @@ EXPORTS = ("ql_status_string", "ql_last_device_error", "ql_version", "daq_worksp
            "ql_pack_w4_host", "ql_plan_create", "ql_plan_destroy", "ql_plan_num_layers",
            "ql_plan_workspace_bytes", "qlinear_plan_run", "ql_set_gemm_variant", "ql_num_gemm_variants",
            "ql_gemm_variant_name", "daq_quantize_robust", "qlinear_plan_run_robust", "ql_time_bin",
-           "qlinear_w4a8_g", "qgemm_w4a8_g", "qlinear_w8a8_fused", "qlinear_w4a8_fused", "qlinear_f16", "ql_repack_w4_pairs_host", "ql_prepack_w4", "qlinear_plan_run_ex", "qlinear_w8a8_noalloc", "qlinear_noalloc_max_bytes",
+           "qlinear_w4a8_g", "qgemm_w4a8_g", "qlinear_w8a8_fused", "qlinear_w4a8_fused", "qlinear_f16", "ql_repack_w4_pairs_host", "ql_prepack_w4", "daq_quantize_rowmax", "qlinear_plan_run_ex", "qlinear_w8a8_noalloc", "qlinear_noalloc_max_bytes",
            "ql_schedule_topk", "ql_plan_greedy", "ql_gptq_quantize_host", "daq_quantize_ln",
            "daq_cg_workspace_bytes", "daq_quantize_cg", "qlinear_grouped_workspace_bytes", "qlinear_grouped", "ql_pack_bits_host",
            "ql_unpack_bits_host", "ql_zero_point_fold_host")
@@ -109,6 +109,8 @@ def lib():
     L.ql_repack_w4_pairs_host.restype = _int
     L.ql_prepack_w4.argtypes = [_vp, _i64, _i64, _vp, _vp]
     L.ql_prepack_w4.restype = _int
+    L.daq_quantize_rowmax.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
+    L.daq_quantize_rowmax.restype = _int
     L.qlinear_plan_run_ex.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _i64, _i64, _vp, ctypes.POINTER(ctypes.POINTER(ql_fusion)), _vp, _sz, _vp]
     L.qlinear_plan_run_ex.restype = _int
     L.qlinear_f16.argtypes = [_vp, _i64, _i64, _vp, _vp, _i64, ctypes.POINTER(ql_fusion), _vp, _vp]
@@ -181,6 +183,24 @@ def daq_quantize(x, R, q=None, scales=None, ws=None, stream=None):
     rc = lib().daq_quantize(_ptr(x), M, K, R, _ptr(q), _ptr(scales), _ptr(ws), 0 if ws is None else ws.numel(),
                             _stream(stream))
     _check(rc, "daq_quantize")
+    return q, scales
+
+
+def daq_quantize_rowmax(x, R, row_absmax, q=None, scales=None, ws=None, stream=None):
+    """DAQ with the row maxima given (int32 [M], binary16 bit patterns, as a fused layer's row_absmax output leaves them)."""
+    import torch
+    _need(x, torch.float16, name="x")
+    M, K = x.shape
+    _need(row_absmax, torch.int32, (M,), "row_absmax")
+    if q is None:
+        q = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    if scales is None:
+        scales = torch.empty((max(M // max(R, 1), 1),), dtype=torch.float32, device=x.device)
+    if ws is None and R > 1:
+        ws = workspace(daq_workspace_bytes(M, K, R), x.device)
+    rc = lib().daq_quantize_rowmax(_ptr(x), M, K, R, _ptr(row_absmax), _ptr(q), _ptr(scales), _ptr(ws),
+                                   0 if ws is None else ws.numel(), _stream(stream))
+    _check(rc, "daq_quantize_rowmax")
     return q, scales
 
 
@@ -280,16 +300,17 @@ def zero_point_fold_host(codes, zeros, group):
 
 class ql_fusion(ctypes.Structure):
     _fields_ = [("act", ctypes.c_int32), ("reserved", ctypes.c_int32), ("residual", ctypes.c_void_p),
-                ("gate", ctypes.c_void_p), ("gate_rows", ctypes.c_int64)]
+                ("gate", ctypes.c_void_p), ("gate_rows", ctypes.c_int64), ("row_absmax", ctypes.c_void_p)]
 
 
 ACT_NONE, ACT_GELU_TANH = 0, 1
 
 
 def qlinear_fused(x, R, w, w_scale, bias=None, bits=8, group=128, act=ACT_NONE, residual=None, gate=None, gate_rows=1,
-                  y=None, ws=None, stream=None):
+                  y=None, ws=None, stream=None, row_absmax=None):
     """The layer with activation, gate and residual folded into its epilogue:
-    h = fp16(act(u)); y = fp16(fma(gate, h, residual)).  bits = 8 (w int8 [N,K]) or 4 (w packed [N,K/2], group)."""
+    h = fp16(act(u)); y = fp16(fma(gate, h, residual)).  bits = 8 (w int8 [N,K]) or 4 (w packed [N,K/2], group).
+    row_absmax: int32 [M] device tensor that receives every row's largest |y| as a binary16 bit pattern, or None."""
     import torch
     _need(x, torch.float16, name="x")
     M, K = x.shape
@@ -302,7 +323,10 @@ def qlinear_fused(x, R, w, w_scale, bias=None, bits=8, group=128, act=ACT_NONE, 
         y = torch.empty((M, N), dtype=torch.float16, device=x.device)
     if ws is None:
         ws = workspace(qlinear_workspace_bytes(M, K, R), x.device)
-    fu = ql_fusion(act, 0, None if residual is None else residual.data_ptr(), None if gate is None else gate.data_ptr(), gate_rows)
+    if row_absmax is not None:
+        _need(row_absmax, torch.int32, (M,), "row_absmax")
+    fu = ql_fusion(act, 0, None if residual is None else residual.data_ptr(), None if gate is None else gate.data_ptr(), gate_rows,
+                   None if row_absmax is None else row_absmax.data_ptr())
     if bits == 8:
         rc = lib().qlinear_w8a8_fused(_ptr(x), M, K, R, _ptr(w), _ptr(w_scale), _ptr(bias), N, ctypes.byref(fu), _ptr(y),
                                       _ptr(ws), ws.numel(), _stream(stream))
@@ -313,7 +337,7 @@ def qlinear_fused(x, R, w, w_scale, bias=None, bits=8, group=128, act=ACT_NONE, 
     return y
 
 
-def qlinear_f16(x, w, bias=None, act=ACT_NONE, residual=None, gate=None, gate_rows=1, y=None, stream=None):
+def qlinear_f16(x, w, bias=None, act=ACT_NONE, residual=None, gate=None, gate_rows=1, y=None, stream=None, row_absmax=None):
     """A layer left in FP16: x fp16 [M,K], w fp16 [N,K] -> y fp16 [M,N] (fp32 accumulation)."""
     import torch
     _need(x, torch.float16, name="x")
@@ -322,7 +346,8 @@ def qlinear_f16(x, w, bias=None, act=ACT_NONE, residual=None, gate=None, gate_ro
     N = w.shape[0]
     if y is None:
         y = torch.empty((M, N), dtype=torch.float16, device=x.device)
-    fu = ql_fusion(act, 0, None if residual is None else residual.data_ptr(), None if gate is None else gate.data_ptr(), gate_rows)
+    fu = ql_fusion(act, 0, None if residual is None else residual.data_ptr(), None if gate is None else gate.data_ptr(), gate_rows,
+                   None if row_absmax is None else row_absmax.data_ptr())
     _check(lib().qlinear_f16(_ptr(x), M, K, _ptr(w), _ptr(bias), N, ctypes.byref(fu), _ptr(y), _stream(stream)), "qlinear_f16")
     return y
 
@@ -506,7 +531,8 @@ class Plan:
                 if f is None:
                     continue
                 fu = ql_fusion(f.get("act", 0), 0, None if f.get("residual") is None else f["residual"].data_ptr(),
-                               None if f.get("gate") is None else f["gate"].data_ptr(), f.get("gate_rows", 1))
+                               None if f.get("gate") is None else f["gate"].data_ptr(), f.get("gate_rows", 1),
+                               None if f.get("row_absmax") is None else f["row_absmax"].data_ptr())
                 keep.append(fu)
                 arr[i] = ctypes.pointer(fu)
             fus = arr

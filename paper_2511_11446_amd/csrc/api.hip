@@ -124,6 +124,11 @@ int run_layer(const void *x, int64_t M, int64_t K, int64_t R, int w_bits, const 
             g.residual = fu->residual;
             g.gate = fu->gate;
             g.gate_rows = (int)fu->gate_rows;
+            g.row_absmax = static_cast<unsigned *>(fu->row_absmax);
+        }
+        if (g.row_absmax) {
+            const int rc = device_status(ql::launch_fill_u32(g.row_absmax, (int)M, 0u, stream));
+            if (rc) return rc;
         }
         return device_status(ql::launch_qgemm(g, g_gemm_variant.load(), stream));
     }
@@ -167,6 +172,11 @@ int run_layer(const void *x, int64_t M, int64_t K, int64_t R, int w_bits, const 
         g.residual = fu->residual;
         g.gate = fu->gate;
         g.gate_rows = (int)fu->gate_rows;
+        g.row_absmax = static_cast<unsigned *>(fu->row_absmax);
+    }
+    if (g.row_absmax) {
+        rc = device_status(ql::launch_fill_u32(g.row_absmax, (int)M, 0u, stream));
+        if (rc) return rc;
     }
     return device_status(ql::launch_qgemm(g, g_gemm_variant.load(), stream));
 }
@@ -196,7 +206,7 @@ int check_fusion(const ql_fusion *fu, int64_t M)
 {
     if (!fu) return QL_OK;
     if (fu->act != QL_ACT_NONE && fu->act != QL_ACT_GELU_TANH) return QL_ERR_UNSUPPORTED;
-    if (misaligned(fu->residual, 2) || misaligned(fu->gate, 2)) return QL_ERR_ALIGN;
+    if (misaligned(fu->residual, 2) || misaligned(fu->gate, 2) || misaligned(fu->row_absmax, 4)) return QL_ERR_ALIGN;
     if (fu->gate && (fu->gate_rows < 1 || M % fu->gate_rows != 0)) return QL_ERR_SHAPE;
     return QL_OK;
 }
@@ -335,6 +345,26 @@ int daq_quantize_robust(const void *x, int64_t M, int64_t K, int64_t R, const ql
 {
     if (!params) return QL_ERR_NULL;
     return daq_any(x, M, K, R, params, q, scales, workspace, workspace_bytes, stream);
+}
+
+int daq_quantize_rowmax(const void *x, int64_t M, int64_t K, int64_t R, const void *row_absmax, void *q, void *scales,
+                        void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!x || !q || !scales || !row_absmax) return QL_ERR_NULL;
+    if (misaligned(x, 2) || misaligned(scales, 4) || misaligned(row_absmax, 4)) return QL_ERR_ALIGN;
+    int rc = check_shape(M, K, R, 1);
+    if (rc) return rc;
+    rc = check_workspace(workspace, workspace_bytes, daq_workspace_bytes(M, K, R));
+    if (rc) return rc;
+    ql::DaqArgs d{};
+    d.x = x;
+    d.q = static_cast<int8_t *>(q);
+    d.scales = static_cast<float *>(scales);
+    d.blockmax = R > 1 ? static_cast<unsigned *>(workspace) : nullptr;
+    d.M = (int)M;
+    d.K = (int)K;
+    d.R = (int)R;
+    return device_status(ql::launch_daq_from_rowmax(d, static_cast<const unsigned *>(row_absmax), static_cast<hipStream_t>(stream)));
 }
 
 // ---- plan-space generality: channel-group activation scales, int8-held codes of any width with group scales ----------

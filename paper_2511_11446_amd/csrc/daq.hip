@@ -311,4 +311,27 @@ hipError_t launch_daq(const DaqArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
+hipError_t launch_fill_u32(unsigned *p, int n, unsigned v, hipStream_t stream)
+{
+    hipLaunchKernelGGL(fill_u32, dim3((n + 255) / 256), dim3(256), 0, stream, p, n, v);
+    return hipGetLastError();
+}
+
+// The first pass is already done: the producing layer's epilogue left every row's maximum.  A block's R row maxima are
+// laid out like the partial maxima of the two-pass modes, so the quantize pass reduces them itself (R <= 256) or after
+// one reduction launch.
+hipError_t launch_daq_from_rowmax(const DaqArgs &a, const unsigned *row_absmax, hipStream_t stream)
+{
+    DaqArgs q = a;
+    q.partmax = const_cast<unsigned *>(row_absmax);
+    if (a.R <= 256) {
+        q.quant_parts = a.R;
+    } else {
+        hipLaunchKernelGGL(daq_reduce_parts, dim3(a.M / a.R), dim3(256), 0, stream, row_absmax, (unsigned)a.R, a.blockmax);
+        q.quant_parts = 0;
+    }
+    run_rows(q, DAQ_QUANT, stream);
+    return hipGetLastError();
+}
+
 }  // namespace ql

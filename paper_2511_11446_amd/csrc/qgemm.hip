@@ -673,6 +673,7 @@ __global__ __launch_bounds__(T::NT, T::WPS) void qgemm_dma(GemmArgs a, int tiles
             gl.gate_rows = a.gate_rows;
             gl.on = true;
         }
+        if (GLUE) gl.rowmax = a.row_absmax;
         unsigned char *strip = smem + T::EPI_OFF + T::STRIP_OFF + wave * T::STRIP_BYTES;
         // the 16 row scales of each 32-row block of this lane (rows 8g + 4*frag_half + 0..3), read once as 4 x 16 bytes
         float sr[TM * 16];
@@ -1028,7 +1029,7 @@ hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream)
 {
     if (a.w_grouped || a.s_ag) {
         // plan-space generality: the pipelined grouped kernel where it takes the shape, else one thread per element
-        if (variant < NUM_VARIANTS && qgemm_w4_takes(a) && !(a.act != 0 || a.residual != nullptr || a.gate != nullptr))
+        if (variant < NUM_VARIANTS && qgemm_w4_takes(a) && !(a.act != 0 || a.residual != nullptr || a.gate != nullptr || a.row_absmax != nullptr))
             return launch_qgemm_w4(a, stream);
         hipLaunchKernelGGL(qgemm_naive, dim3((a.M + 3) / 4, (a.N + 63) / 64), dim3(256), 0, stream, a);
         return hipGetLastError();
@@ -1051,7 +1052,7 @@ hipError_t launch_qgemm(const GemmArgs &a, int variant, hipStream_t stream)
         if (a.K > 128 * 40 && __builtin_strncmp(VARIANTS[v].name, "w4 dma", 6) == 0)
             v = find_variant("w4 128x64 bk128 4w occ3");
     }
-    if (a.act != 0 || a.residual != nullptr || a.gate != nullptr) {
+    if (a.act != 0 || a.residual != nullptr || a.gate != nullptr || a.row_absmax != nullptr) {
         // block glue in the epilogue: only the shape-chosen tiles carry it
         if (!VARIANTS[v].run_glue) v = choose_variant(a);
         // the prefetched gate and residual pieces need registers the persistent tiles do not have left

@@ -39,7 +39,7 @@ __device__ __forceinline__ float gelu_tanh_dev(float u)
     return u * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * z));
 }
 
-__device__ __forceinline__ bool has_glue(const GemmArgs &a) { return a.act != 0 || a.residual != nullptr || a.gate != nullptr; }
+__device__ __forceinline__ bool has_glue(const GemmArgs &a) { return a.act != 0 || a.residual != nullptr || a.gate != nullptr || a.row_absmax != nullptr; }
 
 // Gate row of tile row d (0 <= d < span) without a division per element: the tile starts at row m_first, whose gate
 // row and remainder are computed once; rows of a tile cross at most one gate boundary when gate_rows >= span.
@@ -69,6 +69,8 @@ __device__ __forceinline__ _Float16 glue_one(const GemmArgs &a, float u, int m, 
         asm volatile("" : "+v"(v));
         h = (_Float16)v;
     }
+    // side output for the next layer's DAQ: the row's largest |y| as a binary16 bit pattern (integer order = numeric order)
+    if (a.row_absmax) atomicMax(a.row_absmax + m, (unsigned)(__builtin_bit_cast(unsigned short, h) & 0x7fffu));
     return h;
 }
 
@@ -78,6 +80,7 @@ struct GluePieces {
     const _Float16 *gate = nullptr, *residual = nullptr;
     int gate_rows = 1;
     bool on = false;
+    unsigned *rowmax = nullptr;   // side output: largest |y| of every row (binary16 bit patterns), or nullptr
 };
 
 // eight neighbouring elements of one row at once (16-byte pieces of the staged tile); g and r were loaded ahead
@@ -161,6 +164,10 @@ __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane
                         *reinterpret_cast<unsigned __attribute__((may_alias)) *>(y + (g_off + (unsigned)((i * 32 + row) * N + j * 32))) = word;
                 }
             if (STAGED) {
+                // row maxima of the block: collected in the 4 spare bytes after every strip row (LDS operations of one
+                // wavefront complete in program order), then one global atomic per row
+                typedef __attribute__((address_space(3))) unsigned lds_u32;
+                if (glue.rowmax && lane < ROWS) *reinterpret_cast<unsigned __attribute__((may_alias)) *>(strip + lane * PITCH + TN * 64) = 0u;
                 asm volatile("" ::: "memory");  // the strip reads below see other lanes' writes: keep program order
 #pragma unroll
                 for (int t = 0; t < ROWS * CH / 64; ++t) {
@@ -169,10 +176,26 @@ __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane
                     v4i v = *reinterpret_cast<const v4i_alias *>(strip + row * PITCH + ch * 16);
                     // gate and residual meet the fp16 result here, eight elements of a row at a time
                     if (glue.on) v = glue_piece(glue.gate != nullptr, glue.residual != nullptr, v, pg[t], pr[t]);
+                    if (glue.rowmax) {
+                        unsigned mx = 0;
+#pragma unroll
+                        for (int w = 0; w < 4; ++w) {
+                            const unsigned t2 = (unsigned)v[w] & 0x7fff7fffu;
+                            const unsigned lo = t2 & 0xffffu, hi = t2 >> 16;
+                            mx = mx > lo ? mx : lo;
+                            mx = mx > hi ? mx : hi;
+                        }
+                        __hip_atomic_fetch_max((lds_u32 *)(strip + row * PITCH + TN * 64), mx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    }
                     // the output is written once and not read again by this kernel: keep it from displacing the operand panels in L2
                     __builtin_nontemporal_store(v, reinterpret_cast<v4i_alias *>(y + (unsigned)((m_base + i * 32 + h * ROWS + row) * N + n_base + ch * 8)));
                 }
                 asm volatile("" ::: "memory");
+                if (glue.rowmax && lane < ROWS) {
+                    const unsigned mx = *reinterpret_cast<const unsigned __attribute__((may_alias)) *>(strip + lane * PITCH + TN * 64);
+                    if (mx) atomicMax(glue.rowmax + (m_base + i * 32 + h * ROWS + lane), mx);
+                    asm volatile("" ::: "memory");
+                }
             }
         }
     }

@@ -409,6 +409,7 @@ __global__ __launch_bounds__(T::NT, 2) void qgemm_w4(GemmArgs a, int tiles_m, in
                 gl.gate_rows = a.gate_rows;
                 gl.on = true;
             }
+            if (GLUE) gl.rowmax = a.row_absmax;
             unsigned char *strip = smem + T::EPI_OFF + T::STRIP_OFF + wave * T::STRIP_BYTES;
             // the 16 row scales of each 32-row block of this lane (rows 8g + 4*frag_half + 0..3), read once as 4 x 16 bytes
             float sr[TM * 16];
@@ -502,7 +503,7 @@ bool qgemm_w4_takes(const GemmArgs &a)
 hipError_t launch_qgemm_w4(const GemmArgs &a, hipStream_t stream)
 {
     using T = TileW4<2, 3, 2>;
-    const bool glue = a.act != 0 || a.residual != nullptr || a.gate != nullptr;
+    const bool glue = a.act != 0 || a.residual != nullptr || a.gate != nullptr || a.row_absmax != nullptr;
     if (a.w_grouped) {
         // int8 codes with group scales: one workgroup per CU (the weight ring is twice as large)
         using T8 = TileW4<2, 3, 2, true>;

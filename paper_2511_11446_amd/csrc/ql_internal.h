@@ -43,6 +43,9 @@ inline size_t daq_parts_per_block(int64_t K, int64_t R)
 hipError_t launch_daq(const DaqArgs &a, hipStream_t stream);
 // eq. (4) with channel groups: scales [M/R, K/cg], blockmax workspace of the same count; K % 8 == 0, cg % 8 == 0, K/cg <= 1024
 hipError_t launch_daq_cg(const DaqArgs &a, int cg, hipStream_t stream);
+// DAQ whose row maxima are already known (row_absmax [M], binary16 bit patterns): scales and the quantize pass only
+hipError_t launch_daq_from_rowmax(const DaqArgs &a, const unsigned *row_absmax, hipStream_t stream);
+hipError_t launch_fill_u32(unsigned *p, int n, unsigned v, hipStream_t stream);
 // eq. (4) with tau = a percentile of the magnitudes and a selectable code width
 hipError_t launch_daq_robust(const DaqArgs &a, hipStream_t stream);
 
@@ -81,6 +84,8 @@ struct GemmArgs {
                           //    [N,K/group] like the 4-bit layers (w_bits stays 8)
     const float *s_ag;    // activation scales per (scale block, channel group) [M/R, K/group] instead of s_a; the channel
                           //    groups are the weight groups
+    unsigned *row_absmax; // optional side output [M] (cleared by the caller of the launch): the largest |y[m,:]| as a binary16
+                          //    bit pattern, taken on the fp16 values the layer writes (what the next layer's DAQ would find)
 };
 
 int num_gemm_variants();

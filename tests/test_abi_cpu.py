@@ -247,6 +247,17 @@ def test_repack_from_pair_order_equals_packing_the_codes(orc):
     assert L.ql_repack_w4_pairs_host(None, 5, 64, buf) == 1
 
 
+def test_daq_quantize_rowmax_argument_checks():
+    L = ql.lib()
+    x, rm, q, sc, ws = (ctypes.c_void_p(v) for v in (0x10000, 0x20000, 0x30000, 0x40000, 0x50000))
+    assert L.daq_quantize_rowmax(x, 64, 128, 1, None, q, sc, None, 0, None) == 1          # no row maxima
+    assert L.daq_quantize_rowmax(x, 64, 128, 1, ctypes.c_void_p(0x20002), q, sc, None, 0, None) == 3
+    assert L.daq_quantize_rowmax(x, 64, 128, 5, rm, q, sc, ws, 1 << 20, None) == 2        # M % R
+    assert L.daq_quantize_rowmax(x, 64, 128, 32, rm, q, sc, None, 0, None) == 5           # workspace for R > 1
+    fu = ql.ql_fusion(0, 0, None, None, 1, 0x1002)                                        # misaligned side output
+    assert L.qlinear_w8a8_fused(x, 64, 128, 1, rm, sc, None, 64, ctypes.byref(fu), q, ws, 1 << 20, None) == 3
+
+
 def test_prepack_w4_argument_checks():
     """The device-side re-layout validates before any device call (fake, aligned pointers)."""
     L = ql.lib()

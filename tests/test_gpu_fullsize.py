@@ -162,6 +162,28 @@ def test_c4_per_sample_m16384_every_element(gpu, orc, name, K, N):
     free()
 
 
+def test_row_absmax_side_output_m16384(gpu, orc):
+    """fc1 (4-bit, GELU) at full size with the row-maximum side output, then fc2's DAQ from it with one scale per token
+    and one per image of 1024 tokens: every row maximum, scale and code against the oracle applied to the y written."""
+    import torch
+    M, K, N = M_FULL, 1152, 4608
+    say("full rowmax", M, K, N)
+    x = workload.activations(M, K, "fullrm", sigma=0.8)
+    lw = workload.layer_weights("fc1", K, N, 4, "fullrm")
+    rowmax = torch.empty((M,), dtype=torch.int32, device="cuda")
+    y = gpu.qlinear_fused(dev(x), 1, dev(gpu.ql_pack_w4_host(lw["w"])), dev(lw["s_w"]), dev(lw["bias"]), bits=4, group=128,
+                          act=gpu.ACT_GELU_TANH, row_absmax=rowmax)
+    yh = host(y)
+    assert np.array_equal(host(rowmax).astype(np.uint32), orc.row_absmax_bits(yh))
+    for R in (1, 1024):
+        q_ref, s_ref = orc.daq(yh, R, nthreads=16)
+        q, s = gpu.daq_quantize_rowmax(y, R, rowmax)
+        assert np.array_equal(host(s).view(np.uint32), s_ref.view(np.uint32)), R
+        assert np.array_equal(host(q), q_ref), R
+        del q, s
+    free()
+
+
 def test_c5_plan_every_layer_on_tile_row_bands(gpu, orc):
     """The 112-layer stack under the seeded bit plan at full size, through qlinear_plan_run: EVERY layer is checked on
     two whole bands of 256 consecutive rows (all columns; the first and a late tile row of the walk) plus 40 scattered rows."""

@@ -678,6 +678,52 @@ def test_fused_epilogue(gpu, orc, M, K, N, R, bits, group, act, use_res, gate_ro
     assert ndiff <= max(4, y.numel() // 500)              # and such elements are rare
 
 
+ROWMAX_CASES = [
+    # M, K, N, bits, group, act, residual+gate
+    (512, 1152, 384, 8, 0, 1, False),       # fc1-like: GELU, staged epilogue (the row maxima pass through the LDS strip)
+    (512, 1152, 384, 8, 0, 0, True),        # gated residual: the maximum is taken after the addition
+    (300, 1152, 200, 8, 0, 1, False),       # ragged: element-wise epilogue, one atomic per element
+    (384, 1152, 320, 4, 128, 1, False),     # the pipelined 4-bit kernel
+    (384, 1152, 320, 4, 288, 0, False),     # no glue at all, only the side output
+    (4096, 1152, 1152, 8, 0, 1, False),     # 256x192 tiles on eight wavefronts
+    (64, 200, 48, 8, 0, 1, True),           # generic kernel
+    (384, 1152, 256, 16, 0, 1, False),      # a layer left in FP16
+]
+
+
+@pytest.mark.parametrize("M,K,N,bits,group,act,use_rg", ROWMAX_CASES)
+def test_row_absmax_side_output_and_daq_from_it(gpu, orc, M, K, N, bits, group, act, use_rg):
+    """The epilogue's side output (largest |y| of every row as a binary16 bit pattern) against the oracle's definition
+    applied to the y the same call wrote, and the DAQ that starts from it against the oracle's DAQ of that y: scales and
+    codes bit for bit, at one row, a few rows and more than 256 rows per scale."""
+    import torch
+    say("rowmax", M, K, N, bits, group, act, use_rg)
+    x = workload.activations(M, K, "rowmax", N, bits)
+    g = workload.rng("rowmax-rg", M, N)
+    residual = dev((g.standard_normal((M, N), dtype=np.float32) * 2).astype(np.float16)) if use_rg else None
+    gate = dev(g.standard_normal((M // 32, N), dtype=np.float32).astype(np.float16)) if use_rg else None
+    rowmax = torch.full((M,), 0x7fffffff, dtype=torch.int32, device="cuda")       # the call clears it
+    if bits == 16:
+        w = workload.f16_weights(N, K, "rowmax")
+        y = gpu.qlinear_f16(dev(x), dev(w), dev(workload.bias(N, "rowmax")), act=act, residual=residual, gate=gate, gate_rows=32,
+                            row_absmax=rowmax)
+    else:
+        lw = workload.layer_weights("rowmax", K, N, bits, "rowmax")
+        if bits == 4 and group != 128:
+            lw = dict(lw, s_w=workload.w4_scales_group(N, K, group, "rowmax"))
+        w = dev(lw["w"]) if bits == 8 else dev(gpu.ql_pack_w4_host(lw["w"]))
+        y = gpu.qlinear_fused(dev(x), 1, w, dev(lw["s_w"]), dev(lw["bias"]), bits=bits, group=group or 128, act=act,
+                              residual=residual, gate=gate, gate_rows=32, row_absmax=rowmax)
+    yh = host(y)
+    assert np.isfinite(yh.astype(np.float32)).all()
+    assert np.array_equal(host(rowmax).astype(np.uint32), orc.row_absmax_bits(yh))
+    for R in (1, 4, M) if M % 4 == 0 else (1, M):
+        q_ref, s_ref = orc.daq(yh, R)
+        q, s = gpu.daq_quantize_rowmax(y, R, rowmax)
+        assert np.array_equal(host(s).view(np.uint32), s_ref.view(np.uint32)), R
+        assert np.array_equal(host(q), q_ref), R
+
+
 def test_fused_epilogue_with_nothing_to_fuse_is_the_plain_layer_and_misaligned_glue_still_works(gpu, orc):
     import torch
     M, K, N = 256, 1152, 256

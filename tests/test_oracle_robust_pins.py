@@ -401,3 +401,15 @@ def test_dense_bit_storage(orc):
         c = g.integers(-(1 << (b - 1)), 1 << (b - 1), (5, 64), dtype=np.int8)
         p = orc.pack_bits(c, b)
         assert p.shape == (5, 64 * b // 8) and np.array_equal(orc.unpack_bits(p, b, 64), c)
+
+
+def test_row_absmax_bits_hand_values_and_its_use_as_the_daq_threshold(orc):
+    """Pins: literal bit patterns (0x3c00 = 1, 0x4248 = 3.140625, 0x0001 = the smallest subnormal, 0x7bff = 65504), sign
+    ignored, zero row -> 0; and alpha = fp16(bits) / 127 is the scale orc.daq finds for that row on its own."""
+    y = np.array([[0.5, -1.0, 0.25], [3.140625, -3.0, 0.0], [0.0, -0.0, 0.0], [6e-8, 0.0, -0.0], [-65504.0, 1.0, 2.0]], dtype=np.float16)
+    assert orc.row_absmax_bits(y).tolist() == [0x3c00, 0x4248, 0, 0x0001, 0x7bff]
+    g = workload.rng("rowmax-pin")
+    x = (g.standard_normal((40, 64)) * 3).astype(np.float16)
+    bits = orc.row_absmax_bits(x)
+    _, s = orc.daq(x, 1)
+    assert np.array_equal(s, (bits.astype(np.uint16).view(np.float16).astype(np.float32) / np.float32(127.0)))
