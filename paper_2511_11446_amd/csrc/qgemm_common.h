@@ -33,10 +33,13 @@ __device__ __forceinline__ float half_to_float_dev(unsigned short h)
 // ---- block glue folded into the epilogue: h = f16(act(u)); y = f16(fma(g, h, r)) -----------------------------------
 // GELU in its tanh form, written with the logistic function: u * sigmoid(2 z), z = sqrt(2/pi) (u + 0.044715 u^3).
 // This keeps the relative accuracy in the negative tail, where 1 + tanh z cancels.
+// exp(-2z) = 2^(u (k0 + k1 u^2)) with k0 = -2 sqrt(2/pi) log2(e), k1 = 0.044715 k0: five plain operations and two
+// transcendental ones per element (the epilogue's ALU work is not hidden behind the MFMAs).
 __device__ __forceinline__ float gelu_tanh_dev(float u)
 {
-    const float z = 0.7978845608028654f * (u + 0.044715f * u * u * u);
-    return u * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * z));
+    const float k0 = -2.302208198f, k1 = -0.1029432396f;
+    const float e = u * __builtin_fmaf(k1, u * u, k0);
+    return u * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(e));
 }
 
 __device__ __forceinline__ bool has_glue(const GemmArgs &a) { return a.act != 0 || a.residual != nullptr || a.gate != nullptr || a.row_absmax != nullptr; }
@@ -177,14 +180,12 @@ __device__ __forceinline__ void store_tile_staged(unsigned char *strip, int lane
                     // gate and residual meet the fp16 result here, eight elements of a row at a time
                     if (glue.on) v = glue_piece(glue.gate != nullptr, glue.residual != nullptr, v, pg[t], pr[t]);
                     if (glue.rowmax) {
-                        unsigned mx = 0;
+                        // packed 16-bit maxima of the magnitudes' bit patterns, then the larger half
+                        typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+                        us2 pm = __builtin_bit_cast(us2, (unsigned)v[0] & 0x7fff7fffu);
 #pragma unroll
-                        for (int w = 0; w < 4; ++w) {
-                            const unsigned t2 = (unsigned)v[w] & 0x7fff7fffu;
-                            const unsigned lo = t2 & 0xffffu, hi = t2 >> 16;
-                            mx = mx > lo ? mx : lo;
-                            mx = mx > hi ? mx : hi;
-                        }
+                        for (int w = 1; w < 4; ++w) pm = __builtin_elementwise_max(pm, __builtin_bit_cast(us2, (unsigned)v[w] & 0x7fff7fffu));
+                        const unsigned mx = pm[0] > pm[1] ? pm[0] : pm[1];
                         __hip_atomic_fetch_max((lds_u32 *)(strip + row * PITCH + TN * 64), mx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     }
                     // the output is written once and not read again by this kernel: keep it from displacing the operand panels in L2
