@@ -32,9 +32,9 @@ POOL = 4                  # distinct activation sets rotated over the steps (dif
 # under profiles/ is named beside each figure.  Keyed by (workload, forced variant, 4-bit group); absent = not measured.
 TRAFFIC_BYTES_PER_LAUNCH = {
     # (2 x FETCH_SIZE + WRITE_SIZE) KiB -> bytes, mean over the launches of the workload's dominant GEMM kernel in a step
-    ("c5_stack_plan_m16384", -1, 128): (176651223, "profiles/qgemm_daq_c5_stack_m16384_hbm_traffic.txt (qgemm_w4, 74 launches per step)"),
-    ("c4_block_w8a8_m16384", -1, 128): (211029744, "profiles/qgemm_daq_c4_block_m16384_hbm_traffic.txt (qgemm_dma, 4 launches per step)"),
-    ("c2_block_w8a8_m2048", -1, 128): (38185062, "profiles/qgemm_daq_c2_block_m2048_hbm_traffic.txt (qgemm_dma, 4 launches per step)"),
+    ("c5_stack_plan_m16384", -1, 128): (176468597, "profiles/qgemm_daq_c5_stack_m16384_hbm_traffic.txt (qgemm_w4, 74 launches per step)"),
+    ("c4_block_w8a8_m16384", -1, 128): (211073875, "profiles/qgemm_daq_c4_block_m16384_hbm_traffic.txt (qgemm_dma, 4 launches per step)"),
+    ("c2_block_w8a8_m2048", -1, 128): (37098200, "profiles/qgemm_daq_c2_block_m2048_hbm_traffic.txt (qgemm_dma, 4 launches per step)"),
 }
 
 
