@@ -26,7 +26,8 @@ typedef __attribute__((address_space(3))) void lds_void_w4;
 
 // WGM_: wavefront rows of the workgroup (2: 128x128 tile, 4: 256x128); SA_/SB_: ring depths of the two operands
 // B8_: the weight operand is int8 codes (128 bytes per row and K step) instead of packed nibbles
-template <int WGM_, int SA_, int SB_, bool B8_ = false>
+// MAXG_: weight groups along K whose scales the tile keeps in LDS (40: two workgroups per CU; more: one)
+template <int WGM_, int SA_, int SB_, bool B8_ = false, int MAXG_ = 40>
 struct TileW4 {
     static constexpr bool B8 = B8_;
     static constexpr int TM = 2, TN = 2, WGM = WGM_, WGN = 2;
@@ -46,7 +47,7 @@ struct TileW4 {
     static constexpr int STRIP_BYTES = 32 * (TN * 64 + 16);
     static constexpr int EPI_BYTES = STRIP_OFF + NW * STRIP_BYTES;
     // group scales of the tile's columns, [column][group] fp16 as in global memory
-    static constexpr int MAX_GROUPS = 40;
+    static constexpr int MAX_GROUPS = MAXG_;
     static constexpr int SCALE_OFF = RINGS;
     static constexpr int LDS_BYTES = RINGS + BN * MAX_GROUPS * 2;
     static constexpr int SMAX = SA > SB ? SA : SB;
@@ -490,13 +491,16 @@ static hipError_t run_w4(const GemmArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+// more than 40 groups (K = 4608 with groups of 32 or 64): a table of up to 144 groups, one workgroup per CU
+constexpr int W4_MANY_GROUPS = 144;
+
 bool qgemm_w4_takes(const GemmArgs &a)
 {
     if (a.s_ag && (a.R % 128 != 0 || a.M % a.R != 0)) return false;   // channel-group activation scales: tiles inside one scale block
     if (a.w_grouped)
         return a.w_bits == 8 && a.K % 128 == 0 && a.group % 32 == 0 && a.K % a.group == 0 && a.K / a.group <= TileW4<2, 3, 2>::MAX_GROUPS &&
                (uintptr_t)a.q % 16 == 0 && (uintptr_t)a.w % 16 == 0;
-    return a.w_bits == 4 && a.K % 128 == 0 && a.group % 32 == 0 && a.K % a.group == 0 && a.K / a.group <= TileW4<2, 3, 2>::MAX_GROUPS &&
+    return a.w_bits == 4 && a.K % 128 == 0 && a.group % 32 == 0 && a.K % a.group == 0 && a.K / a.group <= W4_MANY_GROUPS &&
            (uintptr_t)a.q % 16 == 0 && (uintptr_t)a.w % 16 == 0;
 }
 
@@ -509,6 +513,14 @@ hipError_t launch_qgemm_w4(const GemmArgs &a, hipStream_t stream)
         using T8 = TileW4<2, 3, 2, true>;
         if (glue) return hipErrorInvalidValue;
         return a.acc_out ? run_w4<T8, 0, true, false>(a, stream) : run_w4<T8, 0, false, false>(a, stream);
+    }
+    if (a.K / a.group > T::MAX_GROUPS) {
+        using TG = TileW4<2, 3, 2, false, W4_MANY_GROUPS>;
+        if (a.acc_out) return run_w4<TG, 0, true, true>(a, stream);
+        if (glue) return run_w4<TG, 0, false, true>(a, stream);
+        if (a.group == 32) return run_w4<TG, 1, false, false>(a, stream);
+        if (a.group == 64) return run_w4<TG, 2, false, false>(a, stream);
+        return run_w4<TG, 0, false, false>(a, stream);
     }
     if (a.acc_out) return run_w4<T, 0, true, true>(a, stream);   // verification: group partial sums exported
     if (glue) return a.group == 128 ? run_w4<T, 4, false, true>(a, stream) : run_w4<T, 0, false, true>(a, stream);

@@ -77,9 +77,10 @@ def test_w8a8_m16384_every_element(gpu, orc, name, K, N):
 
 @pytest.mark.parametrize("name,K,N,group", [("fc1", 1152, 4608, 128), ("fc2", 4608, 1152, 128),
                                             ("fc1", 1152, 4608, 288), ("fc2", 4608, 1152, 288),
-                                            ("proj", 1152, 1152, 32)])
+                                            ("proj", 1152, 1152, 32), ("fc2", 4608, 1152, 64)])
 def test_w4a8_m16384_every_element(gpu, orc, name, K, N, group):
-    """4-bit layers with weight groups of 128, 288 and 32: every group partial sum and every output."""
+    """4-bit layers with weight groups of 128, 288, 32 and (72 groups along K: the large scale table, one workgroup per CU)
+    64: every group partial sum and every output."""
     M, R = M_FULL, 1
     say("full W4", name, M, K, N, "group", group)
     x = workload.activations(M, K, "full4", name, sigma=0.6)

@@ -545,7 +545,8 @@ W4G_CASES = [
     (300, 2304, 200, 1, 192),     # period of 3 K steps, 6 periods
     (520, 1152, 136, 4, 288),     # period of 9 K steps = the whole row
     (300, 4608, 200, 1, 288),     # 4 periods
-    (300, 4608, 200, 1, 64),
+    (300, 4608, 200, 1, 64),      # 72 groups: the table of up to 144 groups, one workgroup per CU
+    (300, 4608, 136, 1, 32),      # 144 groups
     (300, 1152, 200, 1, 384),     # a group size outside the set: the uniform-branch form
 ]
 
