@@ -778,12 +778,13 @@ static hipError_t run_dma(const GemmArgs &a, hipStream_t s)
         // as many workgroups as the chip holds at once (LDS decides), a multiple of the XCD count
         static const int resident = [] {
             int dev = 0, cus = 0;
-            if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-                cus = 256;   // MI355X
+            if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+                cus < XCDS)
+                return 0;   // no guess: the launch fails instead
             const int per_cu = 160 * 1024 / T::LDS_BYTES > 0 ? 160 * 1024 / T::LDS_BYTES : 1;
-            const int r = cus / XCDS * XCDS * per_cu;
-            return r < XCDS ? XCDS : r;
+            return cus / XCDS * XCDS * per_cu;
         }();
+        if (resident <= 0) return hipErrorInvalidDevice;
         if (grid > resident) grid = resident;
     }
     hipLaunchKernelGGL((qgemm_dma<T, GLUE>), dim3(grid), dim3(T::NT), T::LDS_BYTES, s, a, tiles_m, tiles_n, padded, pick_group_m(T::BM));

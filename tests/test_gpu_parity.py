@@ -643,8 +643,8 @@ GLUE_CASES = [
     (64, 200, 48, 1, 8, 0, 1, True, 32),          # generic kernel (K % 64 != 0)
     (256, 1152, 256, 1, 4, 128, 1, True, 256),    # 4-bit weights
     (256, 1152, 192, 1, 4, 288, 0, True, 128),    # 4-bit, group 288
-    (4096, 1152, 1152, 1, 8, 0, 0, True, 1024),   # persistent 128x192 tiles
-    (4096, 1152, 3456, 1, 8, 0, 1, False, 0),     # persistent 128x128 tiles
+    (4096, 1152, 1152, 1, 8, 0, 0, True, 1024),   # a shape of the persistent walk: with glue it runs on 256x192 tiles, eight wavefronts
+    (4096, 1152, 3456, 1, 8, 0, 1, False, 0),     # the same for a wide layer, GELU only
     (256, 4608, 384, 256, 8, 0, 0, True, 256),    # K = 4608, per-sample scales
 ]
 
