@@ -227,8 +227,9 @@ int qgemm_w4a8_g(const void *q, const void *a_scales, int64_t M, int64_t K, int6
  *                       f = fma(float(P), c, f);  y = fp16(f + bias[n])
  *   (other act_group values: QL_ERR_UNSUPPORTED.)  w_scale fp16 [N,K/group];
  *   dbg->a_scales is [M/R] or [M/R, K/group]; dbg->acc [M, K/group, N].
- * The pipelined kernel takes K % 128 == 0, K/group <= 40 and, with channel-group
- * activation scales, R % 128 == 0; other shapes run on the generic kernel.
+ * The pipelined kernel takes K % 128 == 0, K/group <= 40 (4-bit storage: <= 144)
+ * and, with channel-group activation scales, R % 128 == 0; other shapes run on
+ * the generic kernel.
  * Workspace: qlinear_grouped_workspace_bytes().
  *
  * Host helpers: ql_pack_bits_host / ql_unpack_bits_host store b-bit two's-
