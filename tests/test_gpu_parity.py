@@ -646,6 +646,8 @@ GLUE_CASES = [
     (4096, 1152, 1152, 1, 8, 0, 0, True, 1024),   # a shape of the persistent walk: with glue it runs on 256x192 tiles, eight wavefronts
     (4096, 1152, 3456, 1, 8, 0, 1, False, 0),     # the same for a wide layer, GELU only
     (256, 4608, 384, 256, 8, 0, 0, True, 256),    # K = 4608, per-sample scales
+    (384, 4608, 256, 1, 4, 64, 1, True, 128),     # 4-bit, 72 groups along K: the pipelined kernel with the large scale table, with glue
+    (384, 1152, 256, 1, 4, 128, 1, True, 128),    # 4-bit group 128 above 256 rows: the pipelined kernel's glue build
 ]
 
 
