@@ -122,31 +122,34 @@ __global__ __launch_bounds__(256) void daq_rows_robust(DaqArgs a, int mode)
             return wave_sum_u32((cnt & 0xffffu) + (cnt >> 16));
         };
         unsigned T = 0;
-        if (a.top_rank <= 4) {
+        if (a.top_rank <= 8) {
             // tau is among the few largest values (the paper's p = 99.9 %: the 2nd largest of 1152, the 5th of 4608):
-            // walk down the distinct magnitudes from the top, one per pass, until top_rank values lie at or above
-            unsigned prev = 0x8000u;   // above every magnitude
-            for (unsigned pass = 0; pass < a.top_rank; ++pass) {
+            // walk down the distinct magnitudes from the top.  One sweep over the registers finds the next magnitude
+            // below `prev` and, with the same comparison, counts the values at or above `prev`; the walk ends at the
+            // first magnitude with top_rank values at or above it (after at most top_rank + 1 sweeps).
+            unsigned prev = 0x8000u;   // above every magnitude: nothing lies at or above it
+            for (unsigned pass = 0; pass <= a.top_rank; ++pass) {
                 const unsigned p2 = prev * 0x00010001u;
-                unsigned m2 = 0;
-                auto below = [&](unsigned w) {
+                unsigned m2 = 0, cnt = 0;
+                auto sweep = [&](unsigned w) {
                     const unsigned mag = w & 0x7fff7fffu;
-                    const unsigned ge = ((mag | 0x80008000u) - p2) >> 15;          // bit 0 / 16: magnitude >= prev
-                    return mag & ((~ge & 0x00010001u) * 0xffffu);                   // keep the halves below prev
+                    const unsigned ge = (((mag | 0x80008000u) - p2) >> 15) & 0x00010001u;   // bit 0 / 16: magnitude >= prev
+                    cnt += ge;
+                    m2 = absmax_word(m2, mag & ((ge ^ 0x00010001u) * 0xffffu));              // the halves below prev
                 };
 #pragma unroll
                 for (int i = 0; i < CH; ++i) {
-                    m2 = absmax_word(m2, below(v[i].x));
-                    m2 = absmax_word(m2, below(v[i].y));
-                    m2 = absmax_word(m2, below(v[i].z));
-                    m2 = absmax_word(m2, below(v[i].w));
+                    sweep(v[i].x);
+                    sweep(v[i].y);
+                    sweep(v[i].z);
+                    sweep(v[i].w);
+                }
+                if (pass > 0 && wave_sum_u32((cnt & 0xffffu) + (cnt >> 16)) >= a.top_rank) {
+                    T = prev;
+                    break;
                 }
                 const unsigned m = wave_max_u32((m2 & 0xffffu) > (m2 >> 16) ? (m2 & 0xffffu) : (m2 >> 16));
                 if (m == 0) break;                      // everything left is zero: tau = 0
-                if (count_ge(m) >= a.top_rank) {
-                    T = m;
-                    break;
-                }
                 prev = m;
             }
         } else {
